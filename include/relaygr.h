@@ -1,0 +1,200 @@
+/*
+ * relaygr.h -- C ABI of the relay-race ranking hot path on one MI355X (gfx950).
+ *
+ * The paper (arXiv 2601.01712) splits ranking-model inference for a user with a
+ * long behaviour history in two (Section 2.3, the relay-race identity; Section
+ * 3.1, "Cache object"; Section 3.2, "Concurrency inside a special instance"):
+ *
+ *   pre-infer   run the backbone over the long-term prefix alone and leave psi,
+ *               the per-layer K/V of that prefix, in HBM under the user's id;
+ *   rank        later, look psi up by user id and run only the incremental
+ *               tokens (short-term suffix, candidates) against it; if psi is
+ *               absent, fall back to full inference (Section 3.1, invariant I1;
+ *               Section 3.3).
+ *
+ * This library is that instance-side path: an HBM pool of psi objects, prefix
+ * pre-inference into the pool, ranking with the cached prefix, and full
+ * recompute.  The model is an HSTU-style backbone with a scalar score head; per
+ * user the sequence is [prefix p_0..p_{L-1} | suffix s_0..s_{S-1} | candidates
+ * c_0..c_{M-1}] and token i may attend to key j iff j <= i and j is not another
+ * candidate.  Per layer:
+ *
+ *     xh = LN(x; g_in, b_in)                      [u|v|q|k] = SiLU(xh W1^T + b1)
+ *     o_i^h = (1/n_i) sum_j m_ij SiLU(<q_i^h,k_j^h>/sqrt(d_head)) v_j^h
+ *     x  <- x + (LN(o; g_at, b_at) * u) W2^T + b2
+ *     score_c = <w_s, LN(x_c; g_out, b_out)> + b_s        (candidate rows, after the last layer)
+ *
+ * with n_i the number of keys row i may see, LN the LayerNorm with biased
+ * variance and SiLU(t) = t / (1 + exp(-t)).
+ *
+ * Conventions
+ *   - Plain C types only.  "device" pointers are HIP device addresses on the
+ *     current device; "host" pointers are ordinary process memory.
+ *   - The caller owns every device buffer (weights, embeddings, the pool slab,
+ *     the scratch buffer, the score output).  The library allocates no device
+ *     memory; it owns host-side metadata and a small pinned staging area.
+ *   - Compute calls enqueue work on the given HIP stream and return without
+ *     synchronising.  Buffers passed to a call must stay valid and unmodified
+ *     until that stream has passed the call's work.  A context must not be used
+ *     from two streams at once (its scratch buffer is shared by its calls).
+ *   - Every function returning int returns RELAYGR_OK or a negative code; the
+ *     text of the last failure on the calling thread is relaygr_last_error().
+ *   - dtype selects storage AND arithmetic: RELAYGR_DTYPE_FP32 keeps everything
+ *     in fp32; RELAYGR_DTYPE_BF16 stores weights, embeddings, activations and
+ *     cached K/V as bfloat16 and accumulates, normalises and keeps the residual
+ *     stream in fp32.  Scores are always fp32.
+ *   - Constraints checked at context creation: d_model a multiple of 64 and at
+ *     most 1024; d_head = d_model / n_heads in {32, 64, 128}.
+ */
+#ifndef RELAYGR_H
+#define RELAYGR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RELAYGR_OK       0
+#define RELAYGR_EINVAL  (-1)  /* null pointer, bad shape, offsets not monotone, unsupported config */
+#define RELAYGR_ENOSPC  (-2)  /* pool has no free extent of the needed size / scratch too small  */
+#define RELAYGR_ENOENT  (-3)  /* unknown user id, or stale / freed handle                        */
+#define RELAYGR_EHIP    (-4)  /* a HIP runtime call failed; see relaygr_last_error()             */
+
+#define RELAYGR_DTYPE_FP32 0
+#define RELAYGR_DTYPE_BF16 1
+
+#define RELAYGR_TILE_TOKENS 64   /* cached K/V are laid out in tiles of 64 tokens */
+
+typedef struct relaygr_ctx     relaygr_ctx;      /* model view + scratch plan (opaque)         */
+typedef struct relaygr_kv_pool relaygr_kv_pool;  /* extent allocator over a caller slab (opaque) */
+
+/* Handle of one user's psi in a pool: (generation << 32) | (slot + 1).  0 means "no cache". */
+typedef uint64_t relaygr_kv_handle;
+#define RELAYGR_NO_CACHE ((relaygr_kv_handle)0)
+
+typedef struct {
+  int32_t n_layers;
+  int32_t d_model;
+  int32_t n_heads;
+  int32_t dtype;     /* RELAYGR_DTYPE_* */
+  float   ln_eps;    /* LayerNorm epsilon, e.g. 1e-5 */
+} relaygr_model_config;
+
+/* One layer's parameters, all DEVICE pointers in the storage dtype.
+ * w1 is [4*d_model, d_model] row-major, output-major (y = x W1^T + b1), its output rows
+ * ordered u | v | q | k (four blocks of d_model).  w2 is [d_model, d_model], output-major. */
+typedef struct {
+  const void *ln_in_g, *ln_in_b;   /* [d_model] */
+  const void *w1, *b1;             /* [4d, d], [4d] */
+  const void *ln_at_g, *ln_at_b;   /* [d_model] */
+  const void *w2, *b2;             /* [d, d], [d] */
+} relaygr_layer_weights;
+
+typedef struct {
+  const relaygr_layer_weights* layers;  /* HOST array of n_layers entries (copied at create) */
+  const void *ln_out_g, *ln_out_b;      /* device [d_model] */
+  const void *w_score;                  /* device [d_model] */
+  float b_score;
+} relaygr_weights;
+
+/* One jagged batch of users.  Offsets are HOST int32 arrays of n_users + 1 monotone entries
+ * starting at 0; embeddings are DEVICE arrays [rows, d_model] in the storage dtype, users
+ * concatenated in order.  A segment a call does not need may be null with null offsets
+ * (treated as all-empty). */
+typedef struct {
+  int32_t n_users;
+  const uint64_t* user_ids;            /* host [n_users]; informational (may be null) */
+  const relaygr_kv_handle* handles;    /* host [n_users]; see each call */
+  const void* prefix_emb; const int32_t* prefix_off;   /* [sum L, d] */
+  const void* suffix_emb; const int32_t* suffix_off;   /* [sum S, d] */
+  const void* cand_emb;   const int32_t* cand_off;     /* [sum M, d] */
+} relaygr_batch;
+
+/* ---- sizes -------------------------------------------------------------------------- */
+
+/* Exact bytes of psi for one user: 2 (K and V) * n_layers * prefix_len * d_model * element size
+ * (Section 5.1 "Cache semantics": 2K tokens, 8 layers, d 256, fp32 -> 32 MB).  0 on bad input. */
+size_t relaygr_kv_footprint_bytes(const relaygr_model_config* cfg, int32_t prefix_len);
+
+/* Bytes the same psi occupies in a pool whose pages hold page_tokens tokens (page-rounded). */
+size_t relaygr_kv_pool_bytes_for(const relaygr_model_config* cfg, int32_t prefix_len, int32_t page_tokens);
+
+/* Scratch bytes a context needs so that any single call may carry up to max_users users,
+ * max_prefix_tokens prefix tokens that must be COMPUTED in that call (prefill, full recompute,
+ * uncached users) and max_new_tokens suffix + candidate tokens.  0 on bad input. */
+size_t relaygr_scratch_bytes(const relaygr_model_config* cfg, int32_t max_users,
+                             int64_t max_prefix_tokens, int64_t max_new_tokens);
+
+/* ---- context ------------------------------------------------------------------------ */
+
+/* Binds a model (config + device weights) to a caller-owned device scratch buffer of
+ * scratch_bytes (256-byte aligned).  Weight memory is referenced, not copied. */
+int  relaygr_ctx_create(const relaygr_model_config* cfg, const relaygr_weights* weights,
+                        void* scratch_dev, size_t scratch_bytes, relaygr_ctx** out);
+void relaygr_ctx_destroy(relaygr_ctx* ctx);
+
+/* ---- HBM pool of psi objects (Section 3.3, "HBM as a lifecycle window") -------------- */
+
+/* Creates an allocator over slab_dev (device, 256-byte aligned, slab_bytes long) for models of
+ * shape cfg.  A page holds page_tokens tokens (a multiple of 64) of every layer's K and V:
+ * 2 * n_layers * page_tokens * d_model * element size bytes.  A user's psi is one contiguous
+ * extent of pages.  The pool never evicts: when no extent fits, alloc says RELAYGR_ENOSPC and the
+ * caller frees consumed entries or ranks that user by full recompute (invariant I2). */
+int  relaygr_kv_pool_create(const relaygr_model_config* cfg, void* slab_dev, size_t slab_bytes,
+                            int32_t page_tokens, relaygr_kv_pool** out);
+void relaygr_kv_pool_destroy(relaygr_kv_pool* pool);
+
+/* Reserves space for a prefix of prefix_len >= 1 tokens under user_id and returns its handle.
+ * A user id holds at most one live entry: allocating again for a live id is RELAYGR_EINVAL.
+ * The entry's contents are undefined until relaygr_prefill_prefix has run for it. */
+int  relaygr_kv_pool_alloc(relaygr_kv_pool* pool, uint64_t user_id, int32_t prefix_len,
+                           relaygr_kv_handle* out);
+/* Releases an entry.  RELAYGR_ENOENT if the handle is stale or was never issued.  The caller
+ * must not free an entry that enqueued work still reads. */
+int  relaygr_kv_pool_free(relaygr_kv_pool* pool, relaygr_kv_handle handle);
+/* Finds the live entry of user_id.  RELAYGR_ENOENT (and *out = RELAYGR_NO_CACHE) if there is none:
+ * the caller then ranks that user without a cache. */
+int  relaygr_kv_pool_lookup(relaygr_kv_pool* pool, uint64_t user_id, relaygr_kv_handle* out);
+/* prefix_len of a live handle into *prefix_len; RELAYGR_ENOENT if stale. */
+int  relaygr_kv_pool_entry_len(relaygr_kv_pool* pool, relaygr_kv_handle handle, int32_t* prefix_len);
+/* Pool occupancy: total pages, free pages, live entries, largest free extent in pages. */
+int  relaygr_kv_pool_stats(relaygr_kv_pool* pool, int64_t* pages_total, int64_t* pages_free,
+                           int64_t* live_entries, int64_t* largest_free_extent);
+/* Where one cached element lives, in ELEMENTS from the start of the slab: K of (layer, token,
+ * feature) at *k_index; V of the same at *v_index.  For inspection and tests. */
+int  relaygr_kv_pool_locate(relaygr_kv_pool* pool, relaygr_kv_handle handle, int32_t layer,
+                            int32_t token, int32_t feature, int64_t* k_index, int64_t* v_index);
+
+/* ---- compute (Section 3.2: the instance dispatches on the request's stage) ------------ */
+
+/* stage = pre-infer.  For every user of the batch: run the backbone over prefix_emb rows of that
+ * user and write every layer's K and V into the pool entry handles[u], whose length must equal
+ * the user's prefix length.  Suffix and candidate segments are ignored.  No output besides the
+ * pool contents.  RELAYGR_ENOENT if a handle is stale, RELAYGR_ENOSPC if scratch is too small. */
+int  relaygr_prefill_prefix(relaygr_ctx* ctx, relaygr_kv_pool* pool, const relaygr_batch* batch,
+                            void* hip_stream);
+
+/* stage = rank.  Scores every candidate of every user into scores_dev (device float32
+ * [sum M], candidate order, users concatenated by cand_off).  A user with a live handle runs only
+ * its suffix and candidate tokens against the cached prefix (prefix_emb rows of that user are not
+ * read, but prefix_off must still give the prefix length, which must equal the entry's).  A user
+ * whose handle is RELAYGR_NO_CACHE is recomputed in the same call from prefix_emb (the paper's
+ * miss fallback); pool may be null if every handle is RELAYGR_NO_CACHE.  A stale handle is
+ * RELAYGR_ENOENT and nothing is enqueued: the caller retries with RELAYGR_NO_CACHE for that user. */
+int  relaygr_rank_with_cache(relaygr_ctx* ctx, relaygr_kv_pool* pool, const relaygr_batch* batch,
+                             float* scores_dev, void* hip_stream);
+
+/* Baseline: full inference inline for every user (Section 5.1 "Baselines"); handles are ignored
+ * and no pool is touched.  Same output as relaygr_rank_with_cache. */
+int  relaygr_rank_full_recompute(relaygr_ctx* ctx, const relaygr_batch* batch,
+                                 float* scores_dev, void* hip_stream);
+
+/* Text of the calling thread's last failure ("" if none).  Valid until the thread's next call. */
+const char* relaygr_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RELAYGR_H */

@@ -1,0 +1,316 @@
+"""ctypes binding of librelaygr.so: argument marshalling only.
+
+Every function named relaygr_* below forwards to the C entry point of the same
+name (include/relaygr.h).  PyTorch supplies device memory and the current HIP
+stream; no step of the path runs in Python or in PyTorch ops.  If the library
+is missing it is built once with hipcc; if that fails the import fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import build as _build
+
+RELAYGR_OK, RELAYGR_EINVAL, RELAYGR_ENOSPC, RELAYGR_ENOENT, RELAYGR_EHIP = 0, -1, -2, -3, -4
+RELAYGR_DTYPE_FP32, RELAYGR_DTYPE_BF16 = 0, 1
+RELAYGR_NO_CACHE = 0
+RELAYGR_TILE_TOKENS = 64
+
+EXPORTS = [
+    "relaygr_kv_footprint_bytes", "relaygr_kv_pool_bytes_for", "relaygr_scratch_bytes",
+    "relaygr_ctx_create", "relaygr_ctx_destroy",
+    "relaygr_kv_pool_create", "relaygr_kv_pool_destroy", "relaygr_kv_pool_alloc", "relaygr_kv_pool_free",
+    "relaygr_kv_pool_lookup", "relaygr_kv_pool_entry_len", "relaygr_kv_pool_stats", "relaygr_kv_pool_locate",
+    "relaygr_prefill_prefix", "relaygr_rank_with_cache", "relaygr_rank_full_recompute",
+    "relaygr_last_error",
+]
+
+
+class ModelConfigC(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32),
+                ("dtype", C.c_int32), ("ln_eps", C.c_float)]
+
+
+class LayerWeightsC(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in
+                ("ln_in_g", "ln_in_b", "w1", "b1", "ln_at_g", "ln_at_b", "w2", "b2")]
+
+
+class WeightsC(C.Structure):
+    _fields_ = [("layers", C.POINTER(LayerWeightsC)), ("ln_out_g", C.c_void_p), ("ln_out_b", C.c_void_p),
+                ("w_score", C.c_void_p), ("b_score", C.c_float)]
+
+
+class BatchC(C.Structure):
+    _fields_ = [("n_users", C.c_int32),
+                ("user_ids", C.POINTER(C.c_uint64)),
+                ("handles", C.POINTER(C.c_uint64)),
+                ("prefix_emb", C.c_void_p), ("prefix_off", C.POINTER(C.c_int32)),
+                ("suffix_emb", C.c_void_p), ("suffix_off", C.POINTER(C.c_int32)),
+                ("cand_emb", C.c_void_p), ("cand_off", C.POINTER(C.c_int32))]
+
+
+class RelayGRError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"relaygr error {code}: {message}")
+        self.code = code
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Loads librelaygr.so from the package directory (building it first if it is absent)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build()
+    lib = C.CDLL(_build.LIB)
+    vp, i32, i64, u64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_size_t
+    P = C.POINTER
+    sig = {
+        "relaygr_kv_footprint_bytes": (sz, [P(ModelConfigC), i32]),
+        "relaygr_kv_pool_bytes_for": (sz, [P(ModelConfigC), i32, i32]),
+        "relaygr_scratch_bytes": (sz, [P(ModelConfigC), i32, i64, i64]),
+        "relaygr_ctx_create": (C.c_int, [P(ModelConfigC), P(WeightsC), vp, sz, P(vp)]),
+        "relaygr_ctx_destroy": (None, [vp]),
+        "relaygr_kv_pool_create": (C.c_int, [P(ModelConfigC), vp, sz, i32, P(vp)]),
+        "relaygr_kv_pool_destroy": (None, [vp]),
+        "relaygr_kv_pool_alloc": (C.c_int, [vp, u64, i32, P(u64)]),
+        "relaygr_kv_pool_free": (C.c_int, [vp, u64]),
+        "relaygr_kv_pool_lookup": (C.c_int, [vp, u64, P(u64)]),
+        "relaygr_kv_pool_entry_len": (C.c_int, [vp, u64, P(i32)]),
+        "relaygr_kv_pool_stats": (C.c_int, [vp, P(i64), P(i64), P(i64), P(i64)]),
+        "relaygr_kv_pool_locate": (C.c_int, [vp, u64, i32, i32, i32, P(i64), P(i64)]),
+        "relaygr_prefill_prefix": (C.c_int, [vp, vp, P(BatchC), vp]),
+        "relaygr_rank_with_cache": (C.c_int, [vp, vp, P(BatchC), vp, vp]),
+        "relaygr_rank_full_recompute": (C.c_int, [vp, P(BatchC), vp, vp]),
+        "relaygr_last_error": (C.c_char_p, []),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)   # AttributeError here means the library lacks a declared symbol
+        fn.restype = res
+        fn.argtypes = args
+    _lib = lib
+    return lib
+
+
+def _check(rc: int) -> None:
+    if rc != RELAYGR_OK:
+        raise RelayGRError(rc, load_library().relaygr_last_error().decode("utf-8", "replace"))
+
+
+def relaygr_last_error() -> str:
+    return load_library().relaygr_last_error().decode("utf-8", "replace")
+
+
+def _dtype_code(dtype: str) -> int:
+    return {"fp32": RELAYGR_DTYPE_FP32, "bf16": RELAYGR_DTYPE_BF16}[dtype]
+
+
+def _torch_dtype(dtype: str):
+    return {"fp32": torch.float32, "bf16": torch.bfloat16}[dtype]
+
+
+def make_config(n_layers: int, d_model: int, n_heads: int, dtype: str, ln_eps: float = 1e-5) -> ModelConfigC:
+    return ModelConfigC(n_layers, d_model, n_heads, _dtype_code(dtype), ln_eps)
+
+
+def relaygr_kv_footprint_bytes(cfg: ModelConfigC, prefix_len: int) -> int:
+    return load_library().relaygr_kv_footprint_bytes(C.byref(cfg), prefix_len)
+
+
+def relaygr_kv_pool_bytes_for(cfg: ModelConfigC, prefix_len: int, page_tokens: int) -> int:
+    return load_library().relaygr_kv_pool_bytes_for(C.byref(cfg), prefix_len, page_tokens)
+
+
+def relaygr_scratch_bytes(cfg: ModelConfigC, max_users: int, max_prefix_tokens: int, max_new_tokens: int) -> int:
+    return load_library().relaygr_scratch_bytes(C.byref(cfg), max_users, max_prefix_tokens, max_new_tokens)
+
+
+def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+class Context:
+    """relaygr_ctx plus the device tensors it references (weights, scratch)."""
+
+    def __init__(self, model_cfg, weights: dict, max_users: int, max_prefix_tokens: int, max_new_tokens: int,
+                 device: str = "cuda:0"):
+        lib = load_library()
+        self.dtype = model_cfg.dtype
+        self.cfg = make_config(model_cfg.n_layers, model_cfg.d_model, model_cfg.n_heads, model_cfg.dtype, model_cfg.ln_eps)
+        td = _torch_dtype(self.dtype)
+        self.device = torch.device(device)
+        self._keep = []
+
+        def dev(a):
+            t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(self.device).to(td).contiguous()
+            self._keep.append(t)
+            return t.data_ptr()
+
+        layers = (LayerWeightsC * model_cfg.n_layers)()
+        for l, lw in enumerate(weights["layers"]):
+            for name, _ in LayerWeightsC._fields_:
+                setattr(layers[l], name, dev(lw[name]))
+        self._layers = layers
+        wc = WeightsC(layers, dev(weights["ln_out_g"]), dev(weights["ln_out_b"]), dev(weights["w_score"]),
+                      float(weights["b_score"]))
+        nbytes = relaygr_scratch_bytes(self.cfg, max_users, max_prefix_tokens, max_new_tokens)
+        if nbytes == 0:
+            raise RelayGRError(RELAYGR_EINVAL, "relaygr_scratch_bytes rejected the configuration")
+        self.scratch = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.scratch_bytes = nbytes
+        h = C.c_void_p()
+        _check(lib.relaygr_ctx_create(C.byref(self.cfg), C.byref(wc), self.scratch.data_ptr(), nbytes, C.byref(h)))
+        self.handle = h
+
+    def close(self):
+        if getattr(self, "handle", None):
+            torch.cuda.synchronize(self.device)
+            load_library().relaygr_ctx_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class KvPool:
+    """relaygr_kv_pool over a torch-allocated device slab."""
+
+    def __init__(self, cfg: ModelConfigC, dtype: str, slab_bytes: int, page_tokens: int = 256, device: str = "cuda:0"):
+        lib = load_library()
+        self.cfg = cfg
+        self.dtype = dtype
+        self.device = torch.device(device)
+        self.slab = torch.empty(slab_bytes, dtype=torch.uint8, device=self.device)
+        h = C.c_void_p()
+        _check(lib.relaygr_kv_pool_create(C.byref(cfg), self.slab.data_ptr(), slab_bytes, page_tokens, C.byref(h)))
+        self.handle = h
+
+    def elements(self) -> torch.Tensor:
+        """The slab viewed in the storage dtype (for inspection with relaygr_kv_pool_locate)."""
+        return self.slab.view(_torch_dtype(self.dtype))
+
+    def close(self):
+        if getattr(self, "handle", None):
+            load_library().relaygr_kv_pool_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def relaygr_kv_pool_alloc(pool: KvPool, user_id: int, prefix_len: int) -> int:
+    out = C.c_uint64(0)
+    _check(load_library().relaygr_kv_pool_alloc(pool.handle, user_id, prefix_len, C.byref(out)))
+    return out.value
+
+
+def relaygr_kv_pool_free(pool: KvPool, handle: int) -> None:
+    _check(load_library().relaygr_kv_pool_free(pool.handle, handle))
+
+
+def relaygr_kv_pool_lookup(pool: KvPool, user_id: int) -> int:
+    """Handle of the user's live entry, or RELAYGR_NO_CACHE if there is none."""
+    out = C.c_uint64(0)
+    rc = load_library().relaygr_kv_pool_lookup(pool.handle, user_id, C.byref(out))
+    if rc == RELAYGR_ENOENT:
+        return RELAYGR_NO_CACHE
+    _check(rc)
+    return out.value
+
+
+def relaygr_kv_pool_entry_len(pool: KvPool, handle: int) -> int:
+    out = C.c_int32(0)
+    _check(load_library().relaygr_kv_pool_entry_len(pool.handle, handle, C.byref(out)))
+    return out.value
+
+
+def relaygr_kv_pool_stats(pool: KvPool) -> dict:
+    a, b, c, d = C.c_int64(), C.c_int64(), C.c_int64(), C.c_int64()
+    _check(load_library().relaygr_kv_pool_stats(pool.handle, C.byref(a), C.byref(b), C.byref(c), C.byref(d)))
+    return {"pages_total": a.value, "pages_free": b.value, "live_entries": c.value, "largest_free_extent": d.value}
+
+
+def relaygr_kv_pool_locate(pool: KvPool, handle: int, layer: int, token: int, feature: int):
+    k, v = C.c_int64(), C.c_int64()
+    _check(load_library().relaygr_kv_pool_locate(pool.handle, handle, layer, token, feature, C.byref(k), C.byref(v)))
+    return k.value, v.value
+
+
+class Batch:
+    """Device embeddings + host offsets of one jagged batch, marshalled as relaygr_batch."""
+
+    def __init__(self, batch: dict, dtype: str, device: str = "cuda:0", handles: Optional[Sequence[int]] = None):
+        td = _torch_dtype(dtype)
+        self.n_users = int(batch["n_users"])
+        dv = torch.device(device)
+
+        def emb(a):
+            if isinstance(a, torch.Tensor):
+                return a
+            return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dv).to(td).contiguous()
+
+        self.prefix_emb = emb(batch["prefix_emb"])
+        self.suffix_emb = emb(batch["suffix_emb"])
+        self.cand_emb = emb(batch["cand_emb"])
+        self.prefix_off = np.ascontiguousarray(batch["prefix_off"], dtype=np.int32)
+        self.suffix_off = np.ascontiguousarray(batch["suffix_off"], dtype=np.int32)
+        self.cand_off = np.ascontiguousarray(batch["cand_off"], dtype=np.int32)
+        self.user_ids = np.ascontiguousarray(batch["user_ids"], dtype=np.uint64)
+        self.handles = np.zeros(self.n_users, dtype=np.uint64)
+        if handles is not None:
+            self.set_handles(handles)
+        self.n_cands = int(self.cand_off[-1]) if self.n_users else 0
+
+    def set_handles(self, handles: Sequence[int]) -> None:
+        self.handles = np.ascontiguousarray(np.asarray(handles, dtype=np.uint64))
+
+    def c_struct(self) -> BatchC:
+        def ptr(t):
+            return t.data_ptr() if t.numel() else None
+        return BatchC(
+            self.n_users,
+            self.user_ids.ctypes.data_as(C.POINTER(C.c_uint64)),
+            self.handles.ctypes.data_as(C.POINTER(C.c_uint64)),
+            ptr(self.prefix_emb), self.prefix_off.ctypes.data_as(C.POINTER(C.c_int32)),
+            ptr(self.suffix_emb), self.suffix_off.ctypes.data_as(C.POINTER(C.c_int32)),
+            ptr(self.cand_emb), self.cand_off.ctypes.data_as(C.POINTER(C.c_int32)),
+        )
+
+
+def relaygr_prefill_prefix(ctx: Context, pool: KvPool, batch: Batch, stream=None) -> None:
+    bc = batch.c_struct()
+    _check(load_library().relaygr_prefill_prefix(ctx.handle, pool.handle, C.byref(bc), _stream_ptr(stream)))
+
+
+def relaygr_rank_with_cache(ctx: Context, pool: Optional[KvPool], batch: Batch, scores: Optional[torch.Tensor] = None,
+                            stream=None) -> torch.Tensor:
+    if scores is None:
+        scores = torch.empty(batch.n_cands, dtype=torch.float32, device=ctx.device)
+    bc = batch.c_struct()
+    _check(load_library().relaygr_rank_with_cache(ctx.handle, pool.handle if pool is not None else None, C.byref(bc),
+                                                  scores.data_ptr(), _stream_ptr(stream)))
+    return scores
+
+
+def relaygr_rank_full_recompute(ctx: Context, batch: Batch, scores: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    if scores is None:
+        scores = torch.empty(batch.n_cands, dtype=torch.float32, device=ctx.device)
+    bc = batch.c_struct()
+    _check(load_library().relaygr_rank_full_recompute(ctx.handle, C.byref(bc), scores.data_ptr(), _stream_ptr(stream)))
+    return scores

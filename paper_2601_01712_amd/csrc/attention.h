@@ -1,0 +1,276 @@
+// Pointwise-SiLU attention over a user's ordered key sequence [prefix | suffix] (step 3 of a
+// layer).  For row i of head h the kernels produce the UNNORMALISED partial sum
+//     part_i^h = sum over the keys j of this split with j < lim_i of  SiLU(alpha <q_i^h, k_j^h>) v_j^h
+// There is no softmax: terms of different keys simply add, so a split of the key range over
+// workgroups needs no renormalisation -- partial sums are added later in fixed split order, the
+// candidate's self term and the 1/n_i are applied there too.
+//
+// Keys come in tiles of 64 tokens (layout in common.h): a K tile [64][dh] followed by a V tile
+// stored transposed [dh][64].  Prefix tiles come from the user's K/V space (pool or scratch),
+// suffix tiles from the suffix scratch space.  Only three kinds of tile need a per-element
+// visibility test: the ragged last prefix tile, suffix tiles (causal for suffix rows), and the
+// diagonal tiles of the causal prefix pass.
+#pragma once
+
+#include "common.h"
+#include "gemm.h"
+
+namespace relaygr {
+
+struct AttnParams {
+  const AttnTile* tiles;
+  const UserDesc* users;
+  RowTables rt;
+  const void* q;      // [rows][d]
+  const void* sfx;    // suffix K/V space (single layer)
+  float* part;        // [nsplit][rows][d]
+  size_t split_stride;
+  int nsplit;
+  int d, n_heads, layer;
+  float score_mul;    // multiplies <q,k> before SiLU (alpha, or 1 if q is stored pre-scaled)
+};
+
+// Key-tile schedule of one work item, shared by both kernels.
+struct TileRange {
+  int nkp;       // prefix tiles this item needs
+  int nfull;     // leading prefix tiles every row of the item sees completely
+  int nks;       // suffix tiles
+  int t0, t1;    // this split's range in the concatenated list [prefix tiles | suffix tiles]
+};
+
+__device__ __forceinline__ TileRange tile_range(const AttnTile& at, const UserDesc& ud, int split, int nsplit) {
+  TileRange tr;
+  if (at.kind == 0) {  // prefix rows: causal, keys 0 .. pos0 + nrows - 1
+    tr.nkp = (at.pos0 + at.nrows + kTile - 1) / kTile;
+    tr.nfull = (at.pos0 + 1) / kTile;
+    tr.nks = 0;
+  } else {             // new rows: the whole prefix, then the suffix
+    tr.nkp = (ud.L + kTile - 1) / kTile;
+    tr.nfull = ud.L / kTile;
+    tr.nks = (ud.S + kTile - 1) / kTile;
+  }
+  int total = tr.nkp + tr.nks;
+  int per = (total + nsplit - 1) / nsplit;
+  tr.t0 = min(split * per, total);
+  tr.t1 = min(tr.t0 + per, total);
+  return tr;
+}
+
+// ---- fp32 kernel: one thread per row, keys broadcast from LDS -----------------------------------
+template <int DH>
+__global__ __launch_bounds__(64) void attn_f32_kernel(AttnParams p) {
+  __shared__ float Ks[kTile * DH];
+  __shared__ float Vs[DH * kTile];
+  const AttnTile at = p.tiles[blockIdx.x];
+  const int head = blockIdx.y, split = blockIdx.z;
+  const UserDesc ud = p.users[at.user];
+  const TileRange tr = tile_range(at, ud, split, p.nsplit);
+  const int t = threadIdx.x;
+  const bool active = t < at.nrows;
+  const int row = at.row0 + (active ? t : 0);
+  const int lim = active ? p.rt.lim[row] : 0;
+
+  float qv[DH], o[DH];
+  const float* qrow = reinterpret_cast<const float*>(p.q) + (size_t)row * p.d + head * DH;
+#pragma unroll
+  for (int f = 0; f < DH; ++f) { qv[f] = qrow[f] * p.score_mul; o[f] = 0.f; }
+
+  for (int tt = tr.t0; tt < tr.t1; ++tt) {
+    const bool is_sfx = tt >= tr.nkp;
+    const float* src;
+    int key0, seg_end;
+    if (!is_sfx) {
+      src = reinterpret_cast<const float*>(ud.kv) + ud.kv_tile0 + (int64_t)tt * ud.kv_tile_stride +
+            (int64_t)p.layer * ud.kv_layer_stride + (int64_t)head * 2 * kTile * DH;
+      key0 = tt * kTile; seg_end = ud.L;
+    } else {
+      int st = tt - tr.nkp;
+      src = reinterpret_cast<const float*>(p.sfx) + ud.sfx_tile0 + (int64_t)st * (2 * kTile * p.d) +
+            (int64_t)head * 2 * kTile * DH;
+      key0 = ud.L + st * kTile; seg_end = ud.L + ud.S;
+    }
+    __syncthreads();
+    for (int i = t; i < kTile * DH; i += 64) { Ks[i] = src[i]; Vs[i] = src[kTile * DH + i]; }
+    __syncthreads();
+    const int vis = min(lim, seg_end) - key0;  // keys [0, vis) of this tile are visible to this row
+    for (int j = 0; j < kTile; ++j) {
+      float s = 0.f;
+#pragma unroll
+      for (int f = 0; f < DH; ++f) s = fmaf(qv[f], Ks[j * DH + f], s);
+      float pj = (j < vis) ? silu_f32(s) : 0.f;
+#pragma unroll
+      for (int f = 0; f < DH; ++f) o[f] = fmaf(pj, Vs[f * kTile + j], o[f]);
+    }
+  }
+  if (active) {
+    float* dst = p.part + split * p.split_stride + (size_t)row * p.d + head * DH;
+#pragma unroll
+    for (int f = 0; f < DH; ++f) dst[f] = o[f];
+  }
+}
+
+// ---- bf16 MFMA kernel ---------------------------------------------------------------------------
+// A workgroup of 4 wavefronts owns up to 128*NQ rows (each wavefront NQ blocks of 32 rows) of one
+// user and one head and walks the key tiles of its split.  Per 64-key tile and wavefront:
+//   S^T[64 keys][32 rows]  = K tile (A operand, rows = keys)  x  Q^T (B operand, held in registers)
+//   P^T = SiLU'(S^T) rounded to bf16 -- the accumulator layout of S^T (lane = row, 4-key runs) is
+//         exactly the B-operand layout of the next product once the V fragment is read with the
+//         same key permutation, so P never leaves registers
+//   O^T[dh][32 rows]      += V^T tile (A operand, rows = features) x P^T
+// q is stored pre-multiplied by alpha*log2(e); SiLU'(t) = t / (1 + 2^-t) = SiLU(s)/ln 2 with
+// s = t ln 2, and the ln 2 is applied once to the output.
+constexpr int kAttnKLd = 8;   // bf16 elements of padding per LDS row
+
+template <int DH, int NQ>
+__global__ __launch_bounds__(256) void attn_bf16_kernel(AttnParams p) {
+  constexpr int KLD = DH + kAttnKLd;      // K tile row stride (elements)
+  constexpr int VLD = kTile + kAttnKLd;   // V^T tile row stride
+  constexpr int KS = DH / 16;             // k-steps of the first product
+  constexpr int DB = DH / 32;             // 32-feature blocks of the output
+  __shared__ __attribute__((aligned(16))) uint16_t Ks[kTile * KLD];
+  __shared__ __attribute__((aligned(16))) uint16_t Vs[DH * VLD];
+
+  const AttnTile at = p.tiles[blockIdx.x];
+  const int head = blockIdx.y, split = blockIdx.z;
+  const UserDesc ud = p.users[at.user];
+  const TileRange tr = tile_range(at, ud, split, p.nsplit);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, g = lane >> 5;
+
+  // this lane's rows: block qb covers rows wave*32*NQ + qb*32 + l32 of the work item
+  int lim[NQ];
+  bf16x8_t qf[NQ][KS];
+  const uint16_t* qbase = reinterpret_cast<const uint16_t*>(p.q);
+#pragma unroll
+  for (int qb = 0; qb < NQ; ++qb) {
+    int lr = wave * 32 * NQ + qb * 32 + l32;
+    bool ok = lr < at.nrows;
+    int row = at.row0 + (ok ? lr : 0);
+    lim[qb] = ok ? p.rt.lim[row] : 0;
+    const uint16_t* qr = qbase + (size_t)row * p.d + head * DH + g * 8;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(qr + ks * 16));
+  }
+
+  f32x16_t oacc[DB][NQ];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int qb = 0; qb < NQ; ++qb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) oacc[db][qb][e] = 0.f;
+
+  // global -> register staging of one K tile and one V^T tile: 64*DH*2 B each = DH/2 chunks of 16 B per thread pair
+  constexpr int CH = (kTile * DH) / (8 * 256);  // 16-byte chunks per thread per operand
+  uint4 rk[CH], rv[CH];
+  auto tile_src = [&](int tt) -> const uint16_t* {
+    if (tt < tr.nkp)
+      return reinterpret_cast<const uint16_t*>(ud.kv) + ud.kv_tile0 + (int64_t)tt * ud.kv_tile_stride +
+             (int64_t)p.layer * ud.kv_layer_stride + (int64_t)head * 2 * kTile * DH;
+    return reinterpret_cast<const uint16_t*>(p.sfx) + ud.sfx_tile0 + (int64_t)(tt - tr.nkp) * (2 * kTile * p.d) +
+           (int64_t)head * 2 * kTile * DH;
+  };
+  auto load_tile = [&](int tt) {
+    const uint4* src = reinterpret_cast<const uint4*>(tile_src(tt));
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      rk[i] = src[tid + i * 256];
+      rv[i] = src[(kTile * DH) / 8 + tid + i * 256];
+    }
+  };
+  auto store_tile = [&]() {
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      int c = tid + i * 256;
+      int krow = c / (DH / 8), kc = c % (DH / 8);
+      *reinterpret_cast<uint4*>(&Ks[krow * KLD + kc * 8]) = rk[i];
+      int vrow = c / (kTile / 8), vc = c % (kTile / 8);
+      *reinterpret_cast<uint4*>(&Vs[vrow * VLD + vc * 8]) = rv[i];
+    }
+  };
+
+  if (tr.t0 < tr.t1) load_tile(tr.t0);
+  for (int tt = tr.t0; tt < tr.t1; ++tt) {
+    __syncthreads();
+    store_tile();
+    __syncthreads();
+    if (tt + 1 < tr.t1) load_tile(tt + 1);
+
+    const bool is_sfx = tt >= tr.nkp;
+    const bool masked = is_sfx || tt >= tr.nfull;
+    const int key0 = is_sfx ? ud.L + (tt - tr.nkp) * kTile : tt * kTile;
+    const int seg_end = is_sfx ? ud.L + ud.S : ud.L;
+
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      f32x16_t s[NQ];
+#pragma unroll
+      for (int qb = 0; qb < NQ; ++qb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s[qb][e] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        bf16x8_t kf = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(&Ks[(kb * 32 + l32) * KLD + ks * 16 + g * 8]));
+#pragma unroll
+        for (int qb = 0; qb < NQ; ++qb) s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], s[qb], 0, 0, 0);
+      }
+      // element e of s: key kb*32 + 8*(e/4) + 4*g + e%4 of the tile, row l32 of block qb
+      uint32_t pk[NQ][8];
+#pragma unroll
+      for (int qb = 0; qb < NQ; ++qb) {
+        float pv[16];
+        const int vis = min(lim[qb], seg_end) - key0;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          float t = s[qb][e];
+          float pe = t * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-t));
+          if (masked) {
+            int key = kb * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
+            pe = (key < vis) ? pe : 0.f;
+          }
+          pv[e] = pe;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          pk[qb][e] = (uint32_t)float_to_bf16_bits(pv[2 * e]) | ((uint32_t)float_to_bf16_bits(pv[2 * e + 1]) << 16);
+      }
+      // second product, 16 keys per step: step m uses accumulator elements 8m .. 8m+7, i.e. keys
+      // kb*32 + 16m + 4g + {0..3} and kb*32 + 16m + 8 + 4g + {0..3}
+#pragma unroll
+      for (int m = 0; m < 2; ++m) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          const uint16_t* vr = &Vs[(db * 32 + l32) * VLD + kb * 32 + 16 * m + 4 * g];
+          uint2 lo = *reinterpret_cast<const uint2*>(vr);
+          uint2 hi = *reinterpret_cast<const uint2*>(vr + 8);
+          uint4 vv = make_uint4(lo.x, lo.y, hi.x, hi.y);
+          bf16x8_t vf = __builtin_bit_cast(bf16x8_t, vv);
+#pragma unroll
+          for (int qb = 0; qb < NQ; ++qb) {
+            uint4 pp = make_uint4(pk[qb][4 * m], pk[qb][4 * m + 1], pk[qb][4 * m + 2], pk[qb][4 * m + 3]);
+            oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, __builtin_bit_cast(bf16x8_t, pp), oacc[db][qb], 0, 0, 0);
+          }
+        }
+      }
+    }
+  }
+
+  // element e of oacc[db][qb]: feature db*32 + 8*(e/4) + 4*g + e%4, row l32 of block qb
+  const float kLn2 = 0.69314718055994531f;
+#pragma unroll
+  for (int qb = 0; qb < NQ; ++qb) {
+    int lr = wave * 32 * NQ + qb * 32 + l32;
+    if (lr >= at.nrows) continue;
+    float* dst = p.part + split * p.split_stride + (size_t)(at.row0 + lr) * p.d + head * DH;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int e4 = 0; e4 < 4; ++e4) {
+        float4 v = make_float4(oacc[db][qb][4 * e4] * kLn2, oacc[db][qb][4 * e4 + 1] * kLn2,
+                               oacc[db][qb][4 * e4 + 2] * kLn2, oacc[db][qb][4 * e4 + 3] * kLn2);
+        *reinterpret_cast<float4*>(dst + db * 32 + 8 * e4 + 4 * g) = v;
+      }
+  }
+}
+
+}  // namespace relaygr

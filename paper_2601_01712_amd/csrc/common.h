@@ -1,0 +1,92 @@
+// Shared device/host declarations of the relay-race kernels (gfx950 only).
+//
+// Row space of one call.  Every token processed in a call is a "row":
+//   [ prefix rows of the users whose prefix is computed in this call, user by user |
+//     new rows of every user: that user's suffix tokens, then its candidates ]
+// (sequence order of Section 2.3: long-term prefix, short-term / cross tokens, candidates).
+// Each row carries its user, its kind, its index inside that segment, the number of keys of
+// the user's ordered key sequence [prefix | suffix] it may see (lim), and where its embedding
+// comes from.  A candidate additionally sees itself; that term never enters the key sequence.
+//
+// Cached K/V layout.  Keys are stored in tiles of 64 tokens.  One tile block holds, for every
+// layer and head, a K tile [64 tokens][d_head] followed by a V tile stored transposed
+// [d_head][64 tokens] (the orientation the second MFMA of the attention wants):
+//     element(K; tile, layer, head, r, f) = tile*tile_stride + layer*layer_stride + head*128*dh + r*dh + f
+//     element(V; ...)                     = the same base + 64*dh + f*64 + r
+// with tile_stride = n_layers*2*64*d and layer_stride = 2*64*d in the pool, and a single-layer
+// form (tile_stride = 2*64*d, layer_stride = 0) in scratch for suffix tokens and for prefixes
+// recomputed inside a ranking call.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_bf16.h>
+#include <stdint.h>
+
+namespace relaygr {
+
+constexpr int kTile = 64;   // tokens per K/V tile
+
+enum RowKind : int32_t { kRowPrefix = 0, kRowSuffix = 1, kRowCand = 2 };
+
+struct UserDesc {
+  const void* kv;          // space holding this user's prefix K/V (pool slab or scratch)
+  int64_t kv_tile0;        // element offset of the user's tile 0, layer 0, head 0
+  int64_t kv_tile_stride;  // elements between consecutive tiles
+  int64_t kv_layer_stride; // elements between layers (0 in single-layer scratch)
+  int64_t sfx_tile0;       // element offset of the user's suffix tile 0 in the suffix scratch space
+  int32_t L, S, M;
+  int32_t prow0;           // first prefix row of this user in the call's row space, -1 if not computed
+  int32_t nrow0;           // first new row (suffix rows, then candidates), -1 if the call has none
+  int32_t prefix_src0, suffix_src0, cand_src0;  // first row in each embedding array
+  int32_t pad0, pad1;
+};
+static_assert(sizeof(UserDesc) == 80, "UserDesc layout");
+
+// One attention work item: nrows (<= rows per workgroup) consecutive rows of one user.
+struct AttnTile {
+  int32_t user;
+  int32_t row0;     // first row in the call's row space
+  int32_t nrows;
+  int32_t kind;     // 0: prefix rows (causal over the prefix); 1: new rows
+  int32_t pos0;     // prefix rows: position of row0 in the prefix; new rows: index among new rows
+  int32_t pad[3];
+};
+static_assert(sizeof(AttnTile) == 32, "AttnTile layout");
+
+struct RowTables {
+  int32_t* user;
+  int32_t* kind;
+  int32_t* idx;    // index inside the user's segment of that kind
+  int32_t* lim;    // keys of [prefix | suffix] visible to this row
+  int32_t* src;    // row in the embedding array of its kind
+};
+
+// ---- element access in the two storage types ------------------------------------------------
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static __device__ __forceinline__ float ld(const float* p) { return *p; }
+  static __device__ __forceinline__ void st(float* p, float v) { *p = v; }
+};
+template <> struct Elem<__hip_bfloat16> {
+  static __device__ __forceinline__ float ld(const __hip_bfloat16* p) {
+    return __uint_as_float(((uint32_t)(*reinterpret_cast<const uint16_t*>(p))) << 16);
+  }
+  static __device__ __forceinline__ void st(__hip_bfloat16* p, float v) { *p = __float2bfloat16(v); }
+};
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float v) {
+  __hip_bfloat16 h = __float2bfloat16(v);
+  return *reinterpret_cast<uint16_t*>(&h);
+}
+
+// SiLU(t) = t / (1 + exp(-t)), fp32, accurate form (used outside the attention inner loop).
+__device__ __forceinline__ float silu_f32(float t) { return t / (1.0f + __expf(-t)); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+}  // namespace relaygr

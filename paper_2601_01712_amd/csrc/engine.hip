@@ -1,0 +1,653 @@
+// C-ABI entry points and the host side of the relay-race path: validation, the per-call row
+// plan, scratch carving and the fixed kernel sequence of a layer.  Declarations and argument
+// contracts are in include/relaygr.h.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <type_traits>
+#include <vector>
+
+#include "../../include/relaygr.h"
+#include "attention.h"
+#include "common.h"
+#include "gemm.h"
+#include "kv_pool.h"
+#include "rowwise.h"
+
+using namespace relaygr;
+
+// ---- errors -----------------------------------------------------------------------------------
+static thread_local char g_err[512] = "";
+
+static int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                          \
+  do {                                                                                         \
+    hipError_t e_ = (expr);                                                                    \
+    if (e_ != hipSuccess) return fail(RELAYGR_EHIP, "%s: %s", #expr, hipGetErrorString(e_));   \
+  } while (0)
+
+#define LAUNCH_CHECK(name)                                                                     \
+  do {                                                                                         \
+    hipError_t e_ = hipGetLastError();                                                         \
+    if (e_ != hipSuccess) return fail(RELAYGR_EHIP, "launch %s: %s", name, hipGetErrorString(e_)); \
+  } while (0)
+
+extern "C" const char* relaygr_last_error(void) { return g_err; }
+
+// ---- config -----------------------------------------------------------------------------------
+static bool config_ok(const relaygr_model_config* c) {
+  if (!c) return false;
+  if (c->n_layers < 1 || c->n_heads < 1 || c->d_model < 64) return false;
+  if (c->dtype != RELAYGR_DTYPE_FP32 && c->dtype != RELAYGR_DTYPE_BF16) return false;
+  int d = c->d_model;
+  if (d != 64 && d != 128 && d != 256 && d != 512 && d != 1024) return false;
+  if (d % c->n_heads) return false;
+  int dh = d / c->n_heads;
+  if (dh != 32 && dh != 64 && dh != 128) return false;
+  if (dh < d / 64) return false;                       // a head must span at least one lane in row-wise kernels
+  if (c->dtype == RELAYGR_DTYPE_BF16 && d < 128) return false;  // the MFMA GEMM tiles 128 output columns
+  if (!(c->ln_eps > 0.f)) return false;
+  return true;
+}
+
+static inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+extern "C" size_t relaygr_kv_footprint_bytes(const relaygr_model_config* cfg, int32_t prefix_len) {
+  if (!config_ok(cfg) || prefix_len < 0) return 0;
+  return (size_t)2 * cfg->n_layers * (size_t)prefix_len * cfg->d_model * elem_bytes(*cfg);
+}
+
+extern "C" size_t relaygr_kv_pool_bytes_for(const relaygr_model_config* cfg, int32_t prefix_len, int32_t page_tokens) {
+  if (!config_ok(cfg) || prefix_len < 0 || page_tokens < kTile || page_tokens % kTile) return 0;
+  size_t pages = ((size_t)prefix_len + page_tokens - 1) / page_tokens;
+  return pages * (size_t)2 * cfg->n_layers * page_tokens * cfg->d_model * elem_bytes(*cfg);
+}
+
+// ---- per-call plan ----------------------------------------------------------------------------
+struct Plan {
+  int n_users = 0;
+  int n_prows = 0, n_nrows = 0, n_rows = 0;
+  int64_t sfx_tiles = 0, kvs_tiles = 0;   // suffix tiles / recomputed-prefix tiles held in scratch
+  int n_tiles_new = 0, n_tiles_prefix = 0;
+  int nsplit = 1;
+  // byte offsets into scratch
+  size_t off_x, off_xh, off_u, off_q, off_knew, off_vnew, off_sfx, off_kvs, off_part, off_rows, off_blob;
+  size_t blob_bytes = 0;
+  size_t total = 0;
+};
+
+static int rows_per_attn_tile(const relaygr_model_config& c) { return c.dtype == RELAYGR_DTYPE_FP32 ? 64 : 128; }
+
+// Lays the call's buffers out in scratch.  Everything is a function of the counts already in p.
+static void carve(const relaygr_model_config& c, Plan& p) {
+  const size_t d = c.d_model, e = elem_bytes(c), R = p.n_rows;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
+  p.off_x = take(R * d * 4);
+  p.off_xh = take(R * d * e);
+  p.off_u = take(R * d * e);
+  p.off_q = take(R * d * e);
+  p.off_knew = take((size_t)p.n_nrows * d * e);
+  p.off_vnew = take((size_t)p.n_nrows * d * e);
+  p.off_sfx = take((size_t)p.sfx_tiles * 2 * kTile * d * e);
+  p.off_kvs = take((size_t)p.kvs_tiles * 2 * kTile * d * e);
+  p.off_part = take((size_t)p.nsplit * R * d * 4);
+  p.off_rows = take(5 * align_up(R * 4));
+  size_t n_tiles = (size_t)p.n_tiles_new + p.n_tiles_prefix;
+  p.blob_bytes = align_up((size_t)p.n_users * sizeof(UserDesc)) + 2 * align_up((size_t)(p.n_users + 1) * 4) +
+                 align_up(n_tiles * sizeof(AttnTile));
+  p.off_blob = take(p.blob_bytes);
+  p.total = o;
+}
+
+// Key-range splits wanted so that the attention launch fills the chip: workgroups = tiles * heads
+// * splits, aiming at two per compute unit, never more splits than a row tile has key tiles.
+static int wanted_splits(int n_tiles, int n_heads, int min_key_tiles) {
+  if (n_tiles <= 0) return 1;
+  int wgs = n_tiles * n_heads;
+  int s = (512 + wgs - 1) / wgs;
+  s = std::min(s, 8);
+  s = std::min(s, std::max(1, min_key_tiles));
+  return std::max(s, 1);
+}
+
+extern "C" size_t relaygr_scratch_bytes(const relaygr_model_config* cfg, int32_t max_users,
+                                        int64_t max_prefix_tokens, int64_t max_new_tokens) {
+  if (!config_ok(cfg) || max_users < 1 || max_prefix_tokens < 0 || max_new_tokens < 0) return 0;
+  if (max_prefix_tokens + max_new_tokens >= (1ll << 31)) return 0;
+  Plan p;
+  p.n_users = max_users;
+  p.n_prows = (int)max_prefix_tokens;
+  p.n_nrows = (int)max_new_tokens;
+  p.n_rows = p.n_prows + p.n_nrows;
+  p.sfx_tiles = max_new_tokens / kTile + max_users;
+  p.kvs_tiles = max_prefix_tokens / kTile + max_users;
+  int rpt = rows_per_attn_tile(*cfg);
+  p.n_tiles_new = (int)(max_new_tokens / rpt) + max_users;
+  p.n_tiles_prefix = (int)(max_prefix_tokens / rpt) + max_users;
+  p.nsplit = 1;
+  carve(*cfg, p);
+  size_t base = p.total;
+  // head-room so that small calls may split their key range 8 ways
+  size_t small_rows = std::min<size_t>((size_t)p.n_rows, 8192);
+  return base + align_up(small_rows * 7 * (size_t)cfg->d_model * 4);
+}
+
+// ---- context ----------------------------------------------------------------------------------
+struct StagingSlot {
+  void* host = nullptr;
+  size_t bytes = 0;
+  hipEvent_t done = nullptr;
+  bool pending = false;
+};
+
+struct relaygr_ctx {
+  relaygr_model_config cfg;
+  std::vector<relaygr_layer_weights> layers;
+  const void *ln_out_g, *ln_out_b, *w_score;
+  float b_score;
+  char* scratch;
+  size_t scratch_bytes;
+  StagingSlot staging[4];
+  int next_slot = 0;
+};
+
+extern "C" int relaygr_ctx_create(const relaygr_model_config* cfg, const relaygr_weights* w, void* scratch_dev,
+                                  size_t scratch_bytes, relaygr_ctx** out) {
+  if (!out) return fail(RELAYGR_EINVAL, "ctx_create: out is null");
+  *out = nullptr;
+  if (!config_ok(cfg)) return fail(RELAYGR_EINVAL, "ctx_create: unsupported model config");
+  if (!w || !w->layers || !w->ln_out_g || !w->ln_out_b || !w->w_score) return fail(RELAYGR_EINVAL, "ctx_create: null weights");
+  if (!scratch_dev || ((uintptr_t)scratch_dev & 255)) return fail(RELAYGR_EINVAL, "ctx_create: scratch null or not 256-byte aligned");
+  for (int l = 0; l < cfg->n_layers; ++l) {
+    const relaygr_layer_weights& lw = w->layers[l];
+    if (!lw.ln_in_g || !lw.ln_in_b || !lw.w1 || !lw.b1 || !lw.ln_at_g || !lw.ln_at_b || !lw.w2 || !lw.b2)
+      return fail(RELAYGR_EINVAL, "ctx_create: layer %d has a null parameter", l);
+  }
+  relaygr_ctx* c = new (std::nothrow) relaygr_ctx();
+  if (!c) return fail(RELAYGR_EINVAL, "ctx_create: out of host memory");
+  c->cfg = *cfg;
+  c->layers.assign(w->layers, w->layers + cfg->n_layers);
+  c->ln_out_g = w->ln_out_g; c->ln_out_b = w->ln_out_b; c->w_score = w->w_score; c->b_score = w->b_score;
+  c->scratch = (char*)scratch_dev;
+  c->scratch_bytes = scratch_bytes;
+  *out = c;
+  return RELAYGR_OK;
+}
+
+extern "C" void relaygr_ctx_destroy(relaygr_ctx* c) {
+  if (!c) return;
+  for (auto& s : c->staging) {
+    if (s.done) { if (s.pending) (void)hipEventSynchronize(s.done); (void)hipEventDestroy(s.done); }
+    if (s.host) (void)hipHostFree(s.host);
+  }
+  delete c;
+}
+
+// Pinned staging for the descriptor blob: a ring of 4, each guarded by an event so that a slot is
+// not rewritten while an earlier call's copy may still read it.
+static int staging_acquire(relaygr_ctx* c, size_t bytes, StagingSlot** out) {
+  StagingSlot& s = c->staging[c->next_slot];
+  c->next_slot = (c->next_slot + 1) & 3;
+  if (!s.done) HIP_TRY(hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
+  if (s.pending) { HIP_TRY(hipEventSynchronize(s.done)); s.pending = false; }
+  if (s.bytes < bytes) {
+    if (s.host) { HIP_TRY(hipHostFree(s.host)); s.host = nullptr; s.bytes = 0; }
+    size_t want = std::max<size_t>(align_up(bytes, 4096) * 2, 1 << 16);
+    HIP_TRY(hipHostMalloc(&s.host, want, hipHostMallocDefault));
+    s.bytes = want;
+  }
+  *out = &s;
+  return RELAYGR_OK;
+}
+
+// ---- pool ABI ---------------------------------------------------------------------------------
+extern "C" int relaygr_kv_pool_create(const relaygr_model_config* cfg, void* slab_dev, size_t slab_bytes,
+                                      int32_t page_tokens, relaygr_kv_pool** out) {
+  if (!out) return fail(RELAYGR_EINVAL, "kv_pool_create: out is null");
+  *out = nullptr;
+  if (!config_ok(cfg)) return fail(RELAYGR_EINVAL, "kv_pool_create: unsupported model config");
+  if (!slab_dev || ((uintptr_t)slab_dev & 255)) return fail(RELAYGR_EINVAL, "kv_pool_create: slab null or not 256-byte aligned");
+  if (page_tokens < kTile || page_tokens % kTile) return fail(RELAYGR_EINVAL, "kv_pool_create: page_tokens must be a positive multiple of 64");
+  size_t page_bytes = (size_t)2 * cfg->n_layers * page_tokens * cfg->d_model * elem_bytes(*cfg);
+  int64_t n_pages = (int64_t)(slab_bytes / page_bytes);
+  if (n_pages < 1) return fail(RELAYGR_ENOSPC, "kv_pool_create: slab smaller than one page (%zu bytes)", page_bytes);
+  if (n_pages * (int64_t)page_tokens >= (1ll << 31)) return fail(RELAYGR_EINVAL, "kv_pool_create: slab holds 2^31 tokens or more");
+  KvPool* p = new (std::nothrow) KvPool();
+  if (!p) return fail(RELAYGR_EINVAL, "kv_pool_create: out of host memory");
+  p->cfg = *cfg;
+  p->slab = slab_dev;
+  p->slab_bytes = slab_bytes;
+  p->page_tokens = page_tokens;
+  p->n_pages = n_pages;
+  p->layer_stride = (int64_t)2 * kTile * cfg->d_model;
+  p->tile_stride = p->layer_stride * cfg->n_layers;
+  p->free_extents[0] = n_pages;
+  *out = reinterpret_cast<relaygr_kv_pool*>(p);
+  return RELAYGR_OK;
+}
+
+extern "C" void relaygr_kv_pool_destroy(relaygr_kv_pool* pool) { delete reinterpret_cast<KvPool*>(pool); }
+
+extern "C" int relaygr_kv_pool_alloc(relaygr_kv_pool* pool, uint64_t user_id, int32_t prefix_len, relaygr_kv_handle* out) {
+  if (!pool || !out) return fail(RELAYGR_EINVAL, "kv_pool_alloc: null argument");
+  int rc = reinterpret_cast<KvPool*>(pool)->alloc(user_id, prefix_len, out);
+  if (rc == RELAYGR_ENOSPC) return fail(rc, "kv_pool_alloc: no free extent for %d tokens", prefix_len);
+  if (rc != RELAYGR_OK) return fail(rc, "kv_pool_alloc: prefix_len < 1 or user %llu already has a live entry", (unsigned long long)user_id);
+  return rc;
+}
+
+extern "C" int relaygr_kv_pool_free(relaygr_kv_pool* pool, relaygr_kv_handle h) {
+  if (!pool) return fail(RELAYGR_EINVAL, "kv_pool_free: null pool");
+  int rc = reinterpret_cast<KvPool*>(pool)->release(h);
+  if (rc != RELAYGR_OK) return fail(rc, "kv_pool_free: stale or unknown handle");
+  return rc;
+}
+
+extern "C" int relaygr_kv_pool_lookup(relaygr_kv_pool* pool, uint64_t user_id, relaygr_kv_handle* out) {
+  if (!pool || !out) return fail(RELAYGR_EINVAL, "kv_pool_lookup: null argument");
+  int rc = reinterpret_cast<KvPool*>(pool)->lookup(user_id, out);
+  if (rc != RELAYGR_OK) return fail(rc, "kv_pool_lookup: user %llu has no live entry", (unsigned long long)user_id);
+  return rc;
+}
+
+extern "C" int relaygr_kv_pool_entry_len(relaygr_kv_pool* pool, relaygr_kv_handle h, int32_t* prefix_len) {
+  if (!pool || !prefix_len) return fail(RELAYGR_EINVAL, "kv_pool_entry_len: null argument");
+  PoolEntry e;
+  int rc = reinterpret_cast<KvPool*>(pool)->resolve(h, &e);
+  if (rc != RELAYGR_OK) return fail(rc, "kv_pool_entry_len: stale or unknown handle");
+  *prefix_len = e.prefix_len;
+  return RELAYGR_OK;
+}
+
+extern "C" int relaygr_kv_pool_stats(relaygr_kv_pool* pool, int64_t* total, int64_t* free_pages, int64_t* live, int64_t* largest) {
+  if (!pool) return fail(RELAYGR_EINVAL, "kv_pool_stats: null pool");
+  reinterpret_cast<KvPool*>(pool)->stats(total, free_pages, live, largest);
+  return RELAYGR_OK;
+}
+
+extern "C" int relaygr_kv_pool_locate(relaygr_kv_pool* pool, relaygr_kv_handle h, int32_t layer, int32_t token,
+                                      int32_t feature, int64_t* k_index, int64_t* v_index) {
+  if (!pool || !k_index || !v_index) return fail(RELAYGR_EINVAL, "kv_pool_locate: null argument");
+  KvPool* p = reinterpret_cast<KvPool*>(pool);
+  PoolEntry e;
+  int rc = p->resolve(h, &e);
+  if (rc != RELAYGR_OK) return fail(rc, "kv_pool_locate: stale or unknown handle");
+  if (layer < 0 || layer >= p->cfg.n_layers || token < 0 || token >= e.prefix_len || feature < 0 || feature >= p->cfg.d_model)
+    return fail(RELAYGR_EINVAL, "kv_pool_locate: index out of range");
+  int dh = p->cfg.d_model / p->cfg.n_heads;
+  int head = feature / dh, f = feature % dh;
+  int64_t tile = e.page0 * (p->page_tokens / kTile) + token / kTile;
+  int r = token % kTile;
+  int64_t base = tile * p->tile_stride + (int64_t)layer * p->layer_stride + (int64_t)head * 2 * kTile * dh;
+  *k_index = base + (int64_t)r * dh + f;
+  *v_index = base + (int64_t)kTile * dh + (int64_t)f * kTile + r;
+  return RELAYGR_OK;
+}
+
+// ---- the layer sequence -----------------------------------------------------------------------
+enum Mode { kPrefill, kRankCached, kRankFull };
+
+template <typename F>
+static inline bool dispatch_e(int d, F&& f) {
+  switch (d / 64) {
+    case 1: f(std::integral_constant<int, 1>()); return true;
+    case 2: f(std::integral_constant<int, 2>()); return true;
+    case 4: f(std::integral_constant<int, 4>()); return true;
+    case 8: f(std::integral_constant<int, 8>()); return true;
+    case 16: f(std::integral_constant<int, 16>()); return true;
+  }
+  return false;
+}
+
+template <typename T> struct GemmLaunch;
+
+template <> struct GemmLaunch<float> {
+  static constexpr int BM = kSgemmBM;
+  template <class Epi>
+  static void run(const float* A, const float* W, int K, int r0, int r1, const ColMap& cm, const Epi& epi, hipStream_t st) {
+    int mt = (r1 - r0 + BM - 1) / BM;
+    int total = mt * cm.nblk * (cm.d / kSgemmBN);
+    hipLaunchKernelGGL((gemm_f32_kernel<Epi>), dim3(total), dim3(256), 0, st, A, W, K, r0, r1, cm, mt, epi);
+  }
+};
+
+template <> struct GemmLaunch<__hip_bfloat16> {
+  static constexpr int BM = kGemmBM;
+  template <class Epi>
+  static void run(const __hip_bfloat16* A, const __hip_bfloat16* W, int K, int r0, int r1, const ColMap& cm, const Epi& epi, hipStream_t st) {
+    int mt = (r1 - r0 + BM - 1) / BM;
+    int total = mt * cm.nblk * (cm.d / kGemmBN);
+    int grid = ((total + 7) / 8) * 8;
+    hipLaunchKernelGGL((gemm_bf16_kernel<Epi>), dim3(grid), dim3(256), 0, st, A, W, K, r0, r1, cm, mt, epi);
+  }
+};
+
+template <typename T>
+static int launch_attention(const relaygr_model_config& cfg, const AttnParams& ap, int n_tiles, hipStream_t st);
+
+template <>
+int launch_attention<float>(const relaygr_model_config& cfg, const AttnParams& ap, int n_tiles, hipStream_t st) {
+  dim3 grid(n_tiles, cfg.n_heads, ap.nsplit);
+  switch (cfg.d_model / cfg.n_heads) {
+    case 32: hipLaunchKernelGGL((attn_f32_kernel<32>), grid, dim3(64), 0, st, ap); break;
+    case 64: hipLaunchKernelGGL((attn_f32_kernel<64>), grid, dim3(64), 0, st, ap); break;
+    case 128: hipLaunchKernelGGL((attn_f32_kernel<128>), grid, dim3(64), 0, st, ap); break;
+    default: return fail(RELAYGR_EINVAL, "attention: unsupported d_head");
+  }
+  LAUNCH_CHECK("attn_f32");
+  return RELAYGR_OK;
+}
+
+template <>
+int launch_attention<__hip_bfloat16>(const relaygr_model_config& cfg, const AttnParams& ap, int n_tiles, hipStream_t st) {
+  dim3 grid(n_tiles, cfg.n_heads, ap.nsplit);
+  switch (cfg.d_model / cfg.n_heads) {
+    case 32: hipLaunchKernelGGL((attn_bf16_kernel<32, 1>), grid, dim3(256), 0, st, ap); break;
+    case 64: hipLaunchKernelGGL((attn_bf16_kernel<64, 1>), grid, dim3(256), 0, st, ap); break;
+    case 128: hipLaunchKernelGGL((attn_bf16_kernel<128, 1>), grid, dim3(256), 0, st, ap); break;
+    default: return fail(RELAYGR_EINVAL, "attention: unsupported d_head");
+  }
+  LAUNCH_CHECK("attn_bf16");
+  return RELAYGR_OK;
+}
+
+static int check_offsets(const int32_t* off, int n, const char* what) {
+  if (!off) return RELAYGR_OK;
+  if (off[0] != 0) return fail(RELAYGR_EINVAL, "%s offsets must start at 0", what);
+  for (int i = 0; i < n; ++i)
+    if (off[i + 1] < off[i]) return fail(RELAYGR_EINVAL, "%s offsets not monotone at user %d", what, i);
+  return RELAYGR_OK;
+}
+
+template <typename T>
+static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode mode, float* scores, hipStream_t st) {
+  const relaygr_model_config& cfg = c->cfg;
+  const int d = cfg.d_model, H = cfg.n_heads, dh = d / H, NL = cfg.n_layers, n = b->n_users;
+  const bool bf16 = cfg.dtype == RELAYGR_DTYPE_BF16;
+  const int rpt = rows_per_attn_tile(cfg);
+
+  // -- per-user shapes and K/V sources
+  std::vector<UserDesc> users(n);
+  std::vector<int32_t> pstart(n + 1, 0), nstart(n + 1, 0);
+  Plan p;
+  p.n_users = n;
+  int64_t prow = 0, nrow = 0, sfx_tiles = 0, kvs_tiles = 0;
+  for (int u = 0; u < n; ++u) {
+    UserDesc& ud = users[u];
+    memset(&ud, 0, sizeof(ud));
+    int L = b->prefix_off ? b->prefix_off[u + 1] - b->prefix_off[u] : 0;
+    int S = (mode != kPrefill && b->suffix_off) ? b->suffix_off[u + 1] - b->suffix_off[u] : 0;
+    int M = (mode != kPrefill && b->cand_off) ? b->cand_off[u + 1] - b->cand_off[u] : 0;
+    ud.L = L; ud.S = S; ud.M = M;
+    ud.prefix_src0 = b->prefix_off ? b->prefix_off[u] : 0;
+    ud.suffix_src0 = b->suffix_off ? b->suffix_off[u] : 0;
+    ud.cand_src0 = b->cand_off ? b->cand_off[u] : 0;
+    relaygr_kv_handle h = (mode == kRankFull || !b->handles) ? RELAYGR_NO_CACHE : b->handles[u];
+    bool compute_prefix;
+    if (h != RELAYGR_NO_CACHE) {
+      if (!pool) return fail(RELAYGR_EINVAL, "user %d has a handle but no pool was given", u);
+      PoolEntry e;
+      if (pool->resolve(h, &e) != RELAYGR_OK) return fail(RELAYGR_ENOENT, "user %d: stale or unknown handle", u);
+      if (e.prefix_len != L) return fail(RELAYGR_EINVAL, "user %d: prefix length %d differs from the cached entry's %d", u, L, e.prefix_len);
+      ud.kv = pool->slab;
+      ud.kv_tile0 = e.page0 * (pool->page_tokens / kTile) * pool->tile_stride;
+      ud.kv_tile_stride = pool->tile_stride;
+      ud.kv_layer_stride = pool->layer_stride;
+      compute_prefix = (mode == kPrefill);
+    } else {
+      if (mode == kPrefill) {
+        if (L > 0) return fail(RELAYGR_EINVAL, "prefill: user %d has no handle", u);
+        compute_prefix = false;
+      } else {
+        compute_prefix = L > 0;
+        ud.kv_tile0 = kvs_tiles * (int64_t)(2 * kTile * d);   // pointer filled in once scratch is carved
+        ud.kv_tile_stride = (int64_t)2 * kTile * d;
+        ud.kv_layer_stride = 0;
+        kvs_tiles += (L + kTile - 1) / kTile;
+      }
+    }
+    pstart[u] = (int32_t)prow;
+    ud.prow0 = compute_prefix ? (int32_t)prow : -1;
+    if (compute_prefix) {
+      if (!b->prefix_emb) return fail(RELAYGR_EINVAL, "user %d needs prefix_emb", u);
+      prow += L;
+    }
+    nstart[u] = (int32_t)nrow;
+    ud.nrow0 = (mode != kPrefill) ? (int32_t)nrow : -1;
+    ud.sfx_tile0 = sfx_tiles * (int64_t)(2 * kTile * d);
+    if (mode != kPrefill) { nrow += S + M; sfx_tiles += (S + kTile - 1) / kTile; }
+    if (prow + nrow >= (1ll << 31) - 1) return fail(RELAYGR_EINVAL, "batch has 2^31 rows or more");
+  }
+  pstart[n] = (int32_t)prow;
+  p.n_prows = (int)prow; p.n_nrows = (int)nrow; p.n_rows = (int)(prow + nrow);
+  p.sfx_tiles = sfx_tiles; p.kvs_tiles = kvs_tiles;
+  for (int u = 0; u <= n; ++u) nstart[u] = (u < n ? nstart[u] : (int32_t)nrow) + p.n_prows;
+  for (int u = 0; u < n; ++u) if (users[u].nrow0 >= 0) users[u].nrow0 += p.n_prows;
+  if (p.n_rows == 0) return RELAYGR_OK;
+  if (mode != kPrefill && nrow > 0) {
+    if ((sfx_tiles > 0 && !b->suffix_emb)) return fail(RELAYGR_EINVAL, "suffix tokens present but suffix_emb is null");
+    if (!b->cand_emb && b->cand_off && b->cand_off[n] > 0) return fail(RELAYGR_EINVAL, "candidates present but cand_emb is null");
+    if (!scores) return fail(RELAYGR_EINVAL, "scores_dev is null");
+  }
+
+  // -- attention work items: new-row tiles first (kept when the last layer skips prefix rows),
+  //    each group sorted by key-tile count, longest first
+  std::vector<AttnTile> tiles_new, tiles_prefix;
+  int min_key_tiles = 1 << 30;
+  for (int u = 0; u < n; ++u) {
+    const UserDesc& ud = users[u];
+    int Tn = ud.S + ud.M;
+    if (ud.nrow0 >= 0)
+      for (int t0 = 0; t0 < Tn; t0 += rpt) {
+        AttnTile at = {u, ud.nrow0 + t0, std::min(rpt, Tn - t0), 1, t0, {0, 0, 0}};
+        tiles_new.push_back(at);
+        min_key_tiles = std::min(min_key_tiles, (ud.L + kTile - 1) / kTile + (ud.S + kTile - 1) / kTile);
+      }
+    if (ud.prow0 >= 0)
+      for (int i0 = 0; i0 < ud.L; i0 += rpt) {
+        AttnTile at = {u, ud.prow0 + i0, std::min(rpt, ud.L - i0), 0, i0, {0, 0, 0}};
+        tiles_prefix.push_back(at);
+      }
+  }
+  auto key_tiles = [&](const AttnTile& a) {
+    const UserDesc& ud = users[a.user];
+    return a.kind == 0 ? (a.pos0 + a.nrows + kTile - 1) / kTile : (ud.L + kTile - 1) / kTile + (ud.S + kTile - 1) / kTile;
+  };
+  auto by_cost = [&](const AttnTile& a, const AttnTile& b2) { return key_tiles(a) > key_tiles(b2); };
+  std::stable_sort(tiles_new.begin(), tiles_new.end(), by_cost);
+  std::stable_sort(tiles_prefix.begin(), tiles_prefix.end(), by_cost);
+  p.n_tiles_new = (int)tiles_new.size();
+  p.n_tiles_prefix = (int)tiles_prefix.size();
+  const int n_tiles_all = p.n_tiles_new + p.n_tiles_prefix;
+  if (tiles_prefix.size()) min_key_tiles = 1;   // the first causal tile has a single key tile
+  if (min_key_tiles == (1 << 30)) min_key_tiles = 1;
+
+  // -- scratch
+  p.nsplit = wanted_splits(n_tiles_all, H, min_key_tiles);
+  carve(cfg, p);
+  while (p.total > c->scratch_bytes && p.nsplit > 1) { p.nsplit -= 1; carve(cfg, p); }
+  if (p.total > c->scratch_bytes)
+    return fail(RELAYGR_ENOSPC, "scratch too small: call needs %zu bytes, context has %zu", p.total, c->scratch_bytes);
+  char* S0 = c->scratch;
+  float* x = (float*)(S0 + p.off_x);
+  T* xh = (T*)(S0 + p.off_xh);
+  T* ubuf = (T*)(S0 + p.off_u);
+  T* qbuf = (T*)(S0 + p.off_q);
+  T* knew = (T*)(S0 + p.off_knew);
+  T* vnew = (T*)(S0 + p.off_vnew);
+  T* sfx = (T*)(S0 + p.off_sfx);
+  T* kvs = (T*)(S0 + p.off_kvs);
+  float* part = (float*)(S0 + p.off_part);
+  RowTables rt;
+  {
+    size_t rb = align_up((size_t)p.n_rows * 4);
+    char* r0 = S0 + p.off_rows;
+    rt.user = (int32_t*)r0; rt.kind = (int32_t*)(r0 + rb); rt.idx = (int32_t*)(r0 + 2 * rb);
+    rt.lim = (int32_t*)(r0 + 3 * rb); rt.src = (int32_t*)(r0 + 4 * rb);
+  }
+  for (int u = 0; u < n; ++u)
+    if (!users[u].kv) users[u].kv = kvs;
+
+  // -- descriptor blob: users | pstart | nstart | tiles(new, prefix)
+  StagingSlot* slot;
+  int rc = staging_acquire(c, p.blob_bytes, &slot);
+  if (rc != RELAYGR_OK) return rc;
+  size_t o_users = 0, o_ps = align_up((size_t)n * sizeof(UserDesc)), o_ns = o_ps + align_up((size_t)(n + 1) * 4),
+         o_tiles = o_ns + align_up((size_t)(n + 1) * 4);
+  char* hb = (char*)slot->host;
+  memcpy(hb + o_users, users.data(), (size_t)n * sizeof(UserDesc));
+  memcpy(hb + o_ps, pstart.data(), (size_t)(n + 1) * 4);
+  memcpy(hb + o_ns, nstart.data(), (size_t)(n + 1) * 4);
+  if (p.n_tiles_new) memcpy(hb + o_tiles, tiles_new.data(), tiles_new.size() * sizeof(AttnTile));
+  if (p.n_tiles_prefix) memcpy(hb + o_tiles + tiles_new.size() * sizeof(AttnTile), tiles_prefix.data(), tiles_prefix.size() * sizeof(AttnTile));
+  char* db = S0 + p.off_blob;
+  HIP_TRY(hipMemcpyAsync(db, hb, p.blob_bytes, hipMemcpyHostToDevice, st));
+  HIP_TRY(hipEventRecord(slot->done, st));
+  slot->pending = true;
+  const UserDesc* d_users = (const UserDesc*)(db + o_users);
+  const int32_t* d_ps = (const int32_t*)(db + o_ps);
+  const int32_t* d_ns = (const int32_t*)(db + o_ns);
+  const AttnTile* d_tiles = (const AttnTile*)(db + o_tiles);
+
+  hipLaunchKernelGGL(build_rows_kernel, dim3((p.n_rows + 255) / 256), dim3(256), 0, st, d_users, d_ps, d_ns, n, p.n_prows, p.n_rows, rt);
+  LAUNCH_CHECK("build_rows");
+  if (p.n_prows) {
+    hipLaunchKernelGGL((zero_kv_tail_kernel<T>), dim3(n), dim3(256), 0, st, d_users, n, NL, H, dh);
+    LAUNCH_CHECK("zero_kv_tail");
+  }
+  if (p.sfx_tiles) {
+    hipLaunchKernelGGL((zero_suffix_tail_kernel<T>), dim3(n), dim3(256), 0, st, d_users, n, sfx, H, dh);
+    LAUNCH_CHECK("zero_suffix_tail");
+  }
+
+  const float alpha = 1.0f / sqrtf((float)dh);
+  const float kLog2e = 1.4426950408889634f, kLn2 = 0.69314718055994531f;
+  const float q_mul = bf16 ? alpha * kLog2e : 1.0f;       // what f1 multiplies q by before storing it
+  const float score_mul = bf16 ? 1.0f : alpha;            // what the attention kernel still applies
+  const float gate_mul = bf16 ? kLn2 : alpha;             // stored q . k  ->  alpha <q,k> for the self term
+  const T* emb_p = (const T*)b->prefix_emb;
+  const T* emb_s = (const T*)b->suffix_emb;
+  const T* emb_c = (const T*)b->cand_emb;
+  const int R = p.n_rows;
+
+  for (int l = 0; l < NL; ++l) {
+    const relaygr_layer_weights& lw = c->layers[l];
+    const bool last = (l == NL - 1);
+    // rows whose layer output is still needed: in the last layer prefix rows only supply K and V
+    const int a0 = last ? p.n_prows : 0;
+    const bool have_active = a0 < R;
+
+    // step 1: input LayerNorm (first layer also gathers the embeddings into the residual stream)
+    {
+      dim3 grid((R + kRowsPerBlock - 1) / kRowsPerBlock);
+      bool ok = dispatch_e(d, [&](auto e) {
+        constexpr int E = decltype(e)::value;
+        if (l == 0)
+          hipLaunchKernelGGL((ln_in_kernel<T, E, true>), grid, dim3(256), 0, st, x, xh, (const T*)lw.ln_in_g, (const T*)lw.ln_in_b,
+                             emb_p, emb_s, emb_c, rt, 0, R, cfg.ln_eps);
+        else
+          hipLaunchKernelGGL((ln_in_kernel<T, E, false>), grid, dim3(256), 0, st, x, xh, (const T*)lw.ln_in_g, (const T*)lw.ln_in_b,
+                             emb_p, emb_s, emb_c, rt, 0, R, cfg.ln_eps);
+      });
+      if (!ok) return fail(RELAYGR_EINVAL, "unsupported d_model");
+      LAUNCH_CHECK("ln_in");
+    }
+    // step 2: projections
+    F1Epilogue<T> e1;
+    e1.bias = (const T*)lw.b1; e1.u = ubuf; e1.q = qbuf; e1.knew = knew; e1.vnew = vnew; e1.sfx = sfx;
+    e1.users = d_users; e1.rt = rt; e1.d = d; e1.dh = dh; e1.n_prows = p.n_prows; e1.layer = l; e1.q_mul = q_mul;
+    ColMap all4 = {4, {0, 1, 2, 3}, d}, kv_only = {2, {1, 3, 0, 0}, d};
+    if (last && p.n_prows) {
+      GemmLaunch<T>::run(xh, (const T*)lw.w1, d, 0, p.n_prows, kv_only, e1, st);
+      LAUNCH_CHECK("f1 (k,v only)");
+    }
+    if (have_active) {
+      GemmLaunch<T>::run(xh, (const T*)lw.w1, d, a0, R, all4, e1, st);
+      LAUNCH_CHECK("f1");
+    }
+    if (!have_active) continue;
+    // step 3: attention partial sums
+    AttnParams ap;
+    ap.tiles = d_tiles; ap.users = d_users; ap.rt = rt; ap.q = qbuf; ap.sfx = sfx; ap.part = part;
+    ap.split_stride = (size_t)R * d; ap.nsplit = p.nsplit; ap.d = d; ap.n_heads = H; ap.layer = l; ap.score_mul = score_mul;
+    int nt = last ? p.n_tiles_new : n_tiles_all;
+    if (nt > 0) {
+      rc = launch_attention<T>(cfg, ap, nt, st);
+      if (rc != RELAYGR_OK) return rc;
+    }
+    // steps 3-4: combine splits, self term, 1/n, LayerNorm, gate by u
+    {
+      dim3 grid((R - a0 + kRowsPerBlock - 1) / kRowsPerBlock);
+      dispatch_e(d, [&](auto e) {
+        constexpr int E = decltype(e)::value;
+        hipLaunchKernelGGL((attn_gate_kernel<T, E>), grid, dim3(256), 0, st, part, p.nsplit, (size_t)R * d, ubuf, qbuf, knew, vnew, xh,
+                           (const T*)lw.ln_at_g, (const T*)lw.ln_at_b, rt, p.n_prows, a0, R, dh, gate_mul, cfg.ln_eps);
+      });
+      LAUNCH_CHECK("attn_gate");
+    }
+    // step 4: output projection and residual
+    F2Epilogue<T> e2;
+    e2.bias = (const T*)lw.b2; e2.x = x; e2.d = d;
+    ColMap one = {1, {0, 0, 0, 0}, d};
+    GemmLaunch<T>::run(xh, (const T*)lw.w2, d, a0, R, one, e2, st);
+    LAUNCH_CHECK("f2");
+  }
+
+  if (mode != kPrefill && p.n_nrows) {
+    dim3 grid((p.n_nrows + kRowsPerBlock - 1) / kRowsPerBlock);
+    dispatch_e(d, [&](auto e) {
+      constexpr int E = decltype(e)::value;
+      hipLaunchKernelGGL((score_kernel<T, E>), grid, dim3(256), 0, st, x, (const T*)c->ln_out_g, (const T*)c->ln_out_b,
+                         (const T*)c->w_score, c->b_score, rt, p.n_prows, R, cfg.ln_eps, scores);
+    });
+    LAUNCH_CHECK("score");
+  }
+  return RELAYGR_OK;
+}
+
+static int run(relaygr_ctx* c, relaygr_kv_pool* pool, const relaygr_batch* b, Mode mode, float* scores, void* stream) {
+  if (!c || !b) return fail(RELAYGR_EINVAL, "null context or batch");
+  if (b->n_users < 0) return fail(RELAYGR_EINVAL, "n_users < 0");
+  if (b->n_users == 0) return RELAYGR_OK;
+  int rc;
+  if ((rc = check_offsets(b->prefix_off, b->n_users, "prefix")) != RELAYGR_OK) return rc;
+  if ((rc = check_offsets(b->suffix_off, b->n_users, "suffix")) != RELAYGR_OK) return rc;
+  if ((rc = check_offsets(b->cand_off, b->n_users, "candidate")) != RELAYGR_OK) return rc;
+  KvPool* kp = reinterpret_cast<KvPool*>(pool);
+  if (kp) {
+    const relaygr_model_config &a = kp->cfg, &m = c->cfg;
+    if (a.n_layers != m.n_layers || a.d_model != m.d_model || a.n_heads != m.n_heads || a.dtype != m.dtype)
+      return fail(RELAYGR_EINVAL, "pool and context were created for different model shapes");
+  }
+  hipStream_t st = (hipStream_t)stream;
+  if (c->cfg.dtype == RELAYGR_DTYPE_FP32) return run_typed<float>(c, kp, b, mode, scores, st);
+  return run_typed<__hip_bfloat16>(c, kp, b, mode, scores, st);
+}
+
+extern "C" int relaygr_prefill_prefix(relaygr_ctx* ctx, relaygr_kv_pool* pool, const relaygr_batch* batch, void* hip_stream) {
+  if (!pool) return fail(RELAYGR_EINVAL, "prefill_prefix: null pool");
+  if (batch && !batch->handles) return fail(RELAYGR_EINVAL, "prefill_prefix: null handles");
+  return run(ctx, pool, batch, kPrefill, nullptr, hip_stream);
+}
+
+extern "C" int relaygr_rank_with_cache(relaygr_ctx* ctx, relaygr_kv_pool* pool, const relaygr_batch* batch, float* scores_dev,
+                                       void* hip_stream) {
+  return run(ctx, pool, batch, kRankCached, scores_dev, hip_stream);
+}
+
+extern "C" int relaygr_rank_full_recompute(relaygr_ctx* ctx, const relaygr_batch* batch, float* scores_dev, void* hip_stream) {
+  return run(ctx, nullptr, batch, kRankFull, scores_dev, hip_stream);
+}

@@ -1,0 +1,220 @@
+// Projection GEMMs of a layer (steps 2 and 4): C[rows, N] = A[rows, K] * W[N, K]^T, with the
+// layer's pointwise work fused into the epilogue.
+//   f1: SiLU(xh W1^T + b1), split into u | v | q | k; u and q go to row-major scratch, k and v of
+//       prefix / suffix rows are scattered straight into K/V tile layout (pool or scratch), k and
+//       v of candidate rows go to row-major scratch for the self term.
+//   f2: x <- x + y W2^T + b2 on the fp32 residual stream.
+// Both operands are K-contiguous (weights are output-major), which is what the bf16 MFMA wants:
+// every lane's 8-element fragment is one 16-byte load.
+#pragma once
+
+#include "common.h"
+
+namespace relaygr {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+// Which output column blocks (of width d) a launch produces: block j of the launch is block
+// blk[j] of the weight (f1 on last-layer prefix rows needs only v and k).
+struct ColMap {
+  int nblk;
+  int blk[4];
+  int d;   // block width
+};
+
+// ---- epilogues -------------------------------------------------------------------------------
+template <typename T>
+struct F1Epilogue {
+  const T* bias;
+  T* u; T* q; T* knew; T* vnew; T* sfx;
+  const UserDesc* users;
+  RowTables rt;
+  int d, dh, n_prows, layer;
+  float q_mul;  // q is stored as q_mul * SiLU(.)
+
+  __device__ __forceinline__ void operator()(int r, int col, float acc) const {
+    float val = silu_f32(acc + Elem<T>::ld(bias + col));
+    int blk = col / d, c = col - blk * d;
+    if (blk == 0) { Elem<T>::st(u + (size_t)r * d + c, val); return; }
+    if (blk == 2) { Elem<T>::st(q + (size_t)r * d + c, val * q_mul); return; }
+    bool is_k = (blk == 3);
+    int kind = rt.kind[r];
+    if (kind == kRowCand) {
+      Elem<T>::st((is_k ? knew : vnew) + (size_t)(r - n_prows) * d + c, val);
+      return;
+    }
+    const UserDesc& ud = users[rt.user[r]];
+    int idx = rt.idx[r];
+    int h = c / dh, f = c - h * dh;
+    int64_t tile = idx / kTile;
+    int rr = idx % kTile;
+    T* base;
+    if (kind == kRowPrefix)
+      base = const_cast<T*>(reinterpret_cast<const T*>(ud.kv)) + ud.kv_tile0 + tile * ud.kv_tile_stride +
+             (int64_t)layer * ud.kv_layer_stride + (int64_t)h * 2 * kTile * dh;
+    else
+      base = sfx + ud.sfx_tile0 + tile * (int64_t)(2 * kTile * d) + (int64_t)h * 2 * kTile * dh;
+    if (is_k) Elem<T>::st(base + rr * dh + f, val);
+    else      Elem<T>::st(base + kTile * dh + f * kTile + rr, val);
+  }
+};
+
+template <typename T>
+struct F2Epilogue {
+  const T* bias;
+  float* x;
+  int d;
+  __device__ __forceinline__ void operator()(int r, int col, float acc) const {
+    size_t i = (size_t)r * d + col;
+    x[i] = x[i] + acc + Elem<T>::ld(bias + col);
+  }
+};
+
+// Workgroups are dispatched round-robin over the 8 XCDs, each with its own L2.  Give each XCD a
+// contiguous run of logical tiles (n fastest) so that the N-tiles sharing one A row-panel run on
+// the same XCD close together in time.
+__device__ __forceinline__ int xcd_remap(int id, int total) {
+  int chunk = (total + 7) >> 3;
+  return (id & 7) * chunk + (id >> 3);
+}
+
+// ---- bf16 MFMA GEMM: 128x128 tile, BK = 64, 4 wavefronts of 64x64 ---------------------------------
+constexpr int kGemmBM = 128, kGemmBN = 128, kGemmBK = 64, kGemmLd = kGemmBK + 8;
+
+template <class Epi>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(const __hip_bfloat16* __restrict__ A,
+                                                        const __hip_bfloat16* __restrict__ W, int K,
+                                                        int row_begin, int row_end, ColMap cm, int n_mtiles,
+                                                        Epi epi) {
+  __shared__ __attribute__((aligned(16))) uint16_t As[kGemmBM * kGemmLd];
+  __shared__ __attribute__((aligned(16))) uint16_t Bs[kGemmBN * kGemmLd];
+  const int ntiles_per_blk = cm.d / kGemmBN;
+  const int n_ntiles = cm.nblk * ntiles_per_blk;
+  const int total = n_mtiles * n_ntiles;
+  int logical = xcd_remap(blockIdx.x, total);
+  if (logical >= total) return;
+  const int mt = logical / n_ntiles, nt = logical - mt * n_ntiles;
+  const int m0 = row_begin + mt * kGemmBM;
+  const int n0 = cm.blk[nt / ntiles_per_blk] * cm.d + (nt % ntiles_per_blk) * kGemmBN;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, g = lane >> 5;
+
+  // global -> register staging: 128 rows x 8 chunks of 16 B per operand, 4 chunks per thread
+  uint4 ra[4], rb[4];
+  const uint16_t* Ag = reinterpret_cast<const uint16_t*>(A);
+  const uint16_t* Wg = reinterpret_cast<const uint16_t*>(W);
+  auto load_tiles = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int c = tid + i * 256, row = c >> 3, kc = c & 7;
+      int ar = min(m0 + row, row_end - 1);
+      ra[i] = *reinterpret_cast<const uint4*>(Ag + (size_t)ar * K + k0 + kc * 8);
+      rb[i] = *reinterpret_cast<const uint4*>(Wg + (size_t)(n0 + row) * K + k0 + kc * 8);
+    }
+  };
+  auto store_tiles = [&]() {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int c = tid + i * 256, row = c >> 3, kc = c & 7;
+      *reinterpret_cast<uint4*>(&As[row * kGemmLd + kc * 8]) = ra[i];
+      *reinterpret_cast<uint4*>(&Bs[row * kGemmLd + kc * 8]) = rb[i];
+    }
+  };
+
+  f32x16_t acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  load_tiles(0);
+  for (int k0 = 0; k0 < K; k0 += kGemmBK) {
+    __syncthreads();
+    store_tiles();
+    __syncthreads();
+    if (k0 + kGemmBK < K) load_tiles(k0 + kGemmBK);
+#pragma unroll
+    for (int ks = 0; ks < kGemmBK / 16; ++ks) {
+      bf16x8_t af[2], bf[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        af[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(&As[(wm * 64 + i * 32 + l32) * kGemmLd + ks * 16 + g * 8]));
+        bf[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(&Bs[(wn * 64 + i * 32 + l32) * kGemmLd + ks * 16 + g * 8]));
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+    }
+  }
+
+  // accumulator element e of a 32x32 block: row 8*(e/4) + 4*(lane/32) + e%4, column lane%32
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        int r = m0 + wm * 64 + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
+        int c = n0 + wn * 64 + j * 32 + l32;
+        if (r < row_end) epi(r, c, acc[i][j][e]);
+      }
+}
+
+// ---- fp32 GEMM: 64x64 tile, BK = 16, 4x4 outputs per thread ---------------------------------------
+constexpr int kSgemmBM = 64, kSgemmBN = 64, kSgemmBK = 16;
+
+template <class Epi>
+__global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__ A, const float* __restrict__ W, int K,
+                                                       int row_begin, int row_end, ColMap cm, int n_mtiles, Epi epi) {
+  __shared__ float As[kSgemmBK][kSgemmBM + 4];
+  __shared__ float Bs[kSgemmBK][kSgemmBN + 4];
+  const int ntiles_per_blk = cm.d / kSgemmBN;
+  const int n_ntiles = cm.nblk * ntiles_per_blk;
+  const int total = n_mtiles * n_ntiles;
+  int logical = blockIdx.x;
+  if (logical >= total) return;
+  const int mt = logical / n_ntiles, nt = logical - mt * n_ntiles;
+  const int m0 = row_begin + mt * kSgemmBM;
+  const int n0 = cm.blk[nt / ntiles_per_blk] * cm.d + (nt % ntiles_per_blk) * kSgemmBN;
+  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+  float acc[4][4] = {};
+  for (int k0 = 0; k0 < K; k0 += kSgemmBK) {
+    // 64 rows x 16 k per operand = 1024 elements, 4 per thread (one float4 along k)
+    {
+      int row = tid >> 2, kc = (tid & 3) * 4;
+      int ar = min(m0 + row, row_end - 1);
+      float4 a = *reinterpret_cast<const float4*>(A + (size_t)ar * K + k0 + kc);
+      float4 b = *reinterpret_cast<const float4*>(W + (size_t)(n0 + row) * K + k0 + kc);
+      As[kc + 0][row] = a.x; As[kc + 1][row] = a.y; As[kc + 2][row] = a.z; As[kc + 3][row] = a.w;
+      Bs[kc + 0][row] = b.x; Bs[kc + 1][row] = b.y; Bs[kc + 2][row] = b.z; Bs[kc + 3][row] = b.w;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < kSgemmBK; ++kk) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { a[i] = As[kk][ty * 4 + i]; b[i] = Bs[kk][tx * 4 + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int r = m0 + ty * 4 + i, c = n0 + tx * 4 + j;
+      if (r < row_end) epi(r, c, acc[i][j]);
+    }
+}
+
+}  // namespace relaygr

@@ -1,0 +1,210 @@
+// Row-wise kernels: row-table construction, the three LayerNorm sites, the attention
+// combine + gate, and the score head.  One 64-lane wavefront owns one row of d = 64*E features;
+// lane l holds features [l*E, l*E + E).
+#pragma once
+
+#include "common.h"
+
+namespace relaygr {
+
+constexpr int kRowsPerBlock = 4;  // wavefronts (rows) per 256-thread workgroup
+
+// ---- row tables ------------------------------------------------------------------------------
+// pstart / nstart: n_users + 1 row boundaries of the prefix rows and of the new rows.
+__global__ void build_rows_kernel(const UserDesc* __restrict__ users, const int32_t* __restrict__ pstart,
+                                  const int32_t* __restrict__ nstart, int n_users, int n_prows, int n_rows,
+                                  RowTables rt) {
+  int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= n_rows) return;
+  const int32_t* start = (r < n_prows) ? pstart : nstart;
+  int lo = 0, hi = n_users;  // find u with start[u] <= r < start[u+1]
+  while (hi - lo > 1) {
+    int mid = (lo + hi) >> 1;
+    if (start[mid] <= r) lo = mid; else hi = mid;
+  }
+  const UserDesc& ud = users[lo];
+  int kind, idx, lim, src;
+  if (r < n_prows) {
+    idx = r - start[lo];
+    kind = kRowPrefix; lim = idx + 1; src = ud.prefix_src0 + idx;
+  } else {
+    int t = r - start[lo];
+    if (t < ud.S) { kind = kRowSuffix; idx = t; lim = ud.L + t + 1; src = ud.suffix_src0 + t; }
+    else          { kind = kRowCand; idx = t - ud.S; lim = ud.L + ud.S; src = ud.cand_src0 + idx; }
+  }
+  rt.user[r] = lo; rt.kind[r] = kind; rt.idx[r] = idx; rt.lim[r] = lim; rt.src[r] = src;
+}
+
+// ---- LayerNorm helpers -----------------------------------------------------------------------
+template <int E>
+__device__ __forceinline__ void ln_stats(const float (&v)[E], int d, float eps, float& mean, float& rstd) {
+  float s = 0.f;
+#pragma unroll
+  for (int e = 0; e < E; ++e) s += v[e];
+  mean = wave_sum(s) / (float)d;
+  float q = 0.f;
+#pragma unroll
+  for (int e = 0; e < E; ++e) { float c = v[e] - mean; q += c * c; }
+  rstd = rsqrtf(wave_sum(q) / (float)d + eps);
+}
+
+// Input LayerNorm of a layer (step 1 of a layer): xh = LN(x; g, b) in the storage type.
+// With GATHER (first layer) the row is first fetched from its embedding array and also written to
+// the fp32 residual stream x.
+template <typename T, int E, bool GATHER>
+__global__ __launch_bounds__(256) void ln_in_kernel(float* __restrict__ x, T* __restrict__ xh,
+                                                    const T* __restrict__ gain, const T* __restrict__ offs,
+                                                    const T* __restrict__ emb_prefix, const T* __restrict__ emb_suffix,
+                                                    const T* __restrict__ emb_cand, RowTables rt,
+                                                    int row_begin, int row_end, float eps) {
+  const int d = 64 * E;
+  int r = row_begin + blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
+  if (r >= row_end) return;
+  int lane = threadIdx.x & 63;
+  float v[E];
+  if (GATHER) {
+    int kind = rt.kind[r];
+    const T* e = (kind == kRowPrefix ? emb_prefix : kind == kRowSuffix ? emb_suffix : emb_cand) + (size_t)rt.src[r] * d + lane * E;
+#pragma unroll
+    for (int i = 0; i < E; ++i) { v[i] = Elem<T>::ld(e + i); x[(size_t)r * d + lane * E + i] = v[i]; }
+  } else {
+#pragma unroll
+    for (int i = 0; i < E; ++i) v[i] = x[(size_t)r * d + lane * E + i];
+  }
+  float mean, rstd;
+  ln_stats<E>(v, d, eps, mean, rstd);
+#pragma unroll
+  for (int i = 0; i < E; ++i) {
+    int f = lane * E + i;
+    Elem<T>::st(xh + (size_t)r * d + f, (v[i] - mean) * rstd * Elem<T>::ld(gain + f) + Elem<T>::ld(offs + f));
+  }
+}
+
+// Attention combine + gate (steps 3-4 of a layer, everything after the key loop):
+//   o_i = ( sum over key splits of the partial sums  +  self term for a candidate ) / n_i
+//   y_i = LN(o_i; g_at, b_at) * u_i
+// part holds nsplit unnormalised partial sums [nsplit][rows][d] of SiLU(alpha q.k) v over the key
+// sequence, added here in split order (fixed order => reproducible bits).  A candidate's self
+// term SiLU(alpha <q_c^h, k_c^h>) v_c^h is evaluated here from the row's own q, k, v.
+// qk_mul turns the stored q into alpha*q (q may be stored pre-scaled).
+template <typename T, int E>
+__global__ __launch_bounds__(256) void attn_gate_kernel(const float* __restrict__ part, int nsplit, size_t split_stride,
+                                                        const T* __restrict__ u, const T* __restrict__ q,
+                                                        const T* __restrict__ knew, const T* __restrict__ vnew,
+                                                        T* __restrict__ y, const T* __restrict__ gain,
+                                                        const T* __restrict__ offs, RowTables rt, int n_prows,
+                                                        int row_begin, int row_end, int dh, float qk_mul, float eps) {
+  const int d = 64 * E;
+  int r = row_begin + blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
+  if (r >= row_end) return;
+  int lane = threadIdx.x & 63;
+  size_t base = (size_t)r * d + lane * E;
+  float o[E];
+#pragma unroll
+  for (int i = 0; i < E; ++i) o[i] = 0.f;
+  for (int s = 0; s < nsplit; ++s) {
+#pragma unroll
+    for (int i = 0; i < E; ++i) o[i] += part[s * split_stride + base + i];
+  }
+  int n = rt.lim[r];
+  if (rt.kind[r] == kRowCand) {
+    size_t nb = (size_t)(r - n_prows) * d + lane * E;
+    float dot = 0.f;
+#pragma unroll
+    for (int i = 0; i < E; ++i) dot += Elem<T>::ld(q + base + i) * Elem<T>::ld(knew + nb + i);
+    // lanes of one head are dh/E consecutive lanes (a power of two): segmented butterfly
+    for (int m = (dh / E) >> 1; m > 0; m >>= 1) dot += __shfl_xor(dot, m, 64);
+    float p = silu_f32(dot * qk_mul);
+#pragma unroll
+    for (int i = 0; i < E; ++i) o[i] += p * Elem<T>::ld(vnew + nb + i);
+    n += 1;
+  }
+  float inv_n = 1.0f / (float)n;
+#pragma unroll
+  for (int i = 0; i < E; ++i) o[i] *= inv_n;
+  float mean, rstd;
+  ln_stats<E>(o, d, eps, mean, rstd);
+#pragma unroll
+  for (int i = 0; i < E; ++i) {
+    int f = lane * E + i;
+    float z = (o[i] - mean) * rstd * Elem<T>::ld(gain + f) + Elem<T>::ld(offs + f);
+    Elem<T>::st(y + base + i, z * Elem<T>::ld(u + base + i));
+  }
+}
+
+// Score head: score_c = <w_s, LN(x_c; g_out, b_out)> + b_s for candidate rows, written at the
+// candidate's position in the caller's candidate order.
+template <typename T, int E>
+__global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ x, const T* __restrict__ gain,
+                                                    const T* __restrict__ offs, const T* __restrict__ w_score,
+                                                    float b_score, RowTables rt, int row_begin, int row_end,
+                                                    float eps, float* __restrict__ scores) {
+  const int d = 64 * E;
+  int r = row_begin + blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
+  if (r >= row_end) return;
+  if (rt.kind[r] != kRowCand) return;
+  int lane = threadIdx.x & 63;
+  float v[E];
+#pragma unroll
+  for (int i = 0; i < E; ++i) v[i] = x[(size_t)r * d + lane * E + i];
+  float mean, rstd;
+  ln_stats<E>(v, d, eps, mean, rstd);
+  float acc = 0.f;
+#pragma unroll
+  for (int i = 0; i < E; ++i) {
+    int f = lane * E + i;
+    acc += ((v[i] - mean) * rstd * Elem<T>::ld(gain + f) + Elem<T>::ld(offs + f)) * Elem<T>::ld(w_score + f);
+  }
+  acc = wave_sum(acc);
+  if (lane == 0) scores[rt.src[r]] = acc + b_score;
+}
+
+// Zero the unused token slots of each computed prefix's last K/V tile (all layers this call
+// writes), so that a ragged tile never holds stale non-finite bits: 0 * NaN would otherwise
+// reach the accumulators through the masked-out keys.
+template <typename T>
+__global__ void zero_kv_tail_kernel(const UserDesc* __restrict__ users, int n_users, int n_layers, int n_heads, int dh) {
+  int u = blockIdx.x;
+  if (u >= n_users) return;
+  const UserDesc ud = users[u];
+  if (ud.prow0 < 0) return;
+  int tail0 = ud.L % kTile;
+  if (tail0 == 0) return;
+  int64_t tile = ud.L / kTile;
+  int layers = ud.kv_layer_stride ? n_layers : 1;
+  int per_head = (kTile - tail0) * dh;  // elements of K (and of V) to clear per layer and head
+  T* base = const_cast<T*>(reinterpret_cast<const T*>(ud.kv)) + ud.kv_tile0 + tile * ud.kv_tile_stride;
+  int total = layers * n_heads * per_head;
+  for (int i = threadIdx.x; i < total; i += blockDim.x) {
+    int lh = i / per_head, w = i % per_head;
+    int layer = lh / n_heads, head = lh % n_heads;
+    T* kt = base + (int64_t)layer * ud.kv_layer_stride + (int64_t)head * 2 * kTile * dh;
+    int rr = tail0 + w / dh, f = w % dh;
+    Elem<T>::st(kt + rr * dh + f, 0.f);
+    Elem<T>::st(kt + kTile * dh + f * kTile + rr, 0.f);
+  }
+}
+
+// Same for the suffix tiles of every user with a suffix (single-layer scratch space).
+template <typename T>
+__global__ void zero_suffix_tail_kernel(const UserDesc* __restrict__ users, int n_users, T* __restrict__ sfx,
+                                        int n_heads, int dh) {
+  int u = blockIdx.x;
+  if (u >= n_users) return;
+  const UserDesc ud = users[u];
+  int tail0 = ud.S % kTile;
+  if (ud.nrow0 < 0 || tail0 == 0) return;
+  int64_t tile = ud.S / kTile;
+  int per_head = (kTile - tail0) * dh;
+  T* base = sfx + ud.sfx_tile0 + tile * (int64_t)(2 * kTile * dh * n_heads);
+  int total = n_heads * per_head;
+  for (int i = threadIdx.x; i < total; i += blockDim.x) {
+    int head = i / per_head, w = i % per_head;
+    T* kt = base + (int64_t)head * 2 * kTile * dh;
+    int rr = tail0 + w / dh, f = w % dh;
+    Elem<T>::st(kt + rr * dh + f, 0.f);
+    Elem<T>::st(kt + kTile * dh + f * kTile + rr, 0.f);
+  }
+}
+
+}  // namespace relaygr

@@ -1,0 +1,200 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Tolerance: max-abs error <= tol * max(1, max|oracle|), tol 1e-4 (fp32) / 2e-2 (bf16).
+
+Small cases span several key tiles (64 tokens), several row tiles (64 rows fp32 / 128 rows bf16)
+and ragged tails; the named benchmark shapes C1 and C2 run in full.  Each case checks the three
+routes to the same scores: ranking on the cached prefix, full recompute, and (where stated) a
+batch mixing cached and uncached users -- the paper's relay-race identity (Section 2.3) and miss
+fallback (Section 3.1, invariant I1).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2601_01712_amd as rg
+import synth
+from gpu_util import Harness, assert_close, build_case, oracle_scores, TOL
+from synth.generator import user_slices
+
+pytestmark = pytest.mark.gpu
+
+
+def run_three_routes(cfg, seed, L, S, M, page_tokens=64, miss=()):
+    weights, batch = build_case(cfg, seed, L, S, M)
+    want = oracle_scores(cfg, weights, batch)
+    h = Harness(cfg, weights, batch, page_tokens)
+    try:
+        hit = [u for u in range(len(L)) if L[u] > 0 and u not in miss]
+        if hit:
+            h.prefill(hit)
+        e1 = h.check(h.rank_cached(), want, "rank_with_cache")
+        e2 = h.check(h.rank_full(), want, "rank_full_recompute")
+        print(f"\n  {cfg.dtype} d={cfg.d_model} H={cfg.n_heads} NL={cfg.n_layers} L={list(L)} S={list(S)} M={list(M)}: "
+              f"max err cached {e1:.2e} full {e2:.2e} (bound {TOL[cfg.dtype]:.0e})", flush=True)
+    finally:
+        h.close()
+
+
+# ------------------------------------------------------------------------------------ fp32
+def test_c1_fp32_full():
+    wl = synth.WORKLOADS["C1"]
+    L, S, M, _ = synth.make_lengths(wl)
+    run_three_routes(wl.model, wl.seed, L, S, M)
+
+
+@pytest.mark.parametrize("L,S,M", [
+    ([1], [0], [1]), ([63], [0], [5]), ([64], [3], [70]), ([65, 130], [0, 7], [3, 64]),
+    ([200, 0, 77], [66, 2, 0], [65, 9, 129]),
+])
+def test_fp32_small_shapes(L, S, M):
+    run_three_routes(synth.ModelConfig(2, 64, 2, "fp32"), 40 + len(L), L, S, M)
+
+
+@pytest.mark.parametrize("d,H", [(128, 2), (128, 1), (256, 8)])
+def test_fp32_head_sizes(d, H):
+    run_three_routes(synth.ModelConfig(2, d, H, "fp32"), 50 + H, [150, 70], [5, 0], [20, 66])
+
+
+# ------------------------------------------------------------------------------------ bf16
+@pytest.mark.parametrize("L,S,M", [
+    ([1], [0], [1]), ([63], [0], [5]), ([64], [3], [130]), ([65, 300], [0, 70], [3, 129]),
+    ([513, 0, 128], [64, 2, 0], [257, 9, 1]), ([1000], [17], [400]),
+])
+def test_bf16_small_shapes(L, S, M):
+    run_three_routes(synth.ModelConfig(3, 128, 2, "bf16"), 60 + len(L), L, S, M)
+
+
+@pytest.mark.parametrize("d,H", [(128, 4), (256, 2), (256, 4), (512, 8), (1024, 8)])
+def test_bf16_head_sizes(d, H):
+    run_three_routes(synth.ModelConfig(2, d, H, "bf16"), 70 + H, [300, 129], [5, 0], [140, 66])
+
+
+def test_bf16_mixed_hits_and_misses_in_one_batch():
+    cfg = synth.ModelConfig(3, 256, 4, "bf16")
+    run_three_routes(cfg, 81, [400, 130, 64, 700, 257], [0, 30, 64, 3, 0], [200, 50, 129, 7, 300],
+                     page_tokens=128, miss=(1, 3))
+
+
+def test_c2_bf16_full():
+    wl = synth.WORKLOADS["C2"]
+    L, S, M, _ = synth.make_lengths(wl)
+    run_three_routes(wl.model, wl.seed, L, S, M, page_tokens=256)
+
+
+# ------------------------------------------------------------------- psi, independence, determinism
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_pool_contents_equal_oracle_psi(dtype):
+    """The cached object itself (Section 3.1): every layer's K and V of the prefix."""
+    cfg = synth.ModelConfig(3, 128, 2, dtype)
+    weights, batch = build_case(cfg, 91, [150, 64], [0, 0], [1, 1])
+    h = Harness(cfg, weights, batch, page_tokens=64)
+    try:
+        h.prefill()
+        el = h.pool.elements().float().cpu().numpy()
+        for u in range(2):
+            p, _, _ = user_slices(batch, u)
+            psi = oracle.prefix_kv(cfg, weights, p)
+            toks = sorted({0, 1, 62, 63, 64, len(p) - 1} & set(range(len(p))))
+            for l, (k, v) in enumerate(psi):
+                for t in toks:
+                    idx = [rg.relaygr_kv_pool_locate(h.pool, int(h.handles[u]), l, t, f) for f in range(cfg.d_model)]
+                    gk = el[[i[0] for i in idx]]
+                    gv = el[[i[1] for i in idx]]
+                    tol = 1e-5 if dtype == "fp32" else 1e-2
+                    np.testing.assert_allclose(gk, k[t].numpy(), rtol=tol, atol=tol * 0.3)
+                    np.testing.assert_allclose(gv, v[t].numpy(), rtol=tol, atol=tol * 0.3)
+    finally:
+        h.close()
+
+
+def test_prefill_is_deterministic_and_reranking_reuses_psi():
+    cfg = synth.ModelConfig(2, 256, 4, "bf16")
+    weights, batch = build_case(cfg, 93, [700, 300], [10, 0], [150, 40])
+    h = Harness(cfg, weights, batch, page_tokens=128)
+    try:
+        h.prefill()
+        snap = h.pool.slab.clone()
+        a = h.rank_cached()
+        b = h.rank_cached()
+        assert np.array_equal(a, b), "same inputs, same cache: scores must be bit-identical"
+        # pre-infer again into the same entries: the pool contents must not change by a bit
+        sub = h.sub_batch([0, 1])
+        sub.set_handles(h.handles)
+        rg.relaygr_prefill_prefix(h.ctx, h.pool, sub)
+        torch.cuda.synchronize()
+        assert torch.equal(snap, h.pool.slab)
+        # one cached prefix, a different candidate set (Section 3.1: psi does not depend on candidates)
+        wl2 = synth.Workload("other", cfg, seed=94, n_users=2, prefix_len=1, n_cands=1, n_suffix=0)
+        other = synth.make_batch(wl2, 0, lengths=([700, 300], [10, 0], [33, 90], np.ones(2, bool)))
+        mixed = dict(batch)
+        mixed["cand_emb"], mixed["cand_off"] = other["cand_emb"], other["cand_off"]
+        want = oracle_scores(cfg, weights, mixed)
+        db = rg.Batch(mixed, cfg.dtype, handles=h.handles)
+        got = rg.relaygr_rank_with_cache(h.ctx, h.pool, db).cpu().numpy()
+        for u in range(2):
+            assert_close(got[mixed["cand_off"][u]:mixed["cand_off"][u + 1]], want[u], "bf16", f"new candidates user {u}")
+    finally:
+        h.close()
+
+
+def test_candidates_and_users_are_independent_on_the_gpu():
+    cfg = synth.ModelConfig(2, 128, 2, "bf16")
+    weights, batch = build_case(cfg, 95, [200, 90], [4, 0], [70, 30])
+    h = Harness(cfg, weights, batch)
+    try:
+        h.prefill()
+        full = h.rank_cached()
+        # user 1 alone, and user 0's candidates in reversed order
+        only1 = h.sub_batch([1]); only1.set_handles([h.handles[1]])
+        s1 = rg.relaygr_rank_with_cache(h.ctx, h.pool, only1).cpu().numpy()
+        np.testing.assert_allclose(s1, full[70:], rtol=0, atol=1e-6)
+        rev = dict(batch)
+        ce = batch["cand_emb"].copy(); ce[:70] = ce[:70][::-1]
+        rev["cand_emb"] = ce
+        sr = rg.relaygr_rank_with_cache(h.ctx, h.pool, rg.Batch(rev, cfg.dtype, handles=h.handles)).cpu().numpy()
+        np.testing.assert_allclose(sr[:70][::-1], full[:70], rtol=0, atol=2e-3)
+    finally:
+        h.close()
+
+
+# ---------------------------------------------------------------------------- failure handling
+def test_stale_handle_is_reported_and_fallback_gives_the_same_scores():
+    """Section 3.3: when the cache is gone the instance falls back to inference without cache."""
+    cfg = synth.ModelConfig(2, 128, 2, "bf16")
+    weights, batch = build_case(cfg, 97, [130, 260], [0, 5], [20, 40])
+    want = oracle_scores(cfg, weights, batch)
+    h = Harness(cfg, weights, batch)
+    try:
+        h.prefill()
+        stale = int(h.handles[0])
+        rg.relaygr_kv_pool_free(h.pool, stale)
+        with pytest.raises(rg.RelayGRError) as e:
+            h.rank_cached()
+        assert e.value.code == rg.RELAYGR_ENOENT
+        assert rg.relaygr_kv_pool_lookup(h.pool, int(batch["user_ids"][0])) == rg.RELAYGR_NO_CACHE
+        h.handles[0] = rg.RELAYGR_NO_CACHE          # the caller's fallback
+        h.check(h.rank_cached(), want, "after fallback")
+        # a pool that is full says so; ranking that user uncached still works
+        with pytest.raises(rg.RelayGRError) as e:
+            rg.relaygr_kv_pool_alloc(h.pool, 424242, 100000)
+        assert e.value.code == rg.RELAYGR_ENOSPC
+        # wrong prefix length for a live handle is an argument error
+        bad = dict(batch); po = batch["prefix_off"].copy(); po[2] -= 1; bad["prefix_off"] = po
+        with pytest.raises(rg.RelayGRError) as e:
+            rg.relaygr_rank_with_cache(h.ctx, h.pool, rg.Batch(bad, cfg.dtype, handles=h.handles))
+        assert e.value.code == rg.RELAYGR_EINVAL
+    finally:
+        h.close()
+
+
+def test_scratch_too_small_is_an_error_not_a_fault():
+    cfg = synth.ModelConfig(2, 128, 2, "bf16")
+    weights, batch = build_case(cfg, 98, [500], [0], [50])
+    ctx = rg.Context(cfg, weights, 1, 64, 64)     # sized for a much smaller call
+    try:
+        with pytest.raises(rg.RelayGRError) as e:
+            rg.relaygr_rank_full_recompute(ctx, rg.Batch(batch, cfg.dtype))
+        assert e.value.code == rg.RELAYGR_ENOSPC
+    finally:
+        ctx.close()
