@@ -191,6 +191,26 @@ int  relaygr_rank_with_cache(relaygr_ctx* ctx, relaygr_kv_pool* pool, const rela
 int  relaygr_rank_full_recompute(relaygr_ctx* ctx, const relaygr_batch* batch,
                                  float* scores_dev, void* hip_stream);
 
+/* ---- measurement ---------------------------------------------------------------------- */
+
+/* Kernel classes of the layer sequence, for per-kernel timing. */
+#define RELAYGR_K_SETUP 0   /* row tables, tail clearing                       */
+#define RELAYGR_K_LN    1   /* input LayerNorm (and first-layer gather)        */
+#define RELAYGR_K_F1    2   /* u|v|q|k projection GEMM + SiLU + K/V scatter     */
+#define RELAYGR_K_ATTN  3   /* pointwise-SiLU attention over the key sequence   */
+#define RELAYGR_K_GATE  4   /* split combine, self term, 1/n, LayerNorm, gate   */
+#define RELAYGR_K_F2    5   /* output projection GEMM + residual                */
+#define RELAYGR_K_SCORE 6   /* final LayerNorm + score head                     */
+#define RELAYGR_K_COUNT 7
+
+/* Turns per-launch timing on for the classes in class_mask (bit k = class k; 0 turns it off) and
+ * clears the accumulated figures.  While on, each launch of a selected class is bracketed by a
+ * pair of HIP events recorded on the call's stream. */
+int  relaygr_ctx_profile_enable(relaygr_ctx* ctx, uint32_t class_mask);
+/* Waits for the recorded events and returns the summed kernel time (milliseconds) and the number
+ * of launches of one class since the last enable.  Synchronises with the GPU. */
+int  relaygr_ctx_profile_read(relaygr_ctx* ctx, int32_t kernel_class, double* total_ms, int64_t* launches);
+
 /* Text of the calling thread's last failure ("" if none).  Valid until the thread's next call. */
 const char* relaygr_last_error(void);
 

@@ -27,8 +27,10 @@ EXPORTS = [
     "relaygr_kv_pool_create", "relaygr_kv_pool_destroy", "relaygr_kv_pool_alloc", "relaygr_kv_pool_free",
     "relaygr_kv_pool_lookup", "relaygr_kv_pool_entry_len", "relaygr_kv_pool_stats", "relaygr_kv_pool_locate",
     "relaygr_prefill_prefix", "relaygr_rank_with_cache", "relaygr_rank_full_recompute",
+    "relaygr_ctx_profile_enable", "relaygr_ctx_profile_read",
     "relaygr_last_error",
 ]
+KERNEL_CLASSES = ["setup", "ln", "f1", "attn", "gate", "f2", "score"]
 
 
 class ModelConfigC(C.Structure):
@@ -91,6 +93,8 @@ def load_library() -> C.CDLL:
         "relaygr_prefill_prefix": (C.c_int, [vp, vp, P(BatchC), vp]),
         "relaygr_rank_with_cache": (C.c_int, [vp, vp, P(BatchC), vp, vp]),
         "relaygr_rank_full_recompute": (C.c_int, [vp, P(BatchC), vp, vp]),
+        "relaygr_ctx_profile_enable": (C.c_int, [vp, C.c_uint32]),
+        "relaygr_ctx_profile_read": (C.c_int, [vp, i32, P(C.c_double), P(i64)]),
         "relaygr_last_error": (C.c_char_p, []),
     }
     for name, (res, args) in sig.items():
@@ -183,6 +187,20 @@ class Context:
             self.close()
         except Exception:
             pass
+
+
+def relaygr_ctx_profile_enable(ctx: Context, classes: Sequence[str]) -> None:
+    mask = 0
+    for c in classes:
+        mask |= 1 << KERNEL_CLASSES.index(c)
+    _check(load_library().relaygr_ctx_profile_enable(ctx.handle, mask))
+
+
+def relaygr_ctx_profile_read(ctx: Context, kernel_class: str):
+    """(total milliseconds, launches) of one kernel class since profiling was enabled."""
+    ms, n = C.c_double(), C.c_int64()
+    _check(load_library().relaygr_ctx_profile_read(ctx.handle, KERNEL_CLASSES.index(kernel_class), C.byref(ms), C.byref(n)))
+    return ms.value, n.value
 
 
 class KvPool:

@@ -114,21 +114,82 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(AttnParams p) {
 // user and one head and walks the key tiles of its split.  Per 64-key tile and wavefront:
 //   S^T[64 keys][32 rows]  = K tile (A operand, rows = keys)  x  Q^T (B operand, held in registers)
 //   P^T = SiLU'(S^T) rounded to bf16 -- the accumulator layout of S^T (lane = row, 4-key runs) is
-//         exactly the B-operand layout of the next product once the V fragment is read with the
-//         same key permutation, so P never leaves registers
+//         exactly the B-operand layout of the next product once the V fragment holds the same key
+//         permutation (it does, see the layout note in common.h), so P never leaves registers
 //   O^T[dh][32 rows]      += V^T tile (A operand, rows = features) x P^T
 // q is stored pre-multiplied by alpha*log2(e); SiLU'(t) = t / (1 + 2^-t) = SiLU(s)/ln 2 with
 // s = t ln 2, and the ln 2 is applied once to the output.
-constexpr int kAttnKLd = 8;   // bf16 elements of padding per LDS row
+//
+// A K/V tile in HBM is already the LDS image (fragment order), so tiles stream HBM -> LDS with
+// direct 16-byte-per-lane loads into a double buffer, one barrier per tile, and every MFMA operand
+// is one linear ds_read_b128.  The arithmetic that bounds this kernel is the SiLU: one v_exp_f32
+// and one v_rcp_f32 (quarter-rate) plus add, multiply and a packed bf16 convert per score element,
+// against 2*DH/32 MFMA passes; everything else in the loop is kept off the vector ALU.
+
+template <int DH, int NQ, bool MASKED>
+__device__ __forceinline__ void attn_tile_step(const uint16_t* __restrict__ buf, const bf16x8_t (&qf)[NQ][DH / 16],
+                                               f32x16_t (&oacc)[DH / 32][NQ], const int (&vis)[NQ], int lane) {
+  constexpr int KS = DH / 16, DB = DH / 32;
+  const int g = lane >> 5;
+  const uint16_t* kfrag = buf + lane * 8;
+  const uint16_t* vfrag = buf + kTile * DH + lane * 8;
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb) {
+    f32x16_t s[NQ];
+#pragma unroll
+    for (int qb = 0; qb < NQ; ++qb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s[qb][e] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      bf16x8_t kf = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(kfrag + (kb * KS + ks) * 512));
+#pragma unroll
+      for (int qb = 0; qb < NQ; ++qb) s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], s[qb], 0, 0, 0);
+    }
+    // element e of s: key kb*32 + 8*(e/4) + 4*g + e%4 of the tile, row l32 of block qb
+    uint32_t pk[NQ][8];
+#pragma unroll
+    for (int qb = 0; qb < NQ; ++qb) {
+#pragma unroll
+      for (int e2 = 0; e2 < 8; ++e2) {
+        f32x2_t pv;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const int e = 2 * e2 + h;
+          float t = s[qb][e];
+          float pe = t * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-t));
+          if (MASKED) {
+            const int key = kb * 32 + 8 * (e >> 2) + (e & 3);   // + 4*g, folded into vis by the caller
+            pe = (key < vis[qb]) ? pe : 0.f;
+          }
+          pv[h] = pe;
+        }
+        pk[qb][e2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pv, bf16x2_t));   // one v_cvt_pk_bf16_f32
+      }
+    }
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        bf16x8_t vf = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(vfrag + ((db * 2 + kb) * 2 + m) * 512));
+#pragma unroll
+        for (int qb = 0; qb < NQ; ++qb) {
+          uint4 pp = make_uint4(pk[qb][4 * m], pk[qb][4 * m + 1], pk[qb][4 * m + 2], pk[qb][4 * m + 3]);
+          oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, __builtin_bit_cast(bf16x8_t, pp), oacc[db][qb], 0, 0, 0);
+        }
+      }
+    }
+  }
+  (void)g;
+}
 
 template <int DH, int NQ>
-__global__ __launch_bounds__(256) void attn_bf16_kernel(AttnParams p) {
-  constexpr int KLD = DH + kAttnKLd;      // K tile row stride (elements)
-  constexpr int VLD = kTile + kAttnKLd;   // V^T tile row stride
-  constexpr int KS = DH / 16;             // k-steps of the first product
-  constexpr int DB = DH / 32;             // 32-feature blocks of the output
-  __shared__ __attribute__((aligned(16))) uint16_t Ks[kTile * KLD];
-  __shared__ __attribute__((aligned(16))) uint16_t Vs[DH * VLD];
+__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p) {
+  constexpr int KS = DH / 16;              // k-steps of the first product
+  constexpr int DB = DH / 32;              // 32-feature blocks of the output
+  constexpr int TILE = 2 * kTile * DH;     // elements of one K tile + one V tile
+  constexpr int CHUNKS = TILE / 8 / 256;   // 16-byte chunks each thread moves per tile
+  __shared__ __attribute__((aligned(16))) uint16_t bufs[2][TILE];
 
   const AttnTile at = p.tiles[blockIdx.x];
   const int head = blockIdx.y, split = blockIdx.z;
@@ -160,98 +221,40 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnParams p) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) oacc[db][qb][e] = 0.f;
 
-  // global -> register staging of one K tile and one V^T tile: 64*DH*2 B each = DH/2 chunks of 16 B per thread pair
-  constexpr int CH = (kTile * DH) / (8 * 256);  // 16-byte chunks per thread per operand
-  uint4 rk[CH], rv[CH];
-  auto tile_src = [&](int tt) -> const uint16_t* {
-    if (tt < tr.nkp)
-      return reinterpret_cast<const uint16_t*>(ud.kv) + ud.kv_tile0 + (int64_t)tt * ud.kv_tile_stride +
-             (int64_t)p.layer * ud.kv_layer_stride + (int64_t)head * 2 * kTile * DH;
-    return reinterpret_cast<const uint16_t*>(p.sfx) + ud.sfx_tile0 + (int64_t)(tt - tr.nkp) * (2 * kTile * p.d) +
-           (int64_t)head * 2 * kTile * DH;
-  };
-  auto load_tile = [&](int tt) {
-    const uint4* src = reinterpret_cast<const uint4*>(tile_src(tt));
+  const uint16_t* kv_base = reinterpret_cast<const uint16_t*>(ud.kv) + ud.kv_tile0 + (int64_t)p.layer * ud.kv_layer_stride +
+                            (int64_t)head * TILE;
+  const uint16_t* sfx_base = reinterpret_cast<const uint16_t*>(p.sfx) + ud.sfx_tile0 + (int64_t)head * TILE;
+  const int64_t sfx_stride = (int64_t)2 * kTile * p.d;
+
+  // HBM -> LDS, no registers in between: wavefront w moves the 1 KiB pieces w, w+4, ... of the tile
+  auto issue_tile = [&](int tt, int b) {
+    const uint16_t* src = (tt < tr.nkp) ? kv_base + (int64_t)tt * ud.kv_tile_stride : sfx_base + (int64_t)(tt - tr.nkp) * sfx_stride;
 #pragma unroll
-    for (int i = 0; i < CH; ++i) {
-      rk[i] = src[tid + i * 256];
-      rv[i] = src[(kTile * DH) / 8 + tid + i * 256];
-    }
-  };
-  auto store_tile = [&]() {
-#pragma unroll
-    for (int i = 0; i < CH; ++i) {
-      int c = tid + i * 256;
-      int krow = c / (DH / 8), kc = c % (DH / 8);
-      *reinterpret_cast<uint4*>(&Ks[krow * KLD + kc * 8]) = rk[i];
-      int vrow = c / (kTile / 8), vc = c % (kTile / 8);
-      *reinterpret_cast<uint4*>(&Vs[vrow * VLD + vc * 8]) = rv[i];
+    for (int i = 0; i < CHUNKS; ++i) {
+      const int piece = i * 4 + wave;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + piece * 512 + lane * 8),
+                                       (__attribute__((address_space(3))) void*)(&bufs[b][piece * 512]), 16, 0, 0);
     }
   };
 
-  if (tr.t0 < tr.t1) load_tile(tr.t0);
+  if (tr.t0 < tr.t1) issue_tile(tr.t0, 0);
   for (int tt = tr.t0; tt < tr.t1; ++tt) {
-    __syncthreads();
-    store_tile();
-    __syncthreads();
-    if (tt + 1 < tr.t1) load_tile(tt + 1);
+    const int b = (tt - tr.t0) & 1;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();                                  // tile tt has landed; everyone is done with the other buffer
+    if (tt + 1 < tr.t1) issue_tile(tt + 1, b ^ 1);
 
     const bool is_sfx = tt >= tr.nkp;
-    const bool masked = is_sfx || tt >= tr.nfull;
-    const int key0 = is_sfx ? ud.L + (tt - tr.nkp) * kTile : tt * kTile;
-    const int seg_end = is_sfx ? ud.L + ud.S : ud.L;
-
+    if (!is_sfx && tt < tr.nfull) {
+      const int none[NQ] = {};
+      attn_tile_step<DH, NQ, false>(bufs[b], qf, oacc, none, lane);
+    } else {
+      const int key0 = is_sfx ? ud.L + (tt - tr.nkp) * kTile : tt * kTile;
+      const int seg_end = is_sfx ? ud.L + ud.S : ud.L;
+      int vis[NQ];   // keys [0, vis) of this tile are visible, shifted by this lane's 4*g key offset
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      f32x16_t s[NQ];
-#pragma unroll
-      for (int qb = 0; qb < NQ; ++qb)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) s[qb][e] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        bf16x8_t kf = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(&Ks[(kb * 32 + l32) * KLD + ks * 16 + g * 8]));
-#pragma unroll
-        for (int qb = 0; qb < NQ; ++qb) s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], s[qb], 0, 0, 0);
-      }
-      // element e of s: key kb*32 + 8*(e/4) + 4*g + e%4 of the tile, row l32 of block qb
-      uint32_t pk[NQ][8];
-#pragma unroll
-      for (int qb = 0; qb < NQ; ++qb) {
-        float pv[16];
-        const int vis = min(lim[qb], seg_end) - key0;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          float t = s[qb][e];
-          float pe = t * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-t));
-          if (masked) {
-            int key = kb * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
-            pe = (key < vis) ? pe : 0.f;
-          }
-          pv[e] = pe;
-        }
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-          pk[qb][e] = (uint32_t)float_to_bf16_bits(pv[2 * e]) | ((uint32_t)float_to_bf16_bits(pv[2 * e + 1]) << 16);
-      }
-      // second product, 16 keys per step: step m uses accumulator elements 8m .. 8m+7, i.e. keys
-      // kb*32 + 16m + 4g + {0..3} and kb*32 + 16m + 8 + 4g + {0..3}
-#pragma unroll
-      for (int m = 0; m < 2; ++m) {
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          const uint16_t* vr = &Vs[(db * 32 + l32) * VLD + kb * 32 + 16 * m + 4 * g];
-          uint2 lo = *reinterpret_cast<const uint2*>(vr);
-          uint2 hi = *reinterpret_cast<const uint2*>(vr + 8);
-          uint4 vv = make_uint4(lo.x, lo.y, hi.x, hi.y);
-          bf16x8_t vf = __builtin_bit_cast(bf16x8_t, vv);
-#pragma unroll
-          for (int qb = 0; qb < NQ; ++qb) {
-            uint4 pp = make_uint4(pk[qb][4 * m], pk[qb][4 * m + 1], pk[qb][4 * m + 2], pk[qb][4 * m + 3]);
-            oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, __builtin_bit_cast(bf16x8_t, pp), oacc[db][qb], 0, 0, 0);
-          }
-        }
-      }
+      for (int qb = 0; qb < NQ; ++qb) vis[qb] = min(lim[qb], seg_end) - key0 - 4 * g;
+      attn_tile_step<DH, NQ, true>(bufs[b], qf, oacc, vis, lane);
     }
   }
 

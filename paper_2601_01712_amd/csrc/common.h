@@ -9,13 +9,21 @@
 // comes from.  A candidate additionally sees itself; that term never enters the key sequence.
 //
 // Cached K/V layout.  Keys are stored in tiles of 64 tokens.  One tile block holds, for every
-// layer and head, a K tile [64 tokens][d_head] followed by a V tile stored transposed
-// [d_head][64 tokens] (the orientation the second MFMA of the attention wants):
-//     element(K; tile, layer, head, r, f) = tile*tile_stride + layer*layer_stride + head*128*dh + r*dh + f
-//     element(V; ...)                     = the same base + 64*dh + f*64 + r
+// layer and head, a K tile (64 tokens x d_head) followed by a V tile (d_head x 64 tokens):
+//     base(tile, layer, head) = tile*tile_stride + layer*layer_stride + head*128*dh
+//     K element (token r, feature f) at base + KvLayout::k_off(r, f, dh)
+//     V element (token r, feature f) at base + KvLayout::v_off(r, f, dh)      (includes the 64*dh K part)
 // with tile_stride = n_layers*2*64*d and layer_stride = 2*64*d in the pool, and a single-layer
 // form (tile_stride = 2*64*d, layer_stride = 0) in scratch for suffix tokens and for prefixes
 // recomputed inside a ranking call.
+//   fp32: K row-major [r][f]; V transposed [f][r].
+//   bf16: both tiles are stored in the order the 32x32x16 MFMA consumes them, as 1 KiB fragments
+//         of 64 lanes x 8 elements, so that a tile in HBM is byte-for-byte the LDS image and every
+//         operand fetch is one linear, conflict-free 16-byte read per lane:
+//         K fragment (kb, ks): lane (g, l32) holds token kb*32+l32, features ks*16+8g .. +7
+//         V fragment (db, kb, m): lane (g, l32) holds feature db*32+l32 and the 8 tokens
+//                    kb*32+16m+4g+{0..3}, kb*32+16m+8+4g+{0..3} -- the key order in which the
+//                    first product's accumulator hands P to the second product.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -59,6 +67,23 @@ struct RowTables {
   int32_t* idx;    // index inside the user's segment of that kind
   int32_t* lim;    // keys of [prefix | suffix] visible to this row
   int32_t* src;    // row in the embedding array of its kind
+};
+
+template <typename T> struct KvLayout;
+template <> struct KvLayout<float> {
+  static __host__ __device__ __forceinline__ int k_off(int r, int f, int dh) { return r * dh + f; }
+  static __host__ __device__ __forceinline__ int v_off(int r, int f, int dh) { return kTile * dh + f * kTile + r; }
+};
+template <> struct KvLayout<__hip_bfloat16> {
+  static __host__ __device__ __forceinline__ int k_off(int r, int f, int dh) {
+    int kb = r >> 5, l32 = r & 31, ks = f >> 4, g = (f >> 3) & 1, j = f & 7;
+    return ((kb * (dh >> 4) + ks) * 64 + g * 32 + l32) * 8 + j;
+  }
+  static __host__ __device__ __forceinline__ int v_off(int r, int f, int dh) {
+    int db = f >> 5, l32 = f & 31, kb = r >> 5, m = (r >> 4) & 1, w = r & 15;
+    int g = (w >> 2) & 1, j = ((w >> 3) << 2) | (w & 3);
+    return kTile * dh + (((db * 2 + kb) * 2 + m) * 64 + g * 32 + l32) * 8 + j;
+  }
 };
 
 // ---- element access in the two storage types ------------------------------------------------

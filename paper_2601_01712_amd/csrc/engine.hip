@@ -153,7 +153,14 @@ struct StagingSlot {
   bool pending = false;
 };
 
+struct ProfRec { int cls; hipEvent_t a, b; };
+
 struct relaygr_ctx {
+  uint32_t prof_mask = 0;
+  std::vector<ProfRec> prof_recs;       // recorded, not yet resolved
+  std::vector<hipEvent_t> prof_free;    // events ready for reuse
+  double prof_ms[RELAYGR_K_COUNT] = {};
+  int64_t prof_n[RELAYGR_K_COUNT] = {};
   relaygr_model_config cfg;
   std::vector<relaygr_layer_weights> layers;
   const void *ln_out_g, *ln_out_b, *w_score;
@@ -189,6 +196,8 @@ extern "C" int relaygr_ctx_create(const relaygr_model_config* cfg, const relaygr
 
 extern "C" void relaygr_ctx_destroy(relaygr_ctx* c) {
   if (!c) return;
+  for (auto& r : c->prof_recs) { (void)hipEventSynchronize(r.b); (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+  for (auto e : c->prof_free) (void)hipEventDestroy(e);
   for (auto& s : c->staging) {
     if (s.done) { if (s.pending) (void)hipEventSynchronize(s.done); (void)hipEventDestroy(s.done); }
     if (s.host) (void)hipHostFree(s.host);
@@ -210,6 +219,59 @@ static int staging_acquire(relaygr_ctx* c, size_t bytes, StagingSlot** out) {
     s.bytes = want;
   }
   *out = &s;
+  return RELAYGR_OK;
+}
+
+// ---- per-kernel timing ------------------------------------------------------------------------
+struct ProfScope {
+  relaygr_ctx* c; int cls; hipStream_t st; hipEvent_t a = nullptr, b = nullptr;
+  ProfScope(relaygr_ctx* c_, int cls_, hipStream_t st_) : c(c_), cls(cls_), st(st_) {
+    if (!(c->prof_mask & (1u << cls))) return;
+    auto get = [&]() -> hipEvent_t {
+      hipEvent_t e = nullptr;
+      if (!c->prof_free.empty()) { e = c->prof_free.back(); c->prof_free.pop_back(); }
+      else if (hipEventCreate(&e) != hipSuccess) e = nullptr;
+      return e;
+    };
+    a = get(); b = get();
+    if (a && b) (void)hipEventRecord(a, st);
+  }
+  ~ProfScope() {
+    if (!a || !b) return;
+    (void)hipEventRecord(b, st);
+    c->prof_recs.push_back({cls, a, b});
+  }
+};
+
+static int prof_resolve(relaygr_ctx* c) {
+  for (auto& r : c->prof_recs) {
+    HIP_TRY(hipEventSynchronize(r.b));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, r.a, r.b));
+    c->prof_ms[r.cls] += ms;
+    c->prof_n[r.cls] += 1;
+    c->prof_free.push_back(r.a);
+    c->prof_free.push_back(r.b);
+  }
+  c->prof_recs.clear();
+  return RELAYGR_OK;
+}
+
+extern "C" int relaygr_ctx_profile_enable(relaygr_ctx* c, uint32_t class_mask) {
+  if (!c) return fail(RELAYGR_EINVAL, "profile_enable: null context");
+  int rc = prof_resolve(c);
+  if (rc != RELAYGR_OK) return rc;
+  c->prof_mask = class_mask & ((1u << RELAYGR_K_COUNT) - 1);
+  for (int k = 0; k < RELAYGR_K_COUNT; ++k) { c->prof_ms[k] = 0.0; c->prof_n[k] = 0; }
+  return RELAYGR_OK;
+}
+
+extern "C" int relaygr_ctx_profile_read(relaygr_ctx* c, int32_t cls, double* total_ms, int64_t* launches) {
+  if (!c || cls < 0 || cls >= RELAYGR_K_COUNT) return fail(RELAYGR_EINVAL, "profile_read: bad argument");
+  int rc = prof_resolve(c);
+  if (rc != RELAYGR_OK) return rc;
+  if (total_ms) *total_ms = c->prof_ms[cls];
+  if (launches) *launches = c->prof_n[cls];
   return RELAYGR_OK;
 }
 
@@ -292,8 +354,13 @@ extern "C" int relaygr_kv_pool_locate(relaygr_kv_pool* pool, relaygr_kv_handle h
   int64_t tile = e.page0 * (p->page_tokens / kTile) + token / kTile;
   int r = token % kTile;
   int64_t base = tile * p->tile_stride + (int64_t)layer * p->layer_stride + (int64_t)head * 2 * kTile * dh;
-  *k_index = base + (int64_t)r * dh + f;
-  *v_index = base + (int64_t)kTile * dh + (int64_t)f * kTile + r;
+  if (p->cfg.dtype == RELAYGR_DTYPE_FP32) {
+    *k_index = base + KvLayout<float>::k_off(r, f, dh);
+    *v_index = base + KvLayout<float>::v_off(r, f, dh);
+  } else {
+    *k_index = base + KvLayout<__hip_bfloat16>::k_off(r, f, dh);
+    *v_index = base + KvLayout<__hip_bfloat16>::v_off(r, f, dh);
+  }
   return RELAYGR_OK;
 }
 
@@ -522,6 +589,8 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
   const int32_t* d_ns = (const int32_t*)(db + o_ns);
   const AttnTile* d_tiles = (const AttnTile*)(db + o_tiles);
 
+  {
+  ProfScope ps(c, RELAYGR_K_SETUP, st);
   hipLaunchKernelGGL(build_rows_kernel, dim3((p.n_rows + 255) / 256), dim3(256), 0, st, d_users, d_ps, d_ns, n, p.n_prows, p.n_rows, rt);
   LAUNCH_CHECK("build_rows");
   if (p.n_prows) {
@@ -531,6 +600,7 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
   if (p.sfx_tiles) {
     hipLaunchKernelGGL((zero_suffix_tail_kernel<T>), dim3(n), dim3(256), 0, st, d_users, n, sfx, H, dh);
     LAUNCH_CHECK("zero_suffix_tail");
+  }
   }
 
   const float alpha = 1.0f / sqrtf((float)dh);
@@ -552,6 +622,7 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
 
     // step 1: input LayerNorm (first layer also gathers the embeddings into the residual stream)
     {
+      ProfScope ps(c, RELAYGR_K_LN, st);
       dim3 grid((R + kRowsPerBlock - 1) / kRowsPerBlock);
       bool ok = dispatch_e(d, [&](auto e) {
         constexpr int E = decltype(e)::value;
@@ -571,10 +642,12 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
     e1.users = d_users; e1.rt = rt; e1.d = d; e1.dh = dh; e1.n_prows = p.n_prows; e1.layer = l; e1.q_mul = q_mul;
     ColMap all4 = {4, {0, 1, 2, 3}, d}, kv_only = {2, {1, 3, 0, 0}, d};
     if (last && p.n_prows) {
+      ProfScope ps(c, RELAYGR_K_F1, st);
       GemmLaunch<T>::run(xh, (const T*)lw.w1, d, 0, p.n_prows, kv_only, e1, st);
       LAUNCH_CHECK("f1 (k,v only)");
     }
     if (have_active) {
+      ProfScope ps(c, RELAYGR_K_F1, st);
       GemmLaunch<T>::run(xh, (const T*)lw.w1, d, a0, R, all4, e1, st);
       LAUNCH_CHECK("f1");
     }
@@ -585,11 +658,13 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
     ap.split_stride = (size_t)R * d; ap.nsplit = p.nsplit; ap.d = d; ap.n_heads = H; ap.layer = l; ap.score_mul = score_mul;
     int nt = last ? p.n_tiles_new : n_tiles_all;
     if (nt > 0) {
+      ProfScope ps(c, RELAYGR_K_ATTN, st);
       rc = launch_attention<T>(cfg, ap, nt, st);
       if (rc != RELAYGR_OK) return rc;
     }
     // steps 3-4: combine splits, self term, 1/n, LayerNorm, gate by u
     {
+      ProfScope ps(c, RELAYGR_K_GATE, st);
       dim3 grid((R - a0 + kRowsPerBlock - 1) / kRowsPerBlock);
       dispatch_e(d, [&](auto e) {
         constexpr int E = decltype(e)::value;
@@ -602,11 +677,15 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
     F2Epilogue<T> e2;
     e2.bias = (const T*)lw.b2; e2.x = x; e2.d = d;
     ColMap one = {1, {0, 0, 0, 0}, d};
-    GemmLaunch<T>::run(xh, (const T*)lw.w2, d, a0, R, one, e2, st);
+    {
+      ProfScope ps(c, RELAYGR_K_F2, st);
+      GemmLaunch<T>::run(xh, (const T*)lw.w2, d, a0, R, one, e2, st);
+    }
     LAUNCH_CHECK("f2");
   }
 
   if (mode != kPrefill && p.n_nrows) {
+    ProfScope ps(c, RELAYGR_K_SCORE, st);
     dim3 grid((p.n_nrows + kRowsPerBlock - 1) / kRowsPerBlock);
     dispatch_e(d, [&](auto e) {
       constexpr int E = decltype(e)::value;

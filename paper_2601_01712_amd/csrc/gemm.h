@@ -14,6 +14,8 @@ namespace relaygr {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
 
 // Which output column blocks (of width d) a launch produces: block j of the launch is block
 // blk[j] of the weight (f1 on last-layer prefix rows needs only v and k).
@@ -55,8 +57,7 @@ struct F1Epilogue {
              (int64_t)layer * ud.kv_layer_stride + (int64_t)h * 2 * kTile * dh;
     else
       base = sfx + ud.sfx_tile0 + tile * (int64_t)(2 * kTile * d) + (int64_t)h * 2 * kTile * dh;
-    if (is_k) Elem<T>::st(base + rr * dh + f, val);
-    else      Elem<T>::st(base + kTile * dh + f * kTile + rr, val);
+    Elem<T>::st(base + (is_k ? KvLayout<T>::k_off(rr, f, dh) : KvLayout<T>::v_off(rr, f, dh)), val);
   }
 };
 

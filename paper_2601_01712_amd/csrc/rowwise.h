@@ -180,8 +180,8 @@ __global__ void zero_kv_tail_kernel(const UserDesc* __restrict__ users, int n_us
     int layer = lh / n_heads, head = lh % n_heads;
     T* kt = base + (int64_t)layer * ud.kv_layer_stride + (int64_t)head * 2 * kTile * dh;
     int rr = tail0 + w / dh, f = w % dh;
-    Elem<T>::st(kt + rr * dh + f, 0.f);
-    Elem<T>::st(kt + kTile * dh + f * kTile + rr, 0.f);
+    Elem<T>::st(kt + KvLayout<T>::k_off(rr, f, dh), 0.f);
+    Elem<T>::st(kt + KvLayout<T>::v_off(rr, f, dh), 0.f);
   }
 }
 
@@ -202,8 +202,8 @@ __global__ void zero_suffix_tail_kernel(const UserDesc* __restrict__ users, int 
     int head = i / per_head, w = i % per_head;
     T* kt = base + (int64_t)head * 2 * kTile * dh;
     int rr = tail0 + w / dh, f = w % dh;
-    Elem<T>::st(kt + rr * dh + f, 0.f);
-    Elem<T>::st(kt + kTile * dh + f * kTile + rr, 0.f);
+    Elem<T>::st(kt + KvLayout<T>::k_off(rr, f, dh), 0.f);
+    Elem<T>::st(kt + KvLayout<T>::v_off(rr, f, dh), 0.f);
   }
 }
 

@@ -124,8 +124,18 @@ def test_pool_locate_follows_the_documented_tile_layout():
     layer_stride = 2 * 64 * 128
     k, v = rg.relaygr_kv_pool_locate(p, h, 1, 70, 64 + 5)    # layer 1, token 70 -> tile 1, r 6; head 1, f 5
     base = (2 + 1) * tile_stride + 1 * layer_stride + 1 * 2 * 64 * 64
-    assert k == base + 6 * 64 + 5
-    assert v == base + 64 * 64 + 5 * 64 + 6
+    # bf16 tiles are stored in MFMA fragment order: 1 KiB fragments of 64 lanes x 8 elements.
+    # K: token 6 -> key block 0, lane 6; feature 5 -> k-step 0, half 0, element 5
+    assert k == base + ((0 * 4 + 0) * 64 + 0 * 32 + 6) * 8 + 5
+    # V: feature 5 -> feature block 0, lane 5; token 6 -> key block 0, step 0, half 1 (tokens 4..7), slot 2
+    assert v == base + 64 * 64 + (((0 * 2 + 0) * 2 + 0) * 64 + 1 * 32 + 5) * 8 + 2
+    # the fp32 layout is plain: K [token][feature], V [feature][token]
+    cfg32 = rg.make_config(2, 128, 2, "fp32")
+    p32 = FakeSlabPool(cfg32, pages=4, page_tokens=128)
+    h32 = rg.relaygr_kv_pool_alloc(p32, 2, 200)
+    k32, v32 = rg.relaygr_kv_pool_locate(p32, h32, 1, 70, 64 + 5)
+    base32 = 1 * tile_stride + 1 * layer_stride + 1 * 2 * 64 * 64
+    assert k32 == base32 + 6 * 64 + 5 and v32 == base32 + 64 * 64 + 5 * 64 + 6
     seen = set()
     for tok in (0, 63, 64, 199):
         for feat in (0, 63, 64, 127):
