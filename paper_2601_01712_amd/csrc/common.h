@@ -34,7 +34,9 @@ namespace relaygr {
 
 constexpr int kTile = 64;   // tokens per K/V tile
 
-enum RowKind : int32_t { kRowPrefix = 0, kRowSuffix = 1, kRowCand = 2 };
+// kRowPad: filler between users in the prefix region of the row space (prefix rows of a user start
+// at an aligned row so that GEMM tiles never straddle users); it carries the user and a position >= L.
+enum RowKind : int32_t { kRowPrefix = 0, kRowSuffix = 1, kRowCand = 2, kRowPad = 3 };
 
 struct UserDesc {
   const void* kv;          // space holding this user's prefix K/V (pool slab or scratch)
@@ -105,8 +107,19 @@ __device__ __forceinline__ uint16_t float_to_bf16_bits(float v) {
   return *reinterpret_cast<uint16_t*>(&h);
 }
 
-// SiLU(t) = t / (1 + exp(-t)), fp32, accurate form (used outside the attention inner loop).
+// SiLU(t) = t / (1 + exp(-t)), fp32, accurate form (fp32 path and row-wise kernels).
 __device__ __forceinline__ float silu_f32(float t) { return t / (1.0f + __expf(-t)); }
+// The same through the hardware exp2 and reciprocal approximations (about 1 ulp each): bf16 path.
+__device__ __forceinline__ float silu_fast(float t) {
+  return t * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(t * -1.4426950408889634f));
+}
+
+// element offset of (row, k) in an array of MFMA-ordered panels of row length K: a panel is 128
+// rows, stored as 1 KiB fragments [k/16][(row%128)/32][lane][8], lane = ((k/8)%2)*32 + row%32
+__host__ __device__ __forceinline__ size_t panel_off(int row, int k, int K) {
+  int panel = row >> 7, rb = (row >> 5) & 3, l32 = row & 31, ks = k >> 4, g = (k >> 3) & 1, j = k & 7;
+  return ((size_t)panel * (K >> 4) + ks) * 2048 + (size_t)rb * 512 + (g * 32 + l32) * 8 + j;
+}
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

@@ -16,6 +16,7 @@
 #include "attention.h"
 #include "common.h"
 #include "gemm.h"
+#include "gemm_bf16.h"
 #include "kv_pool.h"
 #include "rowwise.h"
 
@@ -91,12 +92,24 @@ struct Plan {
 static int rows_per_attn_tile(const relaygr_model_config& c) { return c.dtype == RELAYGR_DTYPE_FP32 ? 64 : 128; }
 
 // Lays the call's buffers out in scratch.  Everything is a function of the counts already in p.
+// Bytes at the start of scratch that hold the weights re-packed into MFMA panels (bf16 only).
+static size_t wpack_bytes(const relaygr_model_config& c) {
+  if (c.dtype != RELAYGR_DTYPE_BF16) return 0;
+  const size_t d = c.d_model;
+  return align_up((size_t)c.n_layers * 5 * d * d * 2);
+}
+
+// Prefix rows of a user start at a multiple of this in the row space (bf16: GEMM tiles of 256 rows
+// never straddle users, and 32-row MFMA blocks coincide with 32-token halves of K/V tiles).
+static int prefix_row_align(const relaygr_model_config& c) { return c.dtype == RELAYGR_DTYPE_BF16 ? kPrefixRowAlign : 1; }
+
 static void carve(const relaygr_model_config& c, Plan& p) {
   const size_t d = c.d_model, e = elem_bytes(c), R = p.n_rows;
-  size_t o = 0;
+  const size_t Rp = (R + 255) / 256 * 256;     // the bf16 GEMMs read whole 256-row tiles of xh
+  size_t o = wpack_bytes(c);
   auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
   p.off_x = take(R * d * 4);
-  p.off_xh = take(R * d * e);
+  p.off_xh = take(Rp * d * e);
   p.off_u = take(R * d * e);
   p.off_q = take(R * d * e);
   p.off_knew = take((size_t)p.n_nrows * d * e);
@@ -129,14 +142,16 @@ extern "C" size_t relaygr_scratch_bytes(const relaygr_model_config* cfg, int32_t
   if (max_prefix_tokens + max_new_tokens >= (1ll << 31)) return 0;
   Plan p;
   p.n_users = max_users;
-  p.n_prows = (int)max_prefix_tokens;
+  int64_t padded = max_prefix_tokens + (int64_t)max_users * (prefix_row_align(*cfg) - 1);
+  if (padded + max_new_tokens >= (1ll << 31)) return 0;
+  p.n_prows = (int)padded;
   p.n_nrows = (int)max_new_tokens;
   p.n_rows = p.n_prows + p.n_nrows;
   p.sfx_tiles = max_new_tokens / kTile + max_users;
   p.kvs_tiles = max_prefix_tokens / kTile + max_users;
   int rpt = rows_per_attn_tile(*cfg);
   p.n_tiles_new = (int)(max_new_tokens / rpt) + max_users;
-  p.n_tiles_prefix = (int)(max_prefix_tokens / rpt) + max_users;
+  p.n_tiles_prefix = (int)(padded / rpt) + max_users;
   p.nsplit = 1;
   carve(*cfg, p);
   size_t base = p.total;
@@ -167,6 +182,7 @@ struct relaygr_ctx {
   float b_score;
   char* scratch;
   size_t scratch_bytes;
+  std::vector<const uint16_t*> w1_packed, w2_packed;   // bf16: panels at the start of scratch
   StagingSlot staging[4];
   int next_slot = 0;
 };
@@ -190,6 +206,25 @@ extern "C" int relaygr_ctx_create(const relaygr_model_config* cfg, const relaygr
   c->ln_out_g = w->ln_out_g; c->ln_out_b = w->ln_out_b; c->w_score = w->w_score; c->b_score = w->b_score;
   c->scratch = (char*)scratch_dev;
   c->scratch_bytes = scratch_bytes;
+  if (cfg->dtype == RELAYGR_DTYPE_BF16) {
+    // re-pack W1 and W2 of every layer into MFMA panels, once
+    const size_t d = cfg->d_model;
+    if (scratch_bytes < wpack_bytes(*cfg)) { delete c; return fail(RELAYGR_ENOSPC, "ctx_create: scratch smaller than the packed weights"); }
+    uint16_t* wp = (uint16_t*)scratch_dev;
+    for (int l = 0; l < cfg->n_layers; ++l) {
+      uint16_t* w1p = wp + (size_t)l * 5 * d * d;
+      uint16_t* w2p = w1p + 4 * d * d;
+      int c1 = (int)(4 * d * d / 8), c2 = (int)(d * d / 8);
+      hipLaunchKernelGGL(pack_weight_kernel, dim3((c1 + 255) / 256), dim3(256), 0, 0, (const __hip_bfloat16*)c->layers[l].w1,
+                         (__hip_bfloat16*)w1p, (int)(4 * d), (int)d);
+      hipLaunchKernelGGL(pack_weight_kernel, dim3((c2 + 255) / 256), dim3(256), 0, 0, (const __hip_bfloat16*)c->layers[l].w2,
+                         (__hip_bfloat16*)w2p, (int)d, (int)d);
+      c->w1_packed.push_back(w1p);
+      c->w2_packed.push_back(w2p);
+    }
+    hipError_t e = hipDeviceSynchronize();
+    if (e != hipSuccess) { delete c; return fail(RELAYGR_EHIP, "ctx_create: packing weights: %s", hipGetErrorString(e)); }
+  }
   *out = c;
   return RELAYGR_OK;
 }
@@ -391,15 +426,9 @@ template <> struct GemmLaunch<float> {
   }
 };
 
+// bf16: the MFMA kernels of gemm_bf16.h take parameter blocks instead of functors
 template <> struct GemmLaunch<__hip_bfloat16> {
-  static constexpr int BM = kGemmBM;
-  template <class Epi>
-  static void run(const __hip_bfloat16* A, const __hip_bfloat16* W, int K, int r0, int r1, const ColMap& cm, const Epi& epi, hipStream_t st) {
-    int mt = (r1 - r0 + BM - 1) / BM;
-    int total = mt * cm.nblk * (cm.d / kGemmBN);
-    int grid = ((total + 7) / 8) * 8;
-    hipLaunchKernelGGL((gemm_bf16_kernel<Epi>), dim3(grid), dim3(256), 0, st, A, W, K, r0, r1, cm, mt, epi);
-  }
+  static constexpr int BM = 64 * kF1TM;
 };
 
 template <typename T>
@@ -445,6 +474,7 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
   const int d = cfg.d_model, H = cfg.n_heads, dh = d / H, NL = cfg.n_layers, n = b->n_users;
   const bool bf16 = cfg.dtype == RELAYGR_DTYPE_BF16;
   const int rpt = rows_per_attn_tile(cfg);
+  const int palign = prefix_row_align(cfg);
 
   // -- per-user shapes and K/V sources
   std::vector<UserDesc> users(n);
@@ -490,7 +520,7 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
     ud.prow0 = compute_prefix ? (int32_t)prow : -1;
     if (compute_prefix) {
       if (!b->prefix_emb) return fail(RELAYGR_EINVAL, "user %d needs prefix_emb", u);
-      prow += L;
+      prow += ((int64_t)L + palign - 1) / palign * palign;   // filler rows up to the next aligned start
     }
     nstart[u] = (int32_t)nrow;
     ud.nrow0 = (mode != kPrefill) ? (int32_t)nrow : -1;
@@ -593,7 +623,7 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
   ProfScope ps(c, RELAYGR_K_SETUP, st);
   hipLaunchKernelGGL(build_rows_kernel, dim3((p.n_rows + 255) / 256), dim3(256), 0, st, d_users, d_ps, d_ns, n, p.n_prows, p.n_rows, rt);
   LAUNCH_CHECK("build_rows");
-  if (p.n_prows) {
+  if (p.n_prows && std::is_same<T, float>::value) {   // the bf16 f1 epilogue zero-fills the ragged tail itself
     hipLaunchKernelGGL((zero_kv_tail_kernel<T>), dim3(n), dim3(256), 0, st, d_users, n, NL, H, dh);
     LAUNCH_CHECK("zero_kv_tail");
   }
@@ -612,6 +642,7 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
   const T* emb_s = (const T*)b->suffix_emb;
   const T* emb_c = (const T*)b->cand_emb;
   const int R = p.n_rows;
+  constexpr bool kPanel = !std::is_same<T, float>::value;   // bf16: xh / y are written as MFMA panels
 
   for (int l = 0; l < NL; ++l) {
     const relaygr_layer_weights& lw = c->layers[l];
@@ -627,28 +658,42 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
       bool ok = dispatch_e(d, [&](auto e) {
         constexpr int E = decltype(e)::value;
         if (l == 0)
-          hipLaunchKernelGGL((ln_in_kernel<T, E, true>), grid, dim3(256), 0, st, x, xh, (const T*)lw.ln_in_g, (const T*)lw.ln_in_b,
+          hipLaunchKernelGGL((ln_in_kernel<T, E, true, kPanel>), grid, dim3(256), 0, st, x, xh, (const T*)lw.ln_in_g, (const T*)lw.ln_in_b,
                              emb_p, emb_s, emb_c, rt, 0, R, cfg.ln_eps);
         else
-          hipLaunchKernelGGL((ln_in_kernel<T, E, false>), grid, dim3(256), 0, st, x, xh, (const T*)lw.ln_in_g, (const T*)lw.ln_in_b,
+          hipLaunchKernelGGL((ln_in_kernel<T, E, false, kPanel>), grid, dim3(256), 0, st, x, xh, (const T*)lw.ln_in_g, (const T*)lw.ln_in_b,
                              emb_p, emb_s, emb_c, rt, 0, R, cfg.ln_eps);
       });
       if (!ok) return fail(RELAYGR_EINVAL, "unsupported d_model");
       LAUNCH_CHECK("ln_in");
     }
     // step 2: projections
-    F1Epilogue<T> e1;
-    e1.bias = (const T*)lw.b1; e1.u = ubuf; e1.q = qbuf; e1.knew = knew; e1.vnew = vnew; e1.sfx = sfx;
-    e1.users = d_users; e1.rt = rt; e1.d = d; e1.dh = dh; e1.n_prows = p.n_prows; e1.layer = l; e1.q_mul = q_mul;
     ColMap all4 = {4, {0, 1, 2, 3}, d}, kv_only = {2, {1, 3, 0, 0}, d};
+    auto run_f1 = [&](int r0, int r1, const ColMap& cm) {
+      if constexpr (std::is_same<T, float>::value) {
+        F1Epilogue<T> e1;
+        e1.bias = (const T*)lw.b1; e1.u = ubuf; e1.q = qbuf; e1.knew = knew; e1.vnew = vnew; e1.sfx = sfx;
+        e1.users = d_users; e1.rt = rt; e1.d = d; e1.dh = dh; e1.n_prows = p.n_prows; e1.layer = l; e1.q_mul = q_mul;
+        GemmLaunch<T>::run(xh, (const T*)lw.w1, d, r0, r1, cm, e1, st);
+      } else {
+        F1Params fp;
+        fp.A = (const uint16_t*)xh; fp.W = c->w1_packed[l]; fp.bias = (const uint16_t*)lw.b1;
+        fp.u = (uint16_t*)ubuf; fp.q = (uint16_t*)qbuf; fp.knew = (uint16_t*)knew; fp.vnew = (uint16_t*)vnew; fp.sfx = (uint16_t*)sfx;
+        fp.users = d_users; fp.rt = rt; fp.d = d; fp.dh = dh; fp.n_prows = p.n_prows; fp.layer = l;
+        fp.row_begin = r0; fp.row_end = r1; fp.n_mtiles = (r1 - r0 + 64 * kF1TM - 1) / (64 * kF1TM);
+        fp.cm = cm; fp.q_mul = q_mul;
+        int total = fp.n_mtiles * cm.nblk * (d / (64 * kF1TN));
+        hipLaunchKernelGGL(f1_gemm_bf16_kernel, dim3((total + 7) / 8 * 8), dim3(256), 0, st, fp);
+      }
+    };
     if (last && p.n_prows) {
       ProfScope ps(c, RELAYGR_K_F1, st);
-      GemmLaunch<T>::run(xh, (const T*)lw.w1, d, 0, p.n_prows, kv_only, e1, st);
+      run_f1(0, p.n_prows, kv_only);
       LAUNCH_CHECK("f1 (k,v only)");
     }
     if (have_active) {
       ProfScope ps(c, RELAYGR_K_F1, st);
-      GemmLaunch<T>::run(xh, (const T*)lw.w1, d, a0, R, all4, e1, st);
+      run_f1(a0, R, all4);
       LAUNCH_CHECK("f1");
     }
     if (!have_active) continue;
@@ -668,18 +713,26 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
       dim3 grid((R - a0 + kRowsPerBlock - 1) / kRowsPerBlock);
       dispatch_e(d, [&](auto e) {
         constexpr int E = decltype(e)::value;
-        hipLaunchKernelGGL((attn_gate_kernel<T, E>), grid, dim3(256), 0, st, part, p.nsplit, (size_t)R * d, ubuf, qbuf, knew, vnew, xh,
+        hipLaunchKernelGGL((attn_gate_kernel<T, E, kPanel>), grid, dim3(256), 0, st, part, p.nsplit, (size_t)R * d, ubuf, qbuf, knew, vnew, xh,
                            (const T*)lw.ln_at_g, (const T*)lw.ln_at_b, rt, p.n_prows, a0, R, dh, gate_mul, cfg.ln_eps);
       });
       LAUNCH_CHECK("attn_gate");
     }
     // step 4: output projection and residual
-    F2Epilogue<T> e2;
-    e2.bias = (const T*)lw.b2; e2.x = x; e2.d = d;
-    ColMap one = {1, {0, 0, 0, 0}, d};
     {
       ProfScope ps(c, RELAYGR_K_F2, st);
-      GemmLaunch<T>::run(xh, (const T*)lw.w2, d, a0, R, one, e2, st);
+      if constexpr (std::is_same<T, float>::value) {
+        F2Epilogue<T> e2;
+        e2.bias = (const T*)lw.b2; e2.x = x; e2.d = d;
+        ColMap one = {1, {0, 0, 0, 0}, d};
+        GemmLaunch<T>::run(xh, (const T*)lw.w2, d, a0, R, one, e2, st);
+      } else {
+        F2Params fp;
+        fp.A = (const uint16_t*)xh; fp.W = c->w2_packed[l]; fp.bias = (const uint16_t*)lw.b2; fp.x = x; fp.rt = rt; fp.d = d;
+        fp.row_begin = a0; fp.row_end = R; fp.n_mtiles = (R - a0 + 64 * kF2TM - 1) / (64 * kF2TM);
+        int total = fp.n_mtiles * (d / (64 * kF2TN));
+        hipLaunchKernelGGL(f2_gemm_bf16_kernel, dim3((total + 7) / 8 * 8), dim3(256), 0, st, fp);
+      }
     }
     LAUNCH_CHECK("f2");
   }

@@ -4,8 +4,8 @@
 //       prefix / suffix rows are scattered straight into K/V tile layout (pool or scratch), k and
 //       v of candidate rows go to row-major scratch for the self term.
 //   f2: x <- x + y W2^T + b2 on the fp32 residual stream.
-// Both operands are K-contiguous (weights are output-major), which is what the bf16 MFMA wants:
-// every lane's 8-element fragment is one 16-byte load.
+// This file holds what the fp32 path uses (per-element epilogue functors, a plain LDS-tiled FMA
+// GEMM) and small pieces shared with the bf16 MFMA GEMMs of gemm_bf16.h.
 #pragma once
 
 #include "common.h"
@@ -78,94 +78,6 @@ struct F2Epilogue {
 __device__ __forceinline__ int xcd_remap(int id, int total) {
   int chunk = (total + 7) >> 3;
   return (id & 7) * chunk + (id >> 3);
-}
-
-// ---- bf16 MFMA GEMM: 128x128 tile, BK = 64, 4 wavefronts of 64x64 ---------------------------------
-constexpr int kGemmBM = 128, kGemmBN = 128, kGemmBK = 64, kGemmLd = kGemmBK + 8;
-
-template <class Epi>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(const __hip_bfloat16* __restrict__ A,
-                                                        const __hip_bfloat16* __restrict__ W, int K,
-                                                        int row_begin, int row_end, ColMap cm, int n_mtiles,
-                                                        Epi epi) {
-  __shared__ __attribute__((aligned(16))) uint16_t As[kGemmBM * kGemmLd];
-  __shared__ __attribute__((aligned(16))) uint16_t Bs[kGemmBN * kGemmLd];
-  const int ntiles_per_blk = cm.d / kGemmBN;
-  const int n_ntiles = cm.nblk * ntiles_per_blk;
-  const int total = n_mtiles * n_ntiles;
-  int logical = xcd_remap(blockIdx.x, total);
-  if (logical >= total) return;
-  const int mt = logical / n_ntiles, nt = logical - mt * n_ntiles;
-  const int m0 = row_begin + mt * kGemmBM;
-  const int n0 = cm.blk[nt / ntiles_per_blk] * cm.d + (nt % ntiles_per_blk) * kGemmBN;
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int l32 = lane & 31, g = lane >> 5;
-
-  // global -> register staging: 128 rows x 8 chunks of 16 B per operand, 4 chunks per thread
-  uint4 ra[4], rb[4];
-  const uint16_t* Ag = reinterpret_cast<const uint16_t*>(A);
-  const uint16_t* Wg = reinterpret_cast<const uint16_t*>(W);
-  auto load_tiles = [&](int k0) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      int c = tid + i * 256, row = c >> 3, kc = c & 7;
-      int ar = min(m0 + row, row_end - 1);
-      ra[i] = *reinterpret_cast<const uint4*>(Ag + (size_t)ar * K + k0 + kc * 8);
-      rb[i] = *reinterpret_cast<const uint4*>(Wg + (size_t)(n0 + row) * K + k0 + kc * 8);
-    }
-  };
-  auto store_tiles = [&]() {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      int c = tid + i * 256, row = c >> 3, kc = c & 7;
-      *reinterpret_cast<uint4*>(&As[row * kGemmLd + kc * 8]) = ra[i];
-      *reinterpret_cast<uint4*>(&Bs[row * kGemmLd + kc * 8]) = rb[i];
-    }
-  };
-
-  f32x16_t acc[2][2];
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-  load_tiles(0);
-  for (int k0 = 0; k0 < K; k0 += kGemmBK) {
-    __syncthreads();
-    store_tiles();
-    __syncthreads();
-    if (k0 + kGemmBK < K) load_tiles(k0 + kGemmBK);
-#pragma unroll
-    for (int ks = 0; ks < kGemmBK / 16; ++ks) {
-      bf16x8_t af[2], bf[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        af[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(&As[(wm * 64 + i * 32 + l32) * kGemmLd + ks * 16 + g * 8]));
-        bf[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(&Bs[(wn * 64 + i * 32 + l32) * kGemmLd + ks * 16 + g * 8]));
-      }
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
-    }
-  }
-
-  // accumulator element e of a 32x32 block: row 8*(e/4) + 4*(lane/32) + e%4, column lane%32
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        int r = m0 + wm * 64 + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
-        int c = n0 + wn * 64 + j * 32 + l32;
-        if (r < row_end) epi(r, c, acc[i][j][e]);
-      }
 }
 
 // ---- fp32 GEMM: 64x64 tile, BK = 16, 4x4 outputs per thread ---------------------------------------

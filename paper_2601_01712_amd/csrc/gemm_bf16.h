@@ -1,0 +1,320 @@
+// bf16 projection GEMMs on the 32x32x16 MFMA: C[tokens, features] = A[tokens, K] * W[features, K]^T
+// with the layer's pointwise work fused in (steps 2 and 4 of a layer):
+//   f1: SiLU(xh W1^T + b1) split into u | v | q | k and written where the next kernel wants it:
+//       u, q (and k, v of candidate rows) row-major; k, v of prefix / suffix rows straight into the
+//       K/V tile layout of the pool or of scratch;
+//   f2: x <- x + y W2^T + b2 on the fp32 residual stream.
+//
+// Operand layout.  Both operands live in global memory already in MFMA fragment order ("panels"):
+// a panel is 128 rows x K, stored as 1 KiB fragments [k-step ks = k/16][row block rb = (row%128)/32]
+// [lane][8], lane (g, l32) holding row rb*32 + l32, k = ks*16 + 8g .. +7.  The LayerNorm kernels
+// write activations that way and the weights are re-packed once per context.  A k-tile of a panel
+// is therefore one contiguous run of bytes that is copied HBM -> LDS with direct 16-byte-per-lane
+// loads (fully coalesced, no registers), lands as the exact LDS image the MFMA reads, and every
+// operand fetch is one linear ds_read_b128 with no bank conflicts.  Because token and feature
+// fragments have the same shape, either can be the MFMA's row operand: "feature-major" products
+// leave each lane with 4 consecutive features of one token (what row-major outputs and K tiles
+// want), "token-major" products leave 4 consecutive tokens of one feature (exactly a V-tile
+// fragment, and what the fp32 residual update wants).
+#pragma once
+
+#include "common.h"
+#include "gemm.h"
+
+namespace relaygr {
+
+constexpr int kPanelRows = 128;
+constexpr int kGemmKTile = 32;          // k per main-loop step (2 MFMA k-steps)
+constexpr int kPrefixRowAlign = 256;    // prefix rows of a user start at a multiple of this in the row space
+
+// Re-packs a row-major [N, K] weight into panels.
+__global__ void pack_weight_kernel(const __hip_bfloat16* __restrict__ w, __hip_bfloat16* __restrict__ packed, int N, int K) {
+  int idx = blockIdx.x * blockDim.x + threadIdx.x;   // one 8-element chunk per thread
+  int chunks_per_row = K >> 3;
+  if (idx >= N * chunks_per_row) return;
+  int n = idx / chunks_per_row, kc = idx - n * chunks_per_row;
+  uint4 v = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(w) + (size_t)n * K + kc * 8);
+  *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(packed) + panel_off(n, kc * 8, K)) = v;
+}
+
+// ---- main loop ----------------------------------------------------------------------------------
+// Workgroup tile: 64*TM tokens x 64*TN features, 4 wavefronts as 2 x 2, each owning TM x TN blocks of
+// 32 x 32.  LDS holds two stages of [token pieces | feature pieces], a piece being one 1 KiB fragment.
+template <int TM, int TN>
+struct GemmTile {
+  static constexpr int BMt = 64 * TM, BNf = 64 * TN;
+  static constexpr int TOK_PIECES = (BMt / 32) * 2, FEAT_PIECES = (BNf / 32) * 2;   // per stage (2 k-steps)
+  static constexpr int PIECES = TOK_PIECES + FEAT_PIECES;
+  static constexpr int STAGE = PIECES * 512;   // elements
+};
+
+// FEATURE_MAJOR: features are the MFMA row operand (lane = token column, 4-feature runs per lane).
+template <int TM, int TN, bool FEATURE_MAJOR>
+__device__ __forceinline__ void gemm_mainloop(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W, int K, int m0, int n0,
+                                              uint16_t* lds, f32x16_t (&acc)[TM][TN]) {
+  using G = GemmTile<TM, TN>;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int KS = K >> 4;
+  // piece p of a stage: token pieces first, ordered [panel][ksl][rb]; then feature pieces [npanel][ksl][nb]
+  auto issue = [&](int kt, int stage) {
+    uint16_t* dst = lds + stage * G::STAGE;
+#pragma unroll
+    for (int p = wave; p < G::PIECES; p += 4) {
+      const uint16_t* src;
+      if (p < G::TOK_PIECES) {
+        int panel = p >> 3, ksl = (p >> 2) & 1, rb = p & 3;
+        src = A + ((size_t)((m0 >> 7) + panel) * KS + (kt * 2 + ksl)) * 2048 + rb * 512;
+      } else {
+        int q = p - G::TOK_PIECES;
+        int panel = q >> 3, ksl = (q >> 2) & 1, nb = q & 3;
+        src = W + ((size_t)((n0 >> 7) + panel) * KS + (kt * 2 + ksl)) * 2048 + nb * 512;
+      }
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + lane * 8),
+                                       (__attribute__((address_space(3))) void*)(dst + p * 512), 16, 0, 0);
+    }
+  };
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  const int n_kt = K / kGemmKTile;
+  issue(0, 0);
+  for (int kt = 0; kt < n_kt; ++kt) {
+    const int stage = kt & 1;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (kt + 1 < n_kt) issue(kt + 1, stage ^ 1);
+    const uint16_t* tokp = lds + stage * G::STAGE + lane * 8;
+    const uint16_t* featp = tokp + G::TOK_PIECES * 512;
+#pragma unroll
+    for (int ksl = 0; ksl < 2; ++ksl) {
+      bf16x8_t tf[TM], ff[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        int rbAll = wm * TM + i;   // 32-row block inside the workgroup tile
+        tf[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(tokp + (((rbAll >> 2) * 2 + ksl) * 4 + (rbAll & 3)) * 512));
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        int nbAll = wn * TN + j;
+        ff[j] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(featp + (((nbAll >> 2) * 2 + ksl) * 4 + (nbAll & 3)) * 512));
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = FEATURE_MAJOR ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(ff[j], tf[i], acc[i][j], 0, 0, 0)
+                                    : __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf[i], ff[j], acc[i][j], 0, 0, 0);
+    }
+  }
+  __syncthreads();   // every wavefront is done reading LDS: the epilogue may reuse it
+}
+
+// ---- f1 -------------------------------------------------------------------------------------------
+struct F1Params {
+  const uint16_t* A;        // xh panels
+  const uint16_t* W;        // packed W1 [4d, d]
+  const uint16_t* bias;     // [4d]
+  uint16_t* u; uint16_t* q; uint16_t* knew; uint16_t* vnew; uint16_t* sfx;
+  const UserDesc* users;
+  RowTables rt;
+  int d, dh, n_prows, layer, row_begin, row_end, n_mtiles;
+  ColMap cm;
+  float q_mul;
+};
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+  f32x2_t v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
+constexpr int kF1TM = 4, kF1TN = 2;               // 256 tokens x 128 features per workgroup
+constexpr int kStageLd = 64 * kF1TN + 8;          // epilogue staging row stride (elements)
+
+__global__ __launch_bounds__(256, 2) void f1_gemm_bf16_kernel(F1Params p) {
+  constexpr int TM = kF1TM, TN = kF1TN;
+  using G = GemmTile<TM, TN>;
+  constexpr int LDS_ELEMS = (2 * G::STAGE > 128 * kStageLd) ? 2 * G::STAGE : 128 * kStageLd;
+  __shared__ __attribute__((aligned(16))) uint16_t lds[LDS_ELEMS];
+
+  const int ntiles_per_blk = p.cm.d / G::BNf;
+  const int n_ntiles = p.cm.nblk * ntiles_per_blk;
+  const int total = p.n_mtiles * n_ntiles;
+  const int logical = xcd_remap(blockIdx.x, total);
+  if (logical >= total) return;
+  const int mt = logical / n_ntiles, nt = logical - mt * n_ntiles;
+  const int m0 = p.row_begin + mt * G::BMt;
+  const int blk = p.cm.blk[nt / ntiles_per_blk];           // 0 u, 1 v, 2 q, 3 k
+  const int c0 = (nt % ntiles_per_blk) * G::BNf;            // first feature inside the block
+  const int n0 = blk * p.cm.d + c0;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1, l32 = lane & 31, g = lane >> 5;
+  const int d = p.d, dh = p.dh;
+
+  // A tile of prefix rows is one user's consecutive prefix positions starting at a multiple of 256
+  // (row-space alignment), possibly followed by padding rows.
+  const bool prefix_tile = m0 < p.n_prows;
+  f32x16_t acc[TM][TN];
+
+  if (blk == 1 && prefix_tile) {
+    // ---- V of prefix rows: token-major product; the accumulator of a 32-token x 32-feature block
+    // is, lane for lane, two V-tile fragments (m = 0, 1), stored as 1 KiB contiguous runs.
+    gemm_mainloop<TM, TN, false>(p.A, p.W, d, m0, n0, lds, acc);
+    const int user = p.rt.user[m0];
+    const UserDesc ud = p.users[user];
+    const int pos0 = p.rt.idx[m0];
+    const int L = ud.L, Lceil = (L + kTile - 1) / kTile * kTile;
+    uint16_t* kvb = reinterpret_cast<uint16_t*>(const_cast<void*>(ud.kv)) + ud.kv_tile0 + (int64_t)p.layer * ud.kv_layer_stride;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int c = c0 + wn * 64 + j * 32;                  // first feature of this 32-feature block
+      const int head = c / dh, db = (c - head * dh) >> 5;
+      const float bias = bf16_bits_to_float(p.bias[n0 + wn * 64 + j * 32 + l32]);
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int tok0 = pos0 + wm * 128 + i * 32;          // first token of this 32-token block
+        if (tok0 >= Lceil) continue;
+        const int kb = (tok0 >> 5) & 1;
+        uint16_t* frag = kvb + (int64_t)(tok0 >> 6) * ud.kv_tile_stride + (int64_t)head * 2 * kTile * dh + kTile * dh;
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+          uint32_t w[4];
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            const int e4 = 2 * m + h;
+            float v[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const int tok = tok0 + 8 * e4 + 4 * g + r;
+              float val = silu_fast(acc[i][j][4 * e4 + r] + bias);
+              v[r] = tok < L ? val : 0.f;                    // the ragged tail of the last tile holds zeros
+            }
+            w[2 * h] = pack_bf16x2(v[0], v[1]);
+            w[2 * h + 1] = pack_bf16x2(v[2], v[3]);
+          }
+          *reinterpret_cast<uint4*>(frag + (((db * 2 + kb) * 2 + m) * 64 + lane) * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+      }
+    }
+    return;
+  }
+
+  // ---- everything else: feature-major product, staged through LDS as [token][feature] so that
+  // every global store is a 16-byte chunk of 8 consecutive features of one token.
+  gemm_mainloop<TM, TN, true>(p.A, p.W, d, m0, n0, lds, acc);
+  const float mul = (blk == 2) ? p.q_mul : 1.0f;
+#pragma unroll 1
+  for (int half = 0; half < 2; ++half) {
+    if (wm == half) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+          const int f = wn * 64 + j * 32 + 8 * e4 + 4 * g;  // 4 consecutive features held by this lane
+          const uint2 bb = *reinterpret_cast<const uint2*>(p.bias + n0 + f);
+          const float b0 = bf16_bits_to_float(bb.x & 0xFFFF), b1 = bf16_bits_to_float(bb.x >> 16);
+          const float b2 = bf16_bits_to_float(bb.y & 0xFFFF), b3 = bf16_bits_to_float(bb.y >> 16);
+#pragma unroll
+          for (int i = 0; i < TM; ++i) {
+            const int t = i * 32 + l32;
+            uint2 w;
+            w.x = pack_bf16x2(silu_fast(acc[i][j][4 * e4] + b0) * mul, silu_fast(acc[i][j][4 * e4 + 1] + b1) * mul);
+            w.y = pack_bf16x2(silu_fast(acc[i][j][4 * e4 + 2] + b2) * mul, silu_fast(acc[i][j][4 * e4 + 3] + b3) * mul);
+            *reinterpret_cast<uint2*>(&lds[t * kStageLd + f]) = w;
+          }
+        }
+    }
+    __syncthreads();
+    // 128 tokens x 16 chunks of 8 features
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int cidx = tid + it * 256;
+      const int t = cidx >> 4, fc = cidx & 15;
+      const int row = m0 + half * 128 + t;
+      if (row >= p.row_end) continue;
+      const int kind = p.rt.kind[row];
+      if (kind == kRowPad && (blk == 0 || blk == 2)) continue;
+      uint4 val = *reinterpret_cast<const uint4*>(&lds[t * kStageLd + fc * 8]);
+      const int c = c0 + fc * 8;                             // feature inside the block
+      if (blk == 0) { *reinterpret_cast<uint4*>(p.u + (size_t)row * d + c) = val; continue; }
+      if (blk == 2) { *reinterpret_cast<uint4*>(p.q + (size_t)row * d + c) = val; continue; }
+      if (kind == kRowCand) {
+        *reinterpret_cast<uint4*>((blk == 3 ? p.knew : p.vnew) + (size_t)(row - p.n_prows) * d + c) = val;
+        continue;
+      }
+      const UserDesc& ud = p.users[p.rt.user[row]];
+      const int idx = p.rt.idx[row];
+      const int head = c / dh, f = c - head * dh;
+      uint16_t* base;
+      if (kind == kRowSuffix) {
+        base = p.sfx + ud.sfx_tile0 + (int64_t)(idx >> 6) * (2 * kTile * d) + (int64_t)head * 2 * kTile * dh;
+      } else {
+        if (idx >= (ud.L + kTile - 1) / kTile * kTile) continue;   // padding beyond the user's last tile
+        if (kind == kRowPad) val = make_uint4(0, 0, 0, 0);         // ragged tail of the last tile: zeros
+        base = reinterpret_cast<uint16_t*>(const_cast<void*>(ud.kv)) + ud.kv_tile0 + (int64_t)(idx >> 6) * ud.kv_tile_stride +
+               (int64_t)p.layer * ud.kv_layer_stride + (int64_t)head * 2 * kTile * dh;
+      }
+      const int rr = idx & 63;
+      if (blk == 3) {
+        *reinterpret_cast<uint4*>(base + KvLayout<__hip_bfloat16>::k_off(rr, f, dh)) = val;
+      } else {   // V of a suffix row: its 8 features go to 8 different fragments
+        const uint16_t* e = reinterpret_cast<const uint16_t*>(&val);
+#pragma unroll
+        for (int x = 0; x < 8; ++x) base[KvLayout<__hip_bfloat16>::v_off(rr, f + x, dh)] = e[x];
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// ---- f2 -------------------------------------------------------------------------------------------
+struct F2Params {
+  const uint16_t* A;        // y panels
+  const uint16_t* W;        // packed W2 [d, d]
+  const uint16_t* bias;     // [d]
+  float* x;                 // residual stream [rows, d], updated in place
+  RowTables rt;
+  int d, row_begin, row_end, n_mtiles;
+};
+
+constexpr int kF2TM = 2, kF2TN = 2;   // 128 tokens x 128 features per workgroup
+
+__global__ __launch_bounds__(256, 2) void f2_gemm_bf16_kernel(F2Params p) {
+  constexpr int TM = kF2TM, TN = kF2TN;
+  using G = GemmTile<TM, TN>;
+  __shared__ __attribute__((aligned(16))) uint16_t lds[2 * G::STAGE];
+  const int n_ntiles = p.d / G::BNf;
+  const int total = p.n_mtiles * n_ntiles;
+  const int logical = xcd_remap(blockIdx.x, total);
+  if (logical >= total) return;
+  const int mt = logical / n_ntiles, nt = logical - mt * n_ntiles;
+  const int m0 = p.row_begin + mt * G::BMt, n0 = nt * G::BNf;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1, l32 = lane & 31, g = lane >> 5;
+  f32x16_t acc[TM][TN];
+  // token-major: a lane holds one feature column and 4-token runs; for a fixed accumulator element
+  // the 32 lanes of a half-wave update 128 contiguous bytes of one row of x
+  gemm_mainloop<TM, TN, false>(p.A, p.W, p.d, m0, n0, lds, acc);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int c = n0 + wn * 64 + j * 32 + l32;
+    const float bias = bf16_bits_to_float(p.bias[c]);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int row = m0 + wm * 64 + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
+        if (row < p.row_end) {
+          float* xp = p.x + (size_t)row * p.d + c;
+          *xp = *xp + acc[i][j][e] + bias;
+        }
+      }
+  }
+}
+
+}  // namespace relaygr

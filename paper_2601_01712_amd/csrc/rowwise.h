@@ -26,7 +26,8 @@ __global__ void build_rows_kernel(const UserDesc* __restrict__ users, const int3
   int kind, idx, lim, src;
   if (r < n_prows) {
     idx = r - start[lo];
-    kind = kRowPrefix; lim = idx + 1; src = ud.prefix_src0 + idx;
+    if (idx < ud.L) { kind = kRowPrefix; lim = idx + 1; src = ud.prefix_src0 + idx; }
+    else            { kind = kRowPad; lim = 0; src = 0; }
   } else {
     int t = r - start[lo];
     if (t < ud.S) { kind = kRowSuffix; idx = t; lim = ud.L + t + 1; src = ud.suffix_src0 + t; }
@@ -48,10 +49,29 @@ __device__ __forceinline__ void ln_stats(const float (&v)[E], int d, float eps, 
   rstd = rsqrtf(wave_sum(q) / (float)d + eps);
 }
 
+// Writes a lane's E consecutive features [lane*E, lane*E+E) of row r, either row-major or into the
+// MFMA-ordered panels the bf16 GEMM reads (E and 8 divide one another, so a lane's run never
+// straddles a 16-byte fragment chunk unless it is made of whole chunks).
+template <typename T, int E, bool PANEL>
+__device__ __forceinline__ void store_row_run(T* __restrict__ out, int r, int lane, int d, const float (&v)[E]) {
+  if (PANEL) {
+    constexpr int RUN = E < 8 ? E : 8;
+#pragma unroll
+    for (int c = 0; c < E; c += RUN) {
+      T* dst = out + panel_off(r, lane * E + c, d);
+#pragma unroll
+      for (int i = 0; i < RUN; ++i) Elem<T>::st(dst + i, v[c + i]);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < E; ++i) Elem<T>::st(out + (size_t)r * d + lane * E + i, v[i]);
+  }
+}
+
 // Input LayerNorm of a layer (step 1 of a layer): xh = LN(x; g, b) in the storage type.
 // With GATHER (first layer) the row is first fetched from its embedding array and also written to
 // the fp32 residual stream x.
-template <typename T, int E, bool GATHER>
+template <typename T, int E, bool GATHER, bool PANEL>
 __global__ __launch_bounds__(256) void ln_in_kernel(float* __restrict__ x, T* __restrict__ xh,
                                                     const T* __restrict__ gain, const T* __restrict__ offs,
                                                     const T* __restrict__ emb_prefix, const T* __restrict__ emb_suffix,
@@ -62,8 +82,14 @@ __global__ __launch_bounds__(256) void ln_in_kernel(float* __restrict__ x, T* __
   if (r >= row_end) return;
   int lane = threadIdx.x & 63;
   float v[E];
+  const int kind = rt.kind[r];
+  if (kind == kRowPad) {   // keep filler rows finite
+#pragma unroll
+    for (int i = 0; i < E; ++i) v[i] = 0.f;
+    store_row_run<T, E, PANEL>(xh, r, lane, d, v);
+    return;
+  }
   if (GATHER) {
-    int kind = rt.kind[r];
     const T* e = (kind == kRowPrefix ? emb_prefix : kind == kRowSuffix ? emb_suffix : emb_cand) + (size_t)rt.src[r] * d + lane * E;
 #pragma unroll
     for (int i = 0; i < E; ++i) { v[i] = Elem<T>::ld(e + i); x[(size_t)r * d + lane * E + i] = v[i]; }
@@ -76,8 +102,9 @@ __global__ __launch_bounds__(256) void ln_in_kernel(float* __restrict__ x, T* __
 #pragma unroll
   for (int i = 0; i < E; ++i) {
     int f = lane * E + i;
-    Elem<T>::st(xh + (size_t)r * d + f, (v[i] - mean) * rstd * Elem<T>::ld(gain + f) + Elem<T>::ld(offs + f));
+    v[i] = (v[i] - mean) * rstd * Elem<T>::ld(gain + f) + Elem<T>::ld(offs + f);
   }
+  store_row_run<T, E, PANEL>(xh, r, lane, d, v);
 }
 
 // Attention combine + gate (steps 3-4 of a layer, everything after the key loop):
@@ -87,7 +114,7 @@ __global__ __launch_bounds__(256) void ln_in_kernel(float* __restrict__ x, T* __
 // sequence, added here in split order (fixed order => reproducible bits).  A candidate's self
 // term SiLU(alpha <q_c^h, k_c^h>) v_c^h is evaluated here from the row's own q, k, v.
 // qk_mul turns the stored q into alpha*q (q may be stored pre-scaled).
-template <typename T, int E>
+template <typename T, int E, bool PANEL>
 __global__ __launch_bounds__(256) void attn_gate_kernel(const float* __restrict__ part, int nsplit, size_t split_stride,
                                                         const T* __restrict__ u, const T* __restrict__ q,
                                                         const T* __restrict__ knew, const T* __restrict__ vnew,
@@ -100,6 +127,12 @@ __global__ __launch_bounds__(256) void attn_gate_kernel(const float* __restrict_
   int lane = threadIdx.x & 63;
   size_t base = (size_t)r * d + lane * E;
   float o[E];
+  if (rt.kind[r] == kRowPad) {
+#pragma unroll
+    for (int i = 0; i < E; ++i) o[i] = 0.f;
+    store_row_run<T, E, PANEL>(y, r, lane, d, o);
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < E; ++i) o[i] = 0.f;
   for (int s = 0; s < nsplit; ++s) {
@@ -128,8 +161,9 @@ __global__ __launch_bounds__(256) void attn_gate_kernel(const float* __restrict_
   for (int i = 0; i < E; ++i) {
     int f = lane * E + i;
     float z = (o[i] - mean) * rstd * Elem<T>::ld(gain + f) + Elem<T>::ld(offs + f);
-    Elem<T>::st(y + base + i, z * Elem<T>::ld(u + base + i));
+    o[i] = z * Elem<T>::ld(u + base + i);
   }
+  store_row_run<T, E, PANEL>(y, r, lane, d, o);
 }
 
 // Score head: score_c = <w_s, LN(x_c; g_out, b_out)> + b_s for candidate rows, written at the

@@ -190,7 +190,7 @@ def test_stale_handle_is_reported_and_fallback_gives_the_same_scores():
 
 def test_scratch_too_small_is_an_error_not_a_fault():
     cfg = synth.ModelConfig(2, 128, 2, "bf16")
-    weights, batch = build_case(cfg, 98, [500], [0], [50])
+    weights, batch = build_case(cfg, 98, [6000], [0], [500])
     ctx = rg.Context(cfg, weights, 1, 64, 64)     # sized for a much smaller call
     try:
         with pytest.raises(rg.RelayGRError) as e:
