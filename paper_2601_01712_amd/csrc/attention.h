@@ -26,6 +26,7 @@ struct AttnParams {
   float* part;        // [nsplit][rows][d]
   size_t split_stride;
   int nsplit;
+  int n_tiles;        // work items in this launch
   int d, n_heads, layer;
   float score_mul;    // multiplies <q,k> before SiLU (alpha, or 1 if q is stored pre-scaled)
 };
@@ -111,76 +112,118 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(AttnParams p) {
 
 // ---- bf16 MFMA kernel ---------------------------------------------------------------------------
 // A workgroup of 4 wavefronts owns up to 128*NQ rows (each wavefront NQ blocks of 32 rows) of one
-// user and one head and walks the key tiles of its split.  Per 64-key tile and wavefront:
-//   S^T[64 keys][32 rows]  = K tile (A operand, rows = keys)  x  Q^T (B operand, held in registers)
+// user and one head and walks the key tiles of its split.  Per 32-key half tile and wavefront:
+//   S^T[32 keys][32 rows]  = K half (A operand, rows = keys)  x  Q^T (B operand, held in registers)
 //   P^T = SiLU'(S^T) rounded to bf16 -- the accumulator layout of S^T (lane = row, 4-key runs) is
 //         exactly the B-operand layout of the next product once the V fragment holds the same key
 //         permutation (it does, see the layout note in common.h), so P never leaves registers
-//   O^T[dh][32 rows]      += V^T tile (A operand, rows = features) x P^T
+//   O^T[dh][32 rows]      += V^T half (A operand, rows = features) x P^T
 // q is stored pre-multiplied by alpha*log2(e); SiLU'(t) = t / (1 + 2^-t) = SiLU(s)/ln 2 with
 // s = t ln 2, and the ln 2 is applied once to the output.
 //
 // A K/V tile in HBM is already the LDS image (fragment order), so tiles stream HBM -> LDS with
-// direct 16-byte-per-lane loads into a double buffer, one barrier per tile, and every MFMA operand
-// is one linear ds_read_b128.  The arithmetic that bounds this kernel is the SiLU: one v_exp_f32
-// and one v_rcp_f32 (quarter-rate) plus add, multiply and a packed bf16 convert per score element,
-// against 2*DH/32 MFMA passes; everything else in the loop is kept off the vector ALU.
+// direct 16-byte-per-lane loads into a ring of three buffers, one barrier per tile, and every MFMA
+// operand is one linear ds_read_b128.  The loop is software-pipelined by half tiles: while the
+// vector ALU evaluates the SiLU of half h, the matrix pipe runs the first product of half h+1 and
+// the second product of half h-1, none of which depend on that SiLU.  What bounds the kernel is the SiLU itself: one v_exp_f32 and one v_rcp_f32
+// (quarter-rate) plus add, multiply and half a packed bf16 convert per score element, against
+// 2*DH/32 MFMA passes per 32 x 32 block.
 
-template <int DH, int NQ, bool MASKED>
-__device__ __forceinline__ void attn_tile_step(const uint16_t* __restrict__ buf, const bf16x8_t (&qf)[NQ][DH / 16],
-                                               f32x16_t (&oacc)[DH / 32][NQ], const int (&vis)[NQ], int lane) {
-  constexpr int KS = DH / 16, DB = DH / 32;
-  const int g = lane >> 5;
-  const uint16_t* kfrag = buf + lane * 8;
-  const uint16_t* vfrag = buf + kTile * DH + lane * 8;
+template <int DH, int NQ>
+__device__ __forceinline__ void attn_s_half(const uint16_t* __restrict__ khalf, const bf16x8_t (&qf)[NQ][DH / 16],
+                                            f32x16_t (&s)[NQ]) {
+  constexpr int KS = DH / 16;
 #pragma unroll
-  for (int kb = 0; kb < 2; ++kb) {
-    f32x16_t s[NQ];
+  for (int qb = 0; qb < NQ; ++qb)
 #pragma unroll
-    for (int qb = 0; qb < NQ; ++qb)
+    for (int e = 0; e < 16; ++e) s[qb][e] = 0.f;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) s[qb][e] = 0.f;
+  for (int ks = 0; ks < KS; ++ks) {
+    bf16x8_t kf = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(khalf + ks * 512));
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      bf16x8_t kf = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(kfrag + (kb * KS + ks) * 512));
+    for (int qb = 0; qb < NQ; ++qb) s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], s[qb], 0, 0, 0);
+  }
+}
+
+template <int DH, int NQ>
+__device__ __forceinline__ void attn_pv_half(const uint16_t* __restrict__ vhalf, const uint32_t (&pk)[NQ][8],
+                                             f32x16_t (&oacc)[DH / 32][NQ]) {
+  constexpr int DB = DH / 32;
 #pragma unroll
-      for (int qb = 0; qb < NQ; ++qb) s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], s[qb], 0, 0, 0);
-    }
-    // element e of s: key kb*32 + 8*(e/4) + 4*g + e%4 of the tile, row l32 of block qb
-    uint32_t pk[NQ][8];
+  for (int m = 0; m < 2; ++m) {
 #pragma unroll
-    for (int qb = 0; qb < NQ; ++qb) {
+    for (int db = 0; db < DB; ++db) {
+      bf16x8_t vf = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(vhalf + (db * 4 + m) * 512));
 #pragma unroll
-      for (int e2 = 0; e2 < 8; ++e2) {
-        f32x2_t pv;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          const int e = 2 * e2 + h;
-          float t = s[qb][e];
-          float pe = t * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-t));
-          if (MASKED) {
-            const int key = kb * 32 + 8 * (e >> 2) + (e & 3);   // + 4*g, folded into vis by the caller
-            pe = (key < vis[qb]) ? pe : 0.f;
-          }
-          pv[h] = pe;
-        }
-        pk[qb][e2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pv, bf16x2_t));   // one v_cvt_pk_bf16_f32
-      }
-    }
-#pragma unroll
-    for (int m = 0; m < 2; ++m) {
-#pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        bf16x8_t vf = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(vfrag + ((db * 2 + kb) * 2 + m) * 512));
-#pragma unroll
-        for (int qb = 0; qb < NQ; ++qb) {
-          uint4 pp = make_uint4(pk[qb][4 * m], pk[qb][4 * m + 1], pk[qb][4 * m + 2], pk[qb][4 * m + 3]);
-          oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, __builtin_bit_cast(bf16x8_t, pp), oacc[db][qb], 0, 0, 0);
-        }
+      for (int qb = 0; qb < NQ; ++qb) {
+        uint4 pp = make_uint4(pk[qb][4 * m], pk[qb][4 * m + 1], pk[qb][4 * m + 2], pk[qb][4 * m + 3]);
+        oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, __builtin_bit_cast(bf16x8_t, pp), oacc[db][qb], 0, 0, 0);
       }
     }
   }
-  (void)g;
+}
+
+// One pipeline step of a wavefront: the SiLU of the half tile whose first product is in s_in runs
+// on the vector ALU while the matrix pipe computes the first product of the following half
+// (khalf -> s_out) and the second product owed from the preceding half (vhalf, pk_in -> oacc).
+// A wavefront issues in order and an MFMA cannot issue while the matrix pipe still works on the
+// previous one, so MFMAs placed back to back would leave the vector ALU idle behind them.  The
+// step is therefore cut into slots -- NQ MFMAs, then the SiLU of 128/DH score elements per row
+// block, about as long as those MFMAs take -- and the scheduler is fenced between slots.
+template <int DH, int NQ, bool MASKED>
+__device__ __forceinline__ void attn_step(const uint16_t* __restrict__ khalf, const uint16_t* __restrict__ vhalf,
+                                          const bf16x8_t (&qf)[NQ][DH / 16], const f32x16_t (&s_in)[NQ], f32x16_t (&s_out)[NQ],
+                                          const uint32_t (&pk_in)[NQ][8], uint32_t (&pk_out)[NQ][8],
+                                          f32x16_t (&oacc)[DH / 32][NQ], const int (&vis)[NQ]) {
+  constexpr int KS = DH / 16, DB = DH / 32;
+  constexpr int SLOTS = KS + 2 * DB;      // = DH / 8
+  constexpr int EPS = 16 / SLOTS > 0 ? 16 / SLOTS : 1;   // score elements per row block and slot
+  static_assert(SLOTS * EPS == 16 || (SLOTS == 16 && EPS == 1), "slot split");
+  bf16x8_t kf[KS], vf[2][DB];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) kf[ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(khalf + ks * 512));
+#pragma unroll
+  for (int m = 0; m < 2; ++m)
+#pragma unroll
+    for (int db = 0; db < DB; ++db) vf[m][db] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(vhalf + (db * 4 + m) * 512));
+#pragma unroll
+  for (int qb = 0; qb < NQ; ++qb)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) s_out[qb][e] = 0.f;
+  float pv[NQ][16];
+#pragma unroll
+  for (int slot = 0; slot < SLOTS; ++slot) {
+    // matrix pipe: alternate the two products so that dependent MFMAs are two slots apart
+    const bool first = (slot % 2 == 0);     // KS == 2*DB: even slots feed the first product, odd the second
+    const int si = slot / 2;
+    if (first) {
+#pragma unroll
+      for (int qb = 0; qb < NQ; ++qb) s_out[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[si], qf[qb][si], s_out[qb], 0, 0, 0);
+    } else {
+      const int m = si / DB, db = si % DB;
+#pragma unroll
+      for (int qb = 0; qb < NQ; ++qb) {
+        uint4 pp = make_uint4(pk_in[qb][4 * m], pk_in[qb][4 * m + 1], pk_in[qb][4 * m + 2], pk_in[qb][4 * m + 3]);
+        oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[m][db], __builtin_bit_cast(bf16x8_t, pp), oacc[db][qb], 0, 0, 0);
+      }
+    }
+    // vector ALU: SiLU' of this slot's score elements; element e is key 8*(e/4) + 4*g + e%4 of the half
+#pragma unroll
+    for (int qb = 0; qb < NQ; ++qb) {
+#pragma unroll
+      for (int e = slot * EPS; e < (slot + 1) * EPS; ++e) {
+        const float t = s_in[qb][e];
+        float pe = t * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-t));
+        if (MASKED) pe = (8 * (e >> 2) + (e & 3) < vis[qb]) ? pe : 0.f;
+        pv[qb][e] = pe;
+        if (e & 1) {
+          f32x2_t two = {pv[qb][e - 1], pv[qb][e]};
+          pk_out[qb][e >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2_t));   // one v_cvt_pk_bf16_f32
+        }
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
 }
 
 template <int DH, int NQ>
@@ -189,10 +232,18 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p) {
   constexpr int DB = DH / 32;              // 32-feature blocks of the output
   constexpr int TILE = 2 * kTile * DH;     // elements of one K tile + one V tile
   constexpr int CHUNKS = TILE / 8 / 256;   // 16-byte chunks each thread moves per tile
-  __shared__ __attribute__((aligned(16))) uint16_t bufs[2][TILE];
+  __shared__ __attribute__((aligned(16))) uint16_t bufs[3][TILE];
 
-  const AttnTile at = p.tiles[blockIdx.x];
-  const int head = blockIdx.y, split = blockIdx.z;
+  // Work items that stream the same K/V (row tiles of one user, same head and split) get
+  // consecutive logical ids, and each of the 8 XCDs (own L2 each; workgroups are dealt to them
+  // round-robin) takes a contiguous run of logical ids: the K/V tiles are then fetched from HBM
+  // once per XCD and found in its L2 by the neighbouring row tiles.
+  const int total = p.n_tiles * p.n_heads * p.nsplit;
+  const int logical = xcd_remap(blockIdx.x, total);
+  if (logical >= total) return;
+  const int tile_i = logical % p.n_tiles, hs = logical / p.n_tiles;
+  const int head = hs % p.n_heads, split = hs / p.n_heads;
+  const AttnTile at = p.tiles[tile_i];
   const UserDesc ud = p.users[at.user];
   const TileRange tr = tile_range(at, ud, split, p.nsplit);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -237,25 +288,70 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p) {
     }
   };
 
-  if (tr.t0 < tr.t1) issue_tile(tr.t0, 0);
-  for (int tt = tr.t0; tt < tr.t1; ++tt) {
-    const int b = (tt - tr.t0) & 1;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();                                  // tile tt has landed; everyone is done with the other buffer
-    if (tt + 1 < tr.t1) issue_tile(tt + 1, b ^ 1);
-
-    const bool is_sfx = tt >= tr.nkp;
-    if (!is_sfx && tt < tr.nfull) {
-      const int none[NQ] = {};
-      attn_tile_step<DH, NQ, false>(bufs[b], qf, oacc, none, lane);
+  const int nt = tr.t1 - tr.t0;
+  if (nt > 0) {
+    issue_tile(tr.t0, 0);
+    if (nt > 1) {
+      issue_tile(tr.t0 + 1, 1);
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(CHUNKS) : "memory");   // tile 0 landed, tile 1 may still fly
     } else {
-      const int key0 = is_sfx ? ud.L + (tt - tr.nkp) * kTile : tt * kTile;
-      const int seg_end = is_sfx ? ud.L + ud.S : ud.L;
-      int vis[NQ];   // keys [0, vis) of this tile are visible, shifted by this lane's 4*g key offset
-#pragma unroll
-      for (int qb = 0; qb < NQ; ++qb) vis[qb] = min(lim[qb], seg_end) - key0 - 4 * g;
-      attn_tile_step<DH, NQ, true>(bufs[b], qf, oacc, vis, lane);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
+    __syncthreads();
+
+    // Pipeline state.  s_cur: first product of the half about to get its SiLU.  pk_prev: P of the
+    // half before it, whose second product is still owed, with vprev pointing at its V half.
+    f32x16_t s_cur[NQ], s_nxt[NQ];
+    uint32_t pk_a[NQ][8], pk_b[NQ][8];
+#pragma unroll
+    for (int qb = 0; qb < NQ; ++qb)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) pk_b[qb][e] = 0u;          // nothing owed yet: P = 0 adds nothing
+    const uint16_t* vprev = &bufs[0][lane * 8] + kTile * DH;  // any finite V will do with P = 0
+    attn_s_half<DH, NQ>(&bufs[0][lane * 8], qf, s_cur);
+    int b = 0;                                                 // ring slot of tile i
+
+    // one tile = two pipeline steps; MASKED tiles apply the per-element visibility test
+    auto tile_iter = [&](auto masked_tag, int i) {
+      constexpr bool MASKED = decltype(masked_tag)::value;
+      int vis[NQ] = {};
+      if (MASKED) {
+        const int tt = tr.t0 + i;
+        const bool is_sfx = tt >= tr.nkp;
+        const int key0 = is_sfx ? ud.L + (tt - tr.nkp) * kTile : tt * kTile;
+        const int seg_end = is_sfx ? ud.L + ud.S : ud.L;
+#pragma unroll
+        for (int qb = 0; qb < NQ; ++qb) vis[qb] = min(lim[qb], seg_end) - key0 - 4 * g;
+      }
+      const uint16_t* kt = &bufs[b][lane * 8];
+      const uint16_t* vt = kt + kTile * DH;
+      // step 1: SiLU of the first half | first product of the second half, second product owed from before
+      attn_step<DH, NQ, MASKED>(kt + KS * 512, vprev, qf, s_cur, s_nxt, pk_b, pk_a, oacc, vis);
+      // the next tile must have landed before its first product; every wavefront is now past tile i-1
+      const int bn = (b == 2) ? 0 : b + 1;
+      const bool more = i + 1 < nt;
+      if (more) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (i + 2 < nt) issue_tile(tr.t0 + i + 2, (bn == 2) ? 0 : bn + 1);
+      }
+      // step 2: SiLU of the second half | first product of the next tile's first half (a repeat of
+      // this tile's when there is none: its result is dropped), second product of the first half
+      if (MASKED) {
+#pragma unroll
+        for (int qb = 0; qb < NQ; ++qb) vis[qb] -= 32;
+      }
+      attn_step<DH, NQ, MASKED>(more ? &bufs[bn][lane * 8] : kt, vt, qf, s_nxt, s_cur, pk_a, pk_b, oacc, vis);
+      vprev = vt + 2 * 512;
+      b = bn;
+    };
+
+    // tiles of this split in order: [fully visible prefix tiles][tiles needing the visibility test]
+    const int n_plain = max(0, min(tr.t1, tr.nfull) - tr.t0);
+    int i = 0;
+    for (; i < n_plain; ++i) tile_iter(std::false_type(), i);
+    for (; i < nt; ++i) tile_iter(std::true_type(), i);
+    attn_pv_half<DH, NQ>(vprev, pk_b, oacc);                   // the last half's second product
   }
 
   // element e of oacc[db][qb]: feature db*32 + 8*(e/4) + 4*g + e%4, row l32 of block qb

@@ -89,7 +89,8 @@ struct Plan {
   size_t total = 0;
 };
 
-static int rows_per_attn_tile(const relaygr_model_config& c) { return c.dtype == RELAYGR_DTYPE_FP32 ? 64 : 128; }
+// Rows per attention work item: 64 (fp32), or 128 * nq for the MFMA kernel, nq in {1, 2}.
+static int rows_per_attn_tile(const relaygr_model_config& c, int nq) { return c.dtype == RELAYGR_DTYPE_FP32 ? 64 : 128 * nq; }
 
 // Lays the call's buffers out in scratch.  Everything is a function of the counts already in p.
 // Bytes at the start of scratch that hold the weights re-packed into MFMA panels (bf16 only).
@@ -130,7 +131,7 @@ static void carve(const relaygr_model_config& c, Plan& p) {
 static int wanted_splits(int n_tiles, int n_heads, int min_key_tiles) {
   if (n_tiles <= 0) return 1;
   int wgs = n_tiles * n_heads;
-  int s = (512 + wgs - 1) / wgs;
+  int s = (256 + wgs - 1) / wgs;
   s = std::min(s, 8);
   s = std::min(s, std::max(1, min_key_tiles));
   return std::max(s, 1);
@@ -149,7 +150,7 @@ extern "C" size_t relaygr_scratch_bytes(const relaygr_model_config* cfg, int32_t
   p.n_rows = p.n_prows + p.n_nrows;
   p.sfx_tiles = max_new_tokens / kTile + max_users;
   p.kvs_tiles = max_prefix_tokens / kTile + max_users;
-  int rpt = rows_per_attn_tile(*cfg);
+  int rpt = rows_per_attn_tile(*cfg, 1);
   p.n_tiles_new = (int)(max_new_tokens / rpt) + max_users;
   p.n_tiles_prefix = (int)(padded / rpt) + max_users;
   p.nsplit = 1;
@@ -432,10 +433,10 @@ template <> struct GemmLaunch<__hip_bfloat16> {
 };
 
 template <typename T>
-static int launch_attention(const relaygr_model_config& cfg, const AttnParams& ap, int n_tiles, hipStream_t st);
+static int launch_attention(const relaygr_model_config& cfg, const AttnParams& ap, int n_tiles, int nq, hipStream_t st);
 
 template <>
-int launch_attention<float>(const relaygr_model_config& cfg, const AttnParams& ap, int n_tiles, hipStream_t st) {
+int launch_attention<float>(const relaygr_model_config& cfg, const AttnParams& ap, int n_tiles, int, hipStream_t st) {
   dim3 grid(n_tiles, cfg.n_heads, ap.nsplit);
   switch (cfg.d_model / cfg.n_heads) {
     case 32: hipLaunchKernelGGL((attn_f32_kernel<32>), grid, dim3(64), 0, st, ap); break;
@@ -448,11 +449,15 @@ int launch_attention<float>(const relaygr_model_config& cfg, const AttnParams& a
 }
 
 template <>
-int launch_attention<__hip_bfloat16>(const relaygr_model_config& cfg, const AttnParams& ap, int n_tiles, hipStream_t st) {
-  dim3 grid(n_tiles, cfg.n_heads, ap.nsplit);
+int launch_attention<__hip_bfloat16>(const relaygr_model_config& cfg, const AttnParams& ap, int n_tiles, int nq, hipStream_t st) {
+  int total = n_tiles * cfg.n_heads * ap.nsplit;
+  dim3 grid((total + 7) / 8 * 8);
   switch (cfg.d_model / cfg.n_heads) {
     case 32: hipLaunchKernelGGL((attn_bf16_kernel<32, 1>), grid, dim3(256), 0, st, ap); break;
-    case 64: hipLaunchKernelGGL((attn_bf16_kernel<64, 1>), grid, dim3(256), 0, st, ap); break;
+    case 64:
+      if (nq == 2) hipLaunchKernelGGL((attn_bf16_kernel<64, 2>), grid, dim3(256), 0, st, ap);
+      else hipLaunchKernelGGL((attn_bf16_kernel<64, 1>), grid, dim3(256), 0, st, ap);
+      break;
     case 128: hipLaunchKernelGGL((attn_bf16_kernel<128, 1>), grid, dim3(256), 0, st, ap); break;
     default: return fail(RELAYGR_EINVAL, "attention: unsupported d_head");
   }
@@ -473,7 +478,6 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
   const relaygr_model_config& cfg = c->cfg;
   const int d = cfg.d_model, H = cfg.n_heads, dh = d / H, NL = cfg.n_layers, n = b->n_users;
   const bool bf16 = cfg.dtype == RELAYGR_DTYPE_BF16;
-  const int rpt = rows_per_attn_tile(cfg);
   const int palign = prefix_row_align(cfg);
 
   // -- per-user shapes and K/V sources
@@ -539,6 +543,20 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
     if (!b->cand_emb && b->cand_off && b->cand_off[n] > 0) return fail(RELAYGR_EINVAL, "candidates present but cand_emb is null");
     if (!scores) return fail(RELAYGR_EINVAL, "scores_dev is null");
   }
+
+  // Rows per attention work item.  The MFMA kernel reads half as much LDS and L2 per score element
+  // with 256-row items (two row blocks per wavefront); use them when that still yields at least
+  // one workgroup per compute unit.
+  int nq = 1;
+  if (bf16 && dh == 64) {
+    int64_t items256 = 0;
+    for (int u = 0; u < n; ++u) {
+      if (users[u].nrow0 >= 0) items256 += (users[u].S + users[u].M + 255) / 256;
+      if (users[u].prow0 >= 0) items256 += (users[u].L + 255) / 256;
+    }
+    if (items256 * H >= 256) nq = 2;
+  }
+  const int rpt = rows_per_attn_tile(cfg, nq);
 
   // -- attention work items: new-row tiles first (kept when the last layer skips prefix rows),
   //    each group sorted by key-tile count, longest first
@@ -702,9 +720,10 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
     ap.tiles = d_tiles; ap.users = d_users; ap.rt = rt; ap.q = qbuf; ap.sfx = sfx; ap.part = part;
     ap.split_stride = (size_t)R * d; ap.nsplit = p.nsplit; ap.d = d; ap.n_heads = H; ap.layer = l; ap.score_mul = score_mul;
     int nt = last ? p.n_tiles_new : n_tiles_all;
+    ap.n_tiles = nt;
     if (nt > 0) {
       ProfScope ps(c, RELAYGR_K_ATTN, st);
-      rc = launch_attention<T>(cfg, ap, nt, st);
+      rc = launch_attention<T>(cfg, ap, nt, nq, st);
       if (rc != RELAYGR_OK) return rc;
     }
     // steps 3-4: combine splits, self term, 1/n, LayerNorm, gate by u

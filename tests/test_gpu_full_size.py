@@ -1,0 +1,74 @@
+"""GPU parity at the benchmark's full sizes (C3, C4, C5), in the launch configuration bench.py times.
+
+Users are independent, so the oracle checks whole users sampled from the batch (every candidate of
+those users, element by element, to the same tolerance as the small cases); for all other users the
+test checks what holds at any size: ranking on the cached prefix and full recompute, two different
+kernel sequences, must agree (Section 2.3 of the paper), scores must be finite, and a second call
+must reproduce the first bit for bit.
+"""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2601_01712_amd as rg
+import synth
+from gpu_util import Harness, assert_close, oracle_scores, TOL
+
+pytestmark = pytest.mark.gpu
+
+
+def run_full(name, sample_users, page_tokens=256):
+    wl = synth.WORKLOADS[name]
+    cfg = wl.model
+    t0 = time.time()
+    weights = synth.make_weights(cfg, wl.seed)
+    batch = synth.make_batch(wl, 0)
+    L, S, M, cached = synth.make_lengths(wl, 0)
+    print(f"\n  {name}: inputs in {time.time() - t0:.1f}s; users {wl.n_users}, prefix tokens {int(L.sum())}, "
+          f"candidates {int(M.sum())}, uncached {int((~cached).sum())}", flush=True)
+    h = Harness(cfg, weights, batch, page_tokens)
+    try:
+        h.prefill([u for u in range(wl.n_users) if cached[u]])
+        got_cached = h.rank_cached()
+        again = h.rank_cached()
+        got_full = h.rank_full()
+        assert np.isfinite(got_cached).all() and np.isfinite(got_full).all()
+        assert np.array_equal(got_cached, again), "two identical calls must give identical bits"
+        scale = max(1.0, float(np.abs(got_full).max()))
+        diff = float(np.abs(got_cached - got_full).max())
+        assert diff <= 2 * TOL[cfg.dtype] * scale, f"cached vs full recompute differ by {diff:.3e}"
+        t1 = time.time()
+        want = oracle_scores(cfg, weights, batch, users=sample_users)
+        e1 = h.check(got_cached, want, f"{name} rank_with_cache")
+        e2 = h.check(got_full, want, f"{name} rank_full_recompute")
+        print(f"  {name}: oracle on users {list(sample_users)} in {time.time() - t1:.1f}s; max err cached {e1:.2e}, "
+              f"full {e2:.2e}; cached vs full over all users {diff:.2e}", flush=True)
+        return L, S, M, cached
+    finally:
+        h.close()
+
+
+def test_c3_full_size_sampled_users():
+    run_full("C3", sample_users=[0, 11])
+
+
+def test_c4_full_size_sampled_user_and_kv_footprint():
+    run_full("C4", sample_users=[5])
+    cfg = rg.make_config(8, 512, 8, "bf16")
+    assert rg.relaygr_kv_footprint_bytes(cfg, 8192) == 134217728     # per-user KV bytes of this workload
+
+
+def test_c5_jagged_batch_with_uncached_users():
+    wl = synth.WORKLOADS["C5"]
+    L, S, M, cached = synth.make_lengths(wl, 0)
+    order = np.argsort(L)
+    miss = [u for u in order if not cached[u]]
+    hit = [u for u in order if cached[u]]
+    # the shortest cached user, a mid-length uncached user, and a cached user with a long suffix (all below
+    # ~6K prefix tokens so that the float64 oracle stays within a minute)
+    mid_miss = [u for u in miss if L[u] <= 6000][-1]
+    with_sfx = max([u for u in hit if L[u] <= 5000], key=lambda u: S[u])
+    sample = sorted({int(hit[0]), int(mid_miss), int(with_sfx)})
+    run_full("C5", sample_users=sample)
