@@ -39,26 +39,31 @@ __global__ void pack_weight_kernel(const __hip_bfloat16* __restrict__ w, __hip_b
 
 // ---- main loop ----------------------------------------------------------------------------------
 // Workgroup tile: 64*TM tokens x 64*TN features, 4 wavefronts as 2 x 2, each owning TM x TN blocks of
-// 32 x 32.  LDS holds two stages of [token pieces | feature pieces], a piece being one 1 KiB fragment.
-template <int TM, int TN>
+// 32 x 32.  LDS holds a ring of NSTAGE stages of [token pieces | feature pieces], a piece being one
+// 1 KiB fragment; NSTAGE-1 stages are in flight while one is consumed, because with K of a few
+// hundred a tile is short and the ramp of its operand stream would otherwise dominate it.
+template <int TM, int TN, int NSTAGE>
 struct GemmTile {
   static constexpr int BMt = 64 * TM, BNf = 64 * TN;
   static constexpr int TOK_PIECES = (BMt / 32) * 2, FEAT_PIECES = (BNf / 32) * 2;   // per stage (2 k-steps)
   static constexpr int PIECES = TOK_PIECES + FEAT_PIECES;
   static constexpr int STAGE = PIECES * 512;   // elements
+  static constexpr int LDS_ELEMS = NSTAGE * STAGE;
+  static constexpr int LOADS_PER_WAVE = PIECES / 4;
+  static_assert(PIECES % 4 == 0, "pieces are dealt evenly to the 4 wavefronts");
 };
 
 // FEATURE_MAJOR: features are the MFMA row operand (lane = token column, 4-feature runs per lane).
-template <int TM, int TN, bool FEATURE_MAJOR>
+template <int TM, int TN, int NSTAGE, bool FEATURE_MAJOR>
 __device__ __forceinline__ void gemm_mainloop(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W, int K, int m0, int n0,
                                               uint16_t* lds, f32x16_t (&acc)[TM][TN]) {
-  using G = GemmTile<TM, TN>;
+  using G = GemmTile<TM, TN, NSTAGE>;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int KS = K >> 4;
   // piece p of a stage: token pieces first, ordered [panel][ksl][rb]; then feature pieces [npanel][ksl][nb]
-  auto issue = [&](int kt, int stage) {
-    uint16_t* dst = lds + stage * G::STAGE;
+  auto issue = [&](int kt, int slot) {
+    uint16_t* dst = lds + slot * G::STAGE;
 #pragma unroll
     for (int p = wave; p < G::PIECES; p += 4) {
       const uint16_t* src;
@@ -82,13 +87,18 @@ __device__ __forceinline__ void gemm_mainloop(const uint16_t* __restrict__ A, co
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   const int n_kt = K / kGemmKTile;
-  issue(0, 0);
+#pragma unroll
+  for (int s = 0; s < NSTAGE - 1; ++s)
+    if (s < n_kt) issue(s, s);
+  int slot = 0;
   for (int kt = 0; kt < n_kt; ++kt) {
-    const int stage = kt & 1;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (kt + 1 < n_kt) issue(kt + 1, stage ^ 1);
-    const uint16_t* tokp = lds + stage * G::STAGE + lane * 8;
+    // stage kt must have landed; the NSTAGE-2 younger stages may stay in flight (near the end fewer
+    // are outstanding, so wait for all of them there)
+    if (kt + NSTAGE - 2 < n_kt) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSTAGE - 2) * G::LOADS_PER_WAVE) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();     // also: every wavefront is past stage kt-1, whose slot is refilled next
+    if (kt + NSTAGE - 1 < n_kt) issue(kt + NSTAGE - 1, slot == 0 ? NSTAGE - 1 : slot - 1);
+    const uint16_t* tokp = lds + slot * G::STAGE + lane * 8;
     const uint16_t* featp = tokp + G::TOK_PIECES * 512;
 #pragma unroll
     for (int ksl = 0; ksl < 2; ++ksl) {
@@ -110,6 +120,7 @@ __device__ __forceinline__ void gemm_mainloop(const uint16_t* __restrict__ A, co
           acc[i][j] = FEATURE_MAJOR ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(ff[j], tf[i], acc[i][j], 0, 0, 0)
                                     : __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf[i], ff[j], acc[i][j], 0, 0, 0);
     }
+    slot = (slot == NSTAGE - 1) ? 0 : slot + 1;
   }
   __syncthreads();   // every wavefront is done reading LDS: the epilogue may reuse it
 }
@@ -132,13 +143,13 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
-constexpr int kF1TM = 4, kF1TN = 2;               // 256 tokens x 128 features per workgroup
+constexpr int kF1TM = 4, kF1TN = 2, kF1Stages = 3;   // 256 tokens x 128 features per workgroup
 constexpr int kStageLd = 64 * kF1TN + 8;          // epilogue staging row stride (elements)
 
 __global__ __launch_bounds__(256, 2) void f1_gemm_bf16_kernel(F1Params p) {
   constexpr int TM = kF1TM, TN = kF1TN;
-  using G = GemmTile<TM, TN>;
-  constexpr int LDS_ELEMS = (2 * G::STAGE > 128 * kStageLd) ? 2 * G::STAGE : 128 * kStageLd;
+  using G = GemmTile<TM, TN, kF1Stages>;
+  constexpr int LDS_ELEMS = (G::LDS_ELEMS > 128 * kStageLd) ? G::LDS_ELEMS : 128 * kStageLd;
   __shared__ __attribute__((aligned(16))) uint16_t lds[LDS_ELEMS];
 
   const int ntiles_per_blk = p.cm.d / G::BNf;
@@ -164,7 +175,7 @@ __global__ __launch_bounds__(256, 2) void f1_gemm_bf16_kernel(F1Params p) {
   if (blk == 1 && prefix_tile) {
     // ---- V of prefix rows: token-major product; the accumulator of a 32-token x 32-feature block
     // is, lane for lane, two V-tile fragments (m = 0, 1), stored as 1 KiB contiguous runs.
-    gemm_mainloop<TM, TN, false>(p.A, p.W, d, m0, n0, lds, acc);
+    gemm_mainloop<TM, TN, kF1Stages, false>(p.A, p.W, d, m0, n0, lds, acc);
     const int user = p.rt.user[m0];
     const UserDesc ud = p.users[user];
     const int pos0 = p.rt.idx[m0];
@@ -206,9 +217,19 @@ __global__ __launch_bounds__(256, 2) void f1_gemm_bf16_kernel(F1Params p) {
 
   // ---- everything else: feature-major product, staged through LDS as [token][feature] so that
   // every global store is a 16-byte chunk of 8 consecutive features of one token.
-  gemm_mainloop<TM, TN, true>(p.A, p.W, d, m0, n0, lds, acc);
+  // In the store phase a thread owns 16-byte chunk (tid & 15) of rows (tid >> 4) + 16*it of each
+  // 128-row half; fetch those rows' kinds now, so that the lookups complete under the main loop.
+  int kinds[2][8];
+#pragma unroll
+  for (int half = 0; half < 2; ++half)
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int row = m0 + half * 128 + (tid >> 4) + 16 * it;
+      kinds[half][it] = row < p.row_end ? p.rt.kind[row] : kRowPad;
+    }
+  gemm_mainloop<TM, TN, kF1Stages, true>(p.A, p.W, d, m0, n0, lds, acc);
   const float mul = (blk == 2) ? p.q_mul : 1.0f;
-#pragma unroll 1
+#pragma unroll
   for (int half = 0; half < 2; ++half) {
     if (wm == half) {
 #pragma unroll
@@ -237,7 +258,7 @@ __global__ __launch_bounds__(256, 2) void f1_gemm_bf16_kernel(F1Params p) {
       const int t = cidx >> 4, fc = cidx & 15;
       const int row = m0 + half * 128 + t;
       if (row >= p.row_end) continue;
-      const int kind = p.rt.kind[row];
+      const int kind = kinds[half][it];
       if (kind == kRowPad && (blk == 0 || blk == 2)) continue;
       uint4 val = *reinterpret_cast<const uint4*>(&lds[t * kStageLd + fc * 8]);
       const int c = c0 + fc * 8;                             // feature inside the block
@@ -282,12 +303,12 @@ struct F2Params {
   int d, row_begin, row_end, n_mtiles;
 };
 
-constexpr int kF2TM = 2, kF2TN = 2;   // 128 tokens x 128 features per workgroup
+constexpr int kF2TM = 2, kF2TN = 2, kF2Stages = 4;   // 128 tokens x 128 features per workgroup
 
 __global__ __launch_bounds__(256, 2) void f2_gemm_bf16_kernel(F2Params p) {
   constexpr int TM = kF2TM, TN = kF2TN;
-  using G = GemmTile<TM, TN>;
-  __shared__ __attribute__((aligned(16))) uint16_t lds[2 * G::STAGE];
+  using G = GemmTile<TM, TN, kF2Stages>;
+  __shared__ __attribute__((aligned(16))) uint16_t lds[G::LDS_ELEMS];
   const int n_ntiles = p.d / G::BNf;
   const int total = p.n_mtiles * n_ntiles;
   const int logical = xcd_remap(blockIdx.x, total);
@@ -297,22 +318,26 @@ __global__ __launch_bounds__(256, 2) void f2_gemm_bf16_kernel(F2Params p) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1, l32 = lane & 31, g = lane >> 5;
   f32x16_t acc[TM][TN];
-  // token-major: a lane holds one feature column and 4-token runs; for a fixed accumulator element
-  // the 32 lanes of a half-wave update 128 contiguous bytes of one row of x
-  gemm_mainloop<TM, TN, false>(p.A, p.W, p.d, m0, n0, lds, acc);
+  // feature-major: a lane holds one token and runs of 4 consecutive features, i.e. one 16-byte
+  // read-modify-write of the fp32 residual row per accumulator quad
+  gemm_mainloop<TM, TN, kF2Stages, true>(p.A, p.W, p.d, m0, n0, lds, acc);
 #pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int c = n0 + wn * 64 + j * 32 + l32;
-    const float bias = bf16_bits_to_float(p.bias[c]);
+  for (int i = 0; i < TM; ++i) {
+    const int row = m0 + wm * 64 + i * 32 + l32;
+    if (row >= p.row_end) continue;
+    float* xrow = p.x + (size_t)row * p.d;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int row = m0 + wm * 64 + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
-        if (row < p.row_end) {
-          float* xp = p.x + (size_t)row * p.d + c;
-          *xp = *xp + acc[i][j][e] + bias;
-        }
+      for (int e4 = 0; e4 < 4; ++e4) {
+        const int c = n0 + wn * 64 + j * 32 + 8 * e4 + 4 * g;
+        const uint2 bb = *reinterpret_cast<const uint2*>(p.bias + c);
+        float4 v = *reinterpret_cast<const float4*>(xrow + c);
+        v.x += acc[i][j][4 * e4] + bf16_bits_to_float(bb.x & 0xFFFF);
+        v.y += acc[i][j][4 * e4 + 1] + bf16_bits_to_float(bb.x >> 16);
+        v.z += acc[i][j][4 * e4 + 2] + bf16_bits_to_float(bb.y & 0xFFFF);
+        v.w += acc[i][j][4 * e4 + 3] + bf16_bits_to_float(bb.y >> 16);
+        *reinterpret_cast<float4*>(xrow + c) = v;
       }
   }
 }
