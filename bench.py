@@ -46,6 +46,55 @@ def percentile(xs, q):
     return xs[k]
 
 
+def small_m_sweep(torch, rg, synth, n_users=128, L=8192, Ms=(16, 32, 64, 128), steps=20):
+    """Attention kernel where HBM binds: few candidates per user, K/V far larger than the 256 MB
+    Infinity Cache (128 users x 8192 tokens x 2 layers = 4 GiB; one launch streams 2 GiB).
+    Reports algorithmic bytes per launch / average launch time against the 8 TB/s peak."""
+    cfg = synth.ModelConfig(2, 512, 8, "bf16")
+    d, e = cfg.d_model, 2
+    weights = synth.make_weights(cfg, 77)
+    ctx = rg.Context(cfg, weights, n_users, 16 * L, n_users * max(Ms))
+    page = 256
+    pool = rg.KvPool(ctx.cfg, cfg.dtype, n_users * rg.relaygr_kv_pool_bytes_for(ctx.cfg, L, page), page)
+    # one generated 16-user prefix batch pre-inferred into 8 groups of pool entries (contents do not matter here)
+    wl = synth.Workload("sweep", cfg, seed=77, n_users=16, prefix_len=L, n_cands=1, n_suffix=0)
+    pb = synth.make_batch(wl, 0)
+    handles = []
+    pre = rg.Batch(pb, cfg.dtype)
+    for grp in range(n_users // 16):
+        hs = [rg.relaygr_kv_pool_alloc(pool, 10_000 + grp * 16 + u, L) for u in range(16)]
+        pre.set_handles(hs)
+        rg.relaygr_prefill_prefix(ctx, pool, pre)
+        handles += hs
+    torch.cuda.synchronize()
+    out = []
+    for M in Ms:
+        wl_m = synth.Workload("sweep", cfg, seed=78, n_users=n_users, prefix_len=1, n_cands=M, n_suffix=0)
+        cb = synth.make_batch(wl_m, 0)
+        cb["prefix_off"] = (np.arange(n_users + 1, dtype=np.int64) * L).astype(np.int32)
+        cb["prefix_emb"] = np.zeros((0, d), np.float32)   # cached users: prefix embeddings are not read
+        b = rg.Batch(cb, cfg.dtype, handles=handles)
+        scores = torch.empty(n_users * M, dtype=torch.float32, device="cuda:0")
+        for _ in range(3):
+            rg.relaygr_rank_with_cache(ctx, pool, b, scores)
+        torch.cuda.synchronize()
+        rg.relaygr_ctx_profile_enable(ctx, ["attn"])
+        for _ in range(steps):
+            rg.relaygr_rank_with_cache(ctx, pool, b, scores)
+        ms, n = rg.relaygr_ctx_profile_read(ctx, "attn")
+        rg.relaygr_ctx_profile_enable(ctx, [])
+        avg = ms / n
+        nbytes = 2.0 * n_users * L * d * e + n_users * M * d * (e + 4)
+        flops = 4.0 * d * n_users * M * L
+        out.append({"M": M, "avg_launch_ms": round(avg, 4), "algorithmic_GBps": round(nbytes / (avg * 1e-3) / 1e9, 1),
+                    "frac_of_8TBps": round(nbytes / (avg * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4),
+                    "TFLOPs": round(flops / (avg * 1e-3) / 1e12, 1), "finite": bool(torch.isfinite(scores).all().item())})
+    ctx.close()
+    pool.close()
+    return {"users": n_users, "prefix_len": L, "layers": cfg.n_layers, "kv_bytes_streamed_per_launch": 2 * n_users * L * d * e,
+            "points": out}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -56,6 +105,9 @@ def main() -> int:
     ap.add_argument("--prefill-steps", type=int, default=5, help="timed prefill calls")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-all", action="store_true", help="time every kernel class, not only attention")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy, the known-size reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the small-M sweep of the attention kernel (its HBM-bound regime)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (users shard by hash across GPUs with no "
@@ -71,6 +123,14 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
+
+    if args.calib_copy:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda:0")   # 1 GiB
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
 
     wl = synth.WORKLOADS[args.config]
     cfg = wl.model
@@ -205,6 +265,15 @@ def main() -> int:
                f"{len(c)} candidates), full recompute in float64, {dt:.1f}s",
                "gpu_vs_oracle_max_abs_err": err, "oracle_max_abs": float(np.abs(ref).max())}
 
+    kv_bytes = {"min": int(rg.relaygr_kv_footprint_bytes(ctx.cfg, int(L.min()))),
+                "max": int(rg.relaygr_kv_footprint_bytes(ctx.cfg, int(L.max())))}
+    sweep = None
+    if not args.no_sweep and cfg.dtype == "bf16":
+        ctx.close(); pool.close()
+        del ctx, pool, db, pre
+        torch.cuda.empty_cache()
+        sweep = small_m_sweep(torch, rg, synth)
+
     out = {
         "metric": "candidates scored/sec, ranking on the cached prefix (rank stage); p99 rank latency and full recompute beside it",
         "value": round(value, 1), "unit": "candidates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -220,16 +289,14 @@ def main() -> int:
         "speedup_cached_vs_full": round(full_mean / ms_per_step, 3) if full_mean else None,
         "prefill": {"ms": round(float(np.mean(prefill_ms)), 4) if prefill_ms else None, "prefix_tokens": int(sum(L[u] for u in hit)),
                     "tokens_per_s": round(sum(int(L[u]) for u in hit) / (np.mean(prefill_ms) * 1e-3), 1) if prefill_ms else None},
-        "kv_bytes_per_user": {"min": int(rg.relaygr_kv_footprint_bytes(ctx.cfg, int(L.min()))),
-                              "max": int(rg.relaygr_kv_footprint_bytes(ctx.cfg, int(L.max())))},
+        "kv_bytes_per_user": kv_bytes,
         "kernel_ms_per_step": {c: round(ms / args.steps, 4) for c, (ms, cnt) in kernel_ms.items()},
         "roofline": roof,
+        "attention_small_m_sweep": sweep,
         "cpu_baseline": cpu,
         "paper_context": "RelayGR on Ascend 910C NPUs: up to 1.5x longer sequences and 3.6x SLO-compliant throughput (system-level, not comparable)",
     }
     print(json.dumps(out), flush=True)
-    ctx.close()
-    pool.close()
     return 0
 
 

@@ -288,6 +288,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p) {
     }
   };
 
+  // a wavefront whose rows all lie beyond the work item's last row only helps move tiles
+  const bool wave_active = wave * 32 * NQ < at.nrows;
   const int nt = tr.t1 - tr.t0;
   if (nt > 0) {
     issue_tile(tr.t0, 0);
@@ -326,7 +328,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p) {
       const uint16_t* kt = &bufs[b][lane * 8];
       const uint16_t* vt = kt + kTile * DH;
       // step 1: SiLU of the first half | first product of the second half, second product owed from before
-      attn_step<DH, NQ, MASKED>(kt + KS * 512, vprev, qf, s_cur, s_nxt, pk_b, pk_a, oacc, vis);
+      if (wave_active) attn_step<DH, NQ, MASKED>(kt + KS * 512, vprev, qf, s_cur, s_nxt, pk_b, pk_a, oacc, vis);
       // the next tile must have landed before its first product; every wavefront is now past tile i-1
       const int bn = (b == 2) ? 0 : b + 1;
       const bool more = i + 1 < nt;
@@ -341,7 +343,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p) {
 #pragma unroll
         for (int qb = 0; qb < NQ; ++qb) vis[qb] -= 32;
       }
-      attn_step<DH, NQ, MASKED>(more ? &bufs[bn][lane * 8] : kt, vt, qf, s_nxt, s_cur, pk_a, pk_b, oacc, vis);
+      if (wave_active) attn_step<DH, NQ, MASKED>(more ? &bufs[bn][lane * 8] : kt, vt, qf, s_nxt, s_cur, pk_a, pk_b, oacc, vis);
       vprev = vt + 2 * 512;
       b = bn;
     };
