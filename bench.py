@@ -29,6 +29,10 @@ PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA
 PEAK_FP32_TFLOPS = 157.3     # fp32 vector
 PEAK_HBM_GBPS = 8000.0
 
+# HBM bytes per attention launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs), scaled by
+# what the same counters read for a plain 1 GiB copy (x2.0 and x1.0); profiles/rank_with_cache_C3_kernels.md.
+MEASURED_ATTN_TRAFFIC_BYTES = {"C3": (69841 * 2 + 16384) * 1024}
+
 WORKLOAD_TEXT = {
     "C1": "C1: fp32, 2 layers, d=64, 2 heads; 1 user, prefix 256, 16 candidates",
     "C2": "C2: bf16, 4 layers, d=256, 4 heads; 8 users x (prefix 2048, suffix 16, 256 candidates)",
@@ -241,7 +245,7 @@ def main() -> int:
             "kernel": "attn_bf16_kernel" if cfg.dtype == "bf16" else "attn_f32_kernel",
             "bound": "mfma" if cfg.dtype == "bf16" else "alu",
             "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-            "traffic": None,
+            "traffic": MEASURED_ATTN_TRAFFIC_BYTES.get(args.config),
             "avg_launch_ms": round(avg_ms, 4), "launches": attn_n,
             "flop_per_launch": avg_flops,
             "algorithmic_bytes_per_launch": kv_bytes,
