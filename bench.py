@@ -184,6 +184,12 @@ def main() -> int:
         torch.cuda.synchronize()
         if i > 0:
             prefill_ms.append(a.elapsed_time(b))
+    prefill_kernels = None
+    if args.profile_all and hit:
+        rg.relaygr_ctx_profile_enable(ctx, rg.binding.KERNEL_CLASSES)
+        rg.relaygr_prefill_prefix(ctx, pool, pre)
+        prefill_kernels = {c: round(rg.relaygr_ctx_profile_read(ctx, c)[0], 4) for c in rg.binding.KERNEL_CLASSES}
+        rg.relaygr_ctx_profile_enable(ctx, [])
     db.set_handles(handles)
     scores = torch.empty(sumM, dtype=torch.float32, device="cuda:0")
 
@@ -293,6 +299,7 @@ def main() -> int:
         "speedup_cached_vs_full": round(full_mean / ms_per_step, 3) if full_mean else None,
         "prefill": {"ms": round(float(np.mean(prefill_ms)), 4) if prefill_ms else None, "prefix_tokens": int(sum(L[u] for u in hit)),
                     "tokens_per_s": round(sum(int(L[u]) for u in hit) / (np.mean(prefill_ms) * 1e-3), 1) if prefill_ms else None},
+        "prefill_kernel_ms": prefill_kernels,
         "kv_bytes_per_user": kv_bytes,
         "kernel_ms_per_step": {c: round(ms / args.steps, 4) for c, (ms, cnt) in kernel_ms.items()},
         "roofline": roof,

@@ -168,8 +168,8 @@ __device__ __forceinline__ void attn_pv_half(const uint16_t* __restrict__ vhalf,
 // (khalf -> s_out) and the second product owed from the preceding half (vhalf, pk_in -> oacc).
 // A wavefront issues in order and an MFMA cannot issue while the matrix pipe still works on the
 // previous one, so MFMAs placed back to back would leave the vector ALU idle behind them.  The
-// step is therefore cut into slots -- NQ MFMAs, then the SiLU of 128/DH score elements per row
-// block, about as long as those MFMAs take -- and the scheduler is fenced between slots.
+// step is therefore cut into slots -- the SiLU of 128/DH score elements per row block, then NQ
+// MFMAs that take about as long -- and the scheduler is fenced between slots.
 template <int DH, int NQ, bool MASKED>
 __device__ __forceinline__ void attn_step(const uint16_t* __restrict__ khalf, const uint16_t* __restrict__ vhalf,
                                           const bf16x8_t (&qf)[NQ][DH / 16], const f32x16_t (&s_in)[NQ], f32x16_t (&s_out)[NQ],
@@ -186,28 +186,12 @@ __device__ __forceinline__ void attn_step(const uint16_t* __restrict__ khalf, co
   for (int m = 0; m < 2; ++m)
 #pragma unroll
     for (int db = 0; db < DB; ++db) vf[m][db] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(vhalf + (db * 4 + m) * 512));
-#pragma unroll
-  for (int qb = 0; qb < NQ; ++qb)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) s_out[qb][e] = 0.f;
   float pv[NQ][16];
+  const f32x16_t zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int slot = 0; slot < SLOTS; ++slot) {
-    // matrix pipe: alternate the two products so that dependent MFMAs are two slots apart
-    const bool first = (slot % 2 == 0);     // KS == 2*DB: even slots feed the first product, odd the second
-    const int si = slot / 2;
-    if (first) {
-#pragma unroll
-      for (int qb = 0; qb < NQ; ++qb) s_out[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[si], qf[qb][si], s_out[qb], 0, 0, 0);
-    } else {
-      const int m = si / DB, db = si % DB;
-#pragma unroll
-      for (int qb = 0; qb < NQ; ++qb) {
-        uint4 pp = make_uint4(pk_in[qb][4 * m], pk_in[qb][4 * m + 1], pk_in[qb][4 * m + 2], pk_in[qb][4 * m + 3]);
-        oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[m][db], __builtin_bit_cast(bf16x8_t, pp), oacc[db][qb], 0, 0, 0);
-      }
-    }
-    // vector ALU: SiLU' of this slot's score elements; element e is key 8*(e/4) + 4*g + e%4 of the half
+    // vector ALU first (the fragment reads above are still in flight during slot 0): SiLU' of this
+    // slot's score elements; element e is key 8*(e/4) + 4*g + e%4 of the half
 #pragma unroll
     for (int qb = 0; qb < NQ; ++qb) {
 #pragma unroll
@@ -220,6 +204,21 @@ __device__ __forceinline__ void attn_step(const uint16_t* __restrict__ khalf, co
           f32x2_t two = {pv[qb][e - 1], pv[qb][e]};
           pk_out[qb][e >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2_t));   // one v_cvt_pk_bf16_f32
         }
+      }
+    }
+    // matrix pipe: even slots feed the first product, odd slots the second (KS == 2*DB), so that
+    // dependent MFMAs are two slots apart
+    const int si = slot / 2;
+    if (slot % 2 == 0) {
+#pragma unroll
+      for (int qb = 0; qb < NQ; ++qb)
+        s_out[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[si], qf[qb][si], si == 0 ? zero : s_out[qb], 0, 0, 0);
+    } else {
+      const int m = si / DB, db = si % DB;
+#pragma unroll
+      for (int qb = 0; qb < NQ; ++qb) {
+        uint4 pp = make_uint4(pk_in[qb][4 * m], pk_in[qb][4 * m + 1], pk_in[qb][4 * m + 2], pk_in[qb][4 * m + 3]);
+        oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[m][db], __builtin_bit_cast(bf16x8_t, pp), oacc[db][qb], 0, 0, 0);
       }
     }
     __builtin_amdgcn_sched_barrier(0);
