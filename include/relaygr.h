@@ -43,8 +43,12 @@
  *     in fp32; RELAYGR_DTYPE_BF16 stores weights, embeddings, activations and
  *     cached K/V as bfloat16 and accumulates, normalises and keeps the residual
  *     stream in fp32.  Scores are always fp32.
- *   - Constraints checked at context creation: d_model a multiple of 64 and at
- *     most 1024; d_head = d_model / n_heads in {32, 64, 128}.
+ *   - Constraints checked at context creation: d_model in {64, 128, 256, 512, 1024}
+ *     (bf16: at least 128); d_head = d_model / n_heads in {32, 64, 128} and at least
+ *     d_model / 64.
+ *   - In the bf16 mode the first bytes of the scratch buffer hold the weights re-packed
+ *     for the matrix cores (done once in relaygr_ctx_create, which synchronises the
+ *     device); relaygr_scratch_bytes includes them.
  */
 #ifndef RELAYGR_H
 #define RELAYGR_H
@@ -130,7 +134,8 @@ size_t relaygr_scratch_bytes(const relaygr_model_config* cfg, int32_t max_users,
 /* ---- context ------------------------------------------------------------------------ */
 
 /* Binds a model (config + device weights) to a caller-owned device scratch buffer of
- * scratch_bytes (256-byte aligned).  Weight memory is referenced, not copied. */
+ * scratch_bytes (256-byte aligned).  Weight memory is referenced (biases, LayerNorm and
+ * score-head parameters are read from it on every call), so it must outlive the context. */
 int  relaygr_ctx_create(const relaygr_model_config* cfg, const relaygr_weights* weights,
                         void* scratch_dev, size_t scratch_bytes, relaygr_ctx** out);
 void relaygr_ctx_destroy(relaygr_ctx* ctx);
