@@ -149,7 +149,7 @@ constexpr int kStageLd = 64 * kF1TN + 8;          // epilogue staging row stride
 __global__ __launch_bounds__(256, 2) void f1_gemm_bf16_kernel(F1Params p) {
   constexpr int TM = kF1TM, TN = kF1TN;
   using G = GemmTile<TM, TN, kF1Stages>;
-  constexpr int LDS_ELEMS = (G::LDS_ELEMS > 128 * kStageLd) ? G::LDS_ELEMS : 128 * kStageLd;
+  constexpr int LDS_ELEMS = (G::LDS_ELEMS > 256 * kStageLd) ? G::LDS_ELEMS : 256 * kStageLd;
   __shared__ __attribute__((aligned(16))) uint16_t lds[LDS_ELEMS];
 
   const int ntiles_per_blk = p.cm.d / G::BNf;
@@ -217,79 +217,76 @@ __global__ __launch_bounds__(256, 2) void f1_gemm_bf16_kernel(F1Params p) {
 
   // ---- everything else: feature-major product, staged through LDS as [token][feature] so that
   // every global store is a 16-byte chunk of 8 consecutive features of one token.
-  // In the store phase a thread owns 16-byte chunk (tid & 15) of rows (tid >> 4) + 16*it of each
-  // 128-row half; fetch those rows' kinds now, so that the lookups complete under the main loop.
-  int kinds[2][8];
+  // In the store phase a thread owns 16-byte chunk (tid & 15) of rows (tid >> 4) + 16*it of the
+  // tile; fetch those rows' kinds now, so that the lookups complete under the main loop.
+  int kinds[16];
 #pragma unroll
-  for (int half = 0; half < 2; ++half)
-#pragma unroll
-    for (int it = 0; it < 8; ++it) {
-      const int row = m0 + half * 128 + (tid >> 4) + 16 * it;
-      kinds[half][it] = row < p.row_end ? p.rt.kind[row] : kRowPad;
-    }
+  for (int it = 0; it < 16; ++it) {
+    const int row = m0 + (tid >> 4) + 16 * it;
+    kinds[it] = row < p.row_end ? p.rt.kind[row] : kRowPad;
+  }
+  // a prefix tile belongs to one user and holds consecutive prefix positions from pos0 on
+  const int tile_user = prefix_tile ? p.rt.user[m0] : 0;
+  const int pos0 = prefix_tile ? p.rt.idx[m0] : 0;
   gemm_mainloop<TM, TN, kF1Stages, true>(p.A, p.W, d, m0, n0, lds, acc);
   const float mul = (blk == 2) ? p.q_mul : 1.0f;
 #pragma unroll
-  for (int half = 0; half < 2; ++half) {
-    if (wm == half) {
+  for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
+    for (int e4 = 0; e4 < 4; ++e4) {
+      const int f = wn * 64 + j * 32 + 8 * e4 + 4 * g;  // 4 consecutive features held by this lane
+      const uint2 bb = *reinterpret_cast<const uint2*>(p.bias + n0 + f);
+      const float b0 = bf16_bits_to_float(bb.x & 0xFFFF), b1 = bf16_bits_to_float(bb.x >> 16);
+      const float b2 = bf16_bits_to_float(bb.y & 0xFFFF), b3 = bf16_bits_to_float(bb.y >> 16);
 #pragma unroll
-        for (int e4 = 0; e4 < 4; ++e4) {
-          const int f = wn * 64 + j * 32 + 8 * e4 + 4 * g;  // 4 consecutive features held by this lane
-          const uint2 bb = *reinterpret_cast<const uint2*>(p.bias + n0 + f);
-          const float b0 = bf16_bits_to_float(bb.x & 0xFFFF), b1 = bf16_bits_to_float(bb.x >> 16);
-          const float b2 = bf16_bits_to_float(bb.y & 0xFFFF), b3 = bf16_bits_to_float(bb.y >> 16);
-#pragma unroll
-          for (int i = 0; i < TM; ++i) {
-            const int t = i * 32 + l32;
-            uint2 w;
-            w.x = pack_bf16x2(silu_fast(acc[i][j][4 * e4] + b0) * mul, silu_fast(acc[i][j][4 * e4 + 1] + b1) * mul);
-            w.y = pack_bf16x2(silu_fast(acc[i][j][4 * e4 + 2] + b2) * mul, silu_fast(acc[i][j][4 * e4 + 3] + b3) * mul);
-            *reinterpret_cast<uint2*>(&lds[t * kStageLd + f]) = w;
-          }
-        }
-    }
-    __syncthreads();
-    // 128 tokens x 16 chunks of 8 features
-#pragma unroll
-    for (int it = 0; it < 8; ++it) {
-      const int cidx = tid + it * 256;
-      const int t = cidx >> 4, fc = cidx & 15;
-      const int row = m0 + half * 128 + t;
-      if (row >= p.row_end) continue;
-      const int kind = kinds[half][it];
-      if (kind == kRowPad && (blk == 0 || blk == 2)) continue;
-      uint4 val = *reinterpret_cast<const uint4*>(&lds[t * kStageLd + fc * 8]);
-      const int c = c0 + fc * 8;                             // feature inside the block
-      if (blk == 0) { *reinterpret_cast<uint4*>(p.u + (size_t)row * d + c) = val; continue; }
-      if (blk == 2) { *reinterpret_cast<uint4*>(p.q + (size_t)row * d + c) = val; continue; }
-      if (kind == kRowCand) {
-        *reinterpret_cast<uint4*>((blk == 3 ? p.knew : p.vnew) + (size_t)(row - p.n_prows) * d + c) = val;
-        continue;
+      for (int i = 0; i < TM; ++i) {
+        const int t = wm * 128 + i * 32 + l32;
+        uint2 w;
+        w.x = pack_bf16x2(silu_fast(acc[i][j][4 * e4] + b0) * mul, silu_fast(acc[i][j][4 * e4 + 1] + b1) * mul);
+        w.y = pack_bf16x2(silu_fast(acc[i][j][4 * e4 + 2] + b2) * mul, silu_fast(acc[i][j][4 * e4 + 3] + b3) * mul);
+        *reinterpret_cast<uint2*>(&lds[t * kStageLd + f]) = w;
       }
+    }
+  __syncthreads();
+  const UserDesc tud = p.users[tile_user];
+  // 256 tokens x 16 chunks of 8 features
+#pragma unroll
+  for (int it = 0; it < 16; ++it) {
+    const int t = (tid >> 4) + 16 * it, fc = tid & 15;
+    const int row = m0 + t;
+    if (row >= p.row_end) continue;
+    const int kind = kinds[it];
+    if (kind == kRowPad && (blk == 0 || blk == 2)) continue;
+    uint4 val = *reinterpret_cast<const uint4*>(&lds[t * kStageLd + fc * 8]);
+    const int c = c0 + fc * 8;                             // feature inside the block
+    if (blk == 0) { *reinterpret_cast<uint4*>(p.u + (size_t)row * d + c) = val; continue; }
+    if (blk == 2) { *reinterpret_cast<uint4*>(p.q + (size_t)row * d + c) = val; continue; }
+    if (kind == kRowCand) {
+      *reinterpret_cast<uint4*>((blk == 3 ? p.knew : p.vnew) + (size_t)(row - p.n_prows) * d + c) = val;
+      continue;
+    }
+    const int head = c / dh, f = c - head * dh;
+    uint16_t* base;
+    int idx;
+    if (kind == kRowSuffix) {
       const UserDesc& ud = p.users[p.rt.user[row]];
-      const int idx = p.rt.idx[row];
-      const int head = c / dh, f = c - head * dh;
-      uint16_t* base;
-      if (kind == kRowSuffix) {
-        base = p.sfx + ud.sfx_tile0 + (int64_t)(idx >> 6) * (2 * kTile * d) + (int64_t)head * 2 * kTile * dh;
-      } else {
-        if (idx >= (ud.L + kTile - 1) / kTile * kTile) continue;   // padding beyond the user's last tile
-        if (kind == kRowPad) val = make_uint4(0, 0, 0, 0);         // ragged tail of the last tile: zeros
-        base = reinterpret_cast<uint16_t*>(const_cast<void*>(ud.kv)) + ud.kv_tile0 + (int64_t)(idx >> 6) * ud.kv_tile_stride +
-               (int64_t)p.layer * ud.kv_layer_stride + (int64_t)head * 2 * kTile * dh;
-      }
-      const int rr = idx & 63;
-      if (blk == 3) {
-        *reinterpret_cast<uint4*>(base + KvLayout<__hip_bfloat16>::k_off(rr, f, dh)) = val;
-      } else {   // V of a suffix row: its 8 features go to 8 different fragments
-        const uint16_t* e = reinterpret_cast<const uint16_t*>(&val);
-#pragma unroll
-        for (int x = 0; x < 8; ++x) base[KvLayout<__hip_bfloat16>::v_off(rr, f + x, dh)] = e[x];
-      }
+      idx = p.rt.idx[row];
+      base = p.sfx + ud.sfx_tile0 + (int64_t)(idx >> 6) * (2 * kTile * d) + (int64_t)head * 2 * kTile * dh;
+    } else {   // prefix row or filler of a prefix tile (blk == 3 here: V of prefix tiles took the other path)
+      idx = pos0 + t;
+      if (idx >= (tud.L + kTile - 1) / kTile * kTile) continue;   // filler beyond the user's last tile
+      if (kind == kRowPad) val = make_uint4(0, 0, 0, 0);          // ragged tail of the last tile: zeros
+      base = reinterpret_cast<uint16_t*>(const_cast<void*>(tud.kv)) + tud.kv_tile0 + (int64_t)(idx >> 6) * tud.kv_tile_stride +
+             (int64_t)p.layer * tud.kv_layer_stride + (int64_t)head * 2 * kTile * dh;
     }
-    __syncthreads();
+    const int rr = idx & 63;
+    if (blk == 3) {
+      *reinterpret_cast<uint4*>(base + KvLayout<__hip_bfloat16>::k_off(rr, f, dh)) = val;
+    } else {   // V of a suffix row: its 8 features go to 8 different fragments
+      const uint16_t* e = reinterpret_cast<const uint16_t*>(&val);
+#pragma unroll
+      for (int x = 0; x < 8; ++x) base[KvLayout<__hip_bfloat16>::v_off(rr, f + x, dh)] = e[x];
+    }
   }
 }
 
