@@ -217,7 +217,7 @@ def main() -> int:
 
     # ---- the baseline in the same run: full inference inline
     full_ms = []
-    for i in range(1 + args.full_steps):
+    for i in range(1 + args.full_steps if args.full_steps > 0 else 0):
         a, b = ev(), ev()
         a.record()
         rg.relaygr_rank_full_recompute(ctx, db, scores)
@@ -227,7 +227,7 @@ def main() -> int:
             full_ms.append(a.elapsed_time(b))
     full_scores = scores.cpu().numpy()
     full_mean = float(np.mean(full_ms)) if full_ms else None
-    max_diff = float(np.abs(full_scores - cached_scores).max()) if sumM else 0.0
+    max_diff = float(np.abs(full_scores - cached_scores).max()) if (sumM and full_ms) else None
 
     # ---- roofline of the dominant kernel (attention over the cached prefix + suffix)
     d = cfg.d_model
