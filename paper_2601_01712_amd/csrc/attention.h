@@ -111,7 +111,7 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(AttnParams p) {
 }
 
 // ---- bf16 MFMA kernel ---------------------------------------------------------------------------
-// A workgroup of 4 wavefronts owns up to 128*NQ rows (each wavefront NQ blocks of 32 rows) of one
+// A workgroup of NW wavefronts owns up to NW*32*NQ rows (each wavefront NQ blocks of 32 rows) of one
 // user and one head and walks the key tiles of its split.  Per 32-key half tile and wavefront:
 //   S^T[32 keys][32 rows]  = K half (A operand, rows = keys)  x  Q^T (B operand, held in registers)
 //   P^T = SiLU'(S^T) rounded to bf16 -- the accumulator layout of S^T (lane = row, 4-key runs) is
@@ -225,12 +225,13 @@ __device__ __forceinline__ void attn_step(const uint16_t* __restrict__ khalf, co
   }
 }
 
-template <int DH, int NQ>
-__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p) {
+template <int DH, int NQ, int NW>
+__global__ __launch_bounds__(NW * 64, 512 / (NW * 64)) void attn_bf16_kernel(AttnParams p) {
   constexpr int KS = DH / 16;              // k-steps of the first product
   constexpr int DB = DH / 32;              // 32-feature blocks of the output
   constexpr int TILE = 2 * kTile * DH;     // elements of one K tile + one V tile
-  constexpr int CHUNKS = TILE / 8 / 256;   // 16-byte chunks each thread moves per tile
+  constexpr int CHUNKS = TILE / 8 / (NW * 64);   // 16-byte chunks each thread moves per tile
+  static_assert(CHUNKS >= 1, "a tile is at least one 16-byte chunk per thread");
   __shared__ __attribute__((aligned(16))) uint16_t bufs[3][TILE];
 
   // Work items that stream the same K/V (row tiles of one user, same head and split) get
@@ -276,12 +277,12 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnParams p) {
   const uint16_t* sfx_base = reinterpret_cast<const uint16_t*>(p.sfx) + ud.sfx_tile0 + (int64_t)head * TILE;
   const int64_t sfx_stride = (int64_t)2 * kTile * p.d;
 
-  // HBM -> LDS, no registers in between: wavefront w moves the 1 KiB pieces w, w+4, ... of the tile
+  // HBM -> LDS, no registers in between: wavefront w moves the 1 KiB pieces w, w+NW, ... of the tile
   auto issue_tile = [&](int tt, int b) {
     const uint16_t* src = (tt < tr.nkp) ? kv_base + (int64_t)tt * ud.kv_tile_stride : sfx_base + (int64_t)(tt - tr.nkp) * sfx_stride;
 #pragma unroll
     for (int i = 0; i < CHUNKS; ++i) {
-      const int piece = i * 4 + wave;
+      const int piece = i * NW + wave;
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + piece * 512 + lane * 8),
                                        (__attribute__((address_space(3))) void*)(&bufs[b][piece * 512]), 16, 0, 0);
     }

@@ -453,12 +453,12 @@ int launch_attention<__hip_bfloat16>(const relaygr_model_config& cfg, const Attn
   int total = n_tiles * cfg.n_heads * ap.nsplit;
   dim3 grid((total + 7) / 8 * 8);
   switch (cfg.d_model / cfg.n_heads) {
-    case 32: hipLaunchKernelGGL((attn_bf16_kernel<32, 1>), grid, dim3(256), 0, st, ap); break;
+    case 32: hipLaunchKernelGGL((attn_bf16_kernel<32, 1, 4>), grid, dim3(256), 0, st, ap); break;
     case 64:
-      if (nq == 2) hipLaunchKernelGGL((attn_bf16_kernel<64, 2>), grid, dim3(256), 0, st, ap);
-      else hipLaunchKernelGGL((attn_bf16_kernel<64, 1>), grid, dim3(256), 0, st, ap);
+      if (nq == 2) hipLaunchKernelGGL((attn_bf16_kernel<64, 2, 4>), grid, dim3(256), 0, st, ap);
+      else hipLaunchKernelGGL((attn_bf16_kernel<64, 1, 4>), grid, dim3(256), 0, st, ap);
       break;
-    case 128: hipLaunchKernelGGL((attn_bf16_kernel<128, 1>), grid, dim3(256), 0, st, ap); break;
+    case 128: hipLaunchKernelGGL((attn_bf16_kernel<128, 1, 4>), grid, dim3(256), 0, st, ap); break;
     default: return fail(RELAYGR_EINVAL, "attention: unsupported d_head");
   }
   LAUNCH_CHECK("attn_bf16");
