@@ -94,32 +94,40 @@ __device__ __forceinline__ void gemm_mainloop(const uint16_t* __restrict__ A, co
   for (int kt = 0; kt < n_kt; ++kt) {
     // stage kt must have landed; the NSTAGE-2 younger stages may stay in flight (near the end fewer
     // are outstanding, so wait for all of them there)
+    // (a bare s_barrier: __syncthreads() would also make the compiler wait for every outstanding load,
+    // i.e. for the stages that are meant to stay in flight)
     if (kt + NSTAGE - 2 < n_kt) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSTAGE - 2) * G::LOADS_PER_WAVE) : "memory");
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();     // also: every wavefront is past stage kt-1, whose slot is refilled next
+    __builtin_amdgcn_s_barrier();   // also: every wavefront is past stage kt-1, whose slot is refilled next
+    asm volatile("" ::: "memory");
     if (kt + NSTAGE - 1 < n_kt) issue(kt + NSTAGE - 1, slot == 0 ? NSTAGE - 1 : slot - 1);
     const uint16_t* tokp = lds + slot * G::STAGE + lane * 8;
     const uint16_t* featp = tokp + G::TOK_PIECES * 512;
+    // fetch the fragments of both k-steps first, so that the second set's LDS latency hides under
+    // the first set's MFMAs
+    bf16x8_t tf[2][TM], ff[2][TN];
 #pragma unroll
     for (int ksl = 0; ksl < 2; ++ksl) {
-      bf16x8_t tf[TM], ff[TN];
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         int rbAll = wm * TM + i;   // 32-row block inside the workgroup tile
-        tf[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(tokp + (((rbAll >> 2) * 2 + ksl) * 4 + (rbAll & 3)) * 512));
+        tf[ksl][i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(tokp + (((rbAll >> 2) * 2 + ksl) * 4 + (rbAll & 3)) * 512));
       }
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         int nbAll = wn * TN + j;
-        ff[j] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(featp + (((nbAll >> 2) * 2 + ksl) * 4 + (nbAll & 3)) * 512));
+        ff[ksl][j] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(featp + (((nbAll >> 2) * 2 + ksl) * 4 + (nbAll & 3)) * 512));
       }
+    }
+    __builtin_amdgcn_sched_barrier(0);   // keep all twelve reads ahead of the MFMAs
+#pragma unroll
+    for (int ksl = 0; ksl < 2; ++ksl)
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = FEATURE_MAJOR ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(ff[j], tf[i], acc[i][j], 0, 0, 0)
-                                    : __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf[i], ff[j], acc[i][j], 0, 0, 0);
-    }
+          acc[i][j] = FEATURE_MAJOR ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(ff[ksl][j], tf[ksl][i], acc[i][j], 0, 0, 0)
+                                    : __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf[ksl][i], ff[ksl][j], acc[i][j], 0, 0, 0);
     slot = (slot == NSTAGE - 1) ? 0 : slot + 1;
   }
   __syncthreads();   // every wavefront is done reading LDS: the epilogue may reuse it
