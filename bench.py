@@ -112,6 +112,7 @@ def main() -> int:
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE")
     ap.add_argument("--no-concurrent", action="store_true", help="skip the rank-beside-prefill measurement on two streams")
+    ap.add_argument("--no-dram", action="store_true", help="skip the spill / reload (DRAM tier) measurement")
     ap.add_argument("--no-sweep", action="store_true", help="skip the small-M sweep of the attention kernel (its HBM-bound regime)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -226,6 +227,12 @@ def main() -> int:
         torch.cuda.synchronize()
         if i > 0:
             full_ms.append(a.elapsed_time(b))
+    full_kernels = None
+    if args.profile_all and full_ms:
+        rg.relaygr_ctx_profile_enable(ctx, rg.binding.KERNEL_CLASSES)
+        rg.relaygr_rank_full_recompute(ctx, db, scores)
+        full_kernels = {c: round(rg.relaygr_ctx_profile_read(ctx, c)[0], 4) for c in rg.binding.KERNEL_CLASSES}
+        rg.relaygr_ctx_profile_enable(ctx, [])
     full_scores = scores.cpu().numpy()
     full_mean = float(np.mean(full_ms)) if full_ms else None
     max_diff = float(np.abs(full_scores - cached_scores).max()) if (sumM and full_ms) else None
@@ -272,6 +279,38 @@ def main() -> int:
         pool2.close()
         del ctx2, pool2, pre2
         torch.cuda.empty_cache()
+
+    # ---- the DRAM tier's `load` step (Section 3.4; the load column of the latency breakdown, Section 5.5): one user's psi
+    # spilled to pinned host memory, its extent freed, the image reloaded, and the same ranking repeated on it
+    dram = None
+    if not args.no_dram and hit:
+        u = hit[0]
+        hu = int(handles[u])
+        nbytes = rg.relaygr_kv_pool_entry_bytes(pool, hu)
+        image = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+        spill_ms, load_ms = [], []
+        for i in range(6):
+            a, b, c2, d2 = ev(), ev(), ev(), ev()
+            a.record()
+            rg.relaygr_kv_pool_spill(pool, hu, image)
+            b.record()
+            torch.cuda.synchronize()
+            rg.relaygr_kv_pool_free(pool, hu)
+            c2.record()
+            hu = rg.relaygr_kv_pool_reload(pool, int(batch["user_ids"][u]), int(L[u]), image)
+            d2.record()
+            torch.cuda.synchronize()
+            if i > 0:
+                spill_ms.append(a.elapsed_time(b))
+                load_ms.append(c2.elapsed_time(d2))
+        handles[u] = hu
+        db.set_handles(handles)
+        rg.relaygr_rank_with_cache(ctx, pool, db, scores)
+        torch.cuda.synchronize()
+        dram = {"user_prefix_tokens": int(L[u]), "image_bytes": int(nbytes),
+                "spill_ms": round(float(np.mean(spill_ms)), 4), "load_ms": round(float(np.mean(load_ms)), 4),
+                "load_GBps": round(nbytes / (float(np.mean(load_ms)) * 1e-3) / 1e9, 1),
+                "scores_identical_after_reload": bool(np.array_equal(scores.cpu().numpy(), cached_scores))}
 
     # ---- roofline of the dominant kernel (attention over the cached prefix + suffix)
     d = cfg.d_model
@@ -339,7 +378,7 @@ def main() -> int:
                             "mean": round(float(np.mean(lat)), 4)},
         "full_recompute": {"ms": round(full_mean, 4) if full_mean else None,
                            "candidates_per_s": round(sumM / (full_mean * 1e-3), 1) if full_mean else None,
-                           "calls": len(full_ms), "max_abs_diff_vs_cached": max_diff},
+                           "calls": len(full_ms), "max_abs_diff_vs_cached": max_diff, "kernel_ms": full_kernels},
         "speedup_cached_vs_full": round(full_mean / ms_per_step, 3) if full_mean else None,
         "prefill": {"ms": round(float(np.mean(prefill_ms)), 4) if prefill_ms else None, "prefix_tokens": int(sum(L[u] for u in hit)),
                     "tokens_per_s": round(sum(int(L[u]) for u in hit) / (np.mean(prefill_ms) * 1e-3), 1) if prefill_ms else None},
@@ -349,6 +388,7 @@ def main() -> int:
         "roofline": roof,
         "rank_beside_prefill": concurrent,
         "attention_small_m_sweep": sweep,
+        "dram_tier": dram,
         "cpu_baseline": cpu,
         "paper_context": "RelayGR on Ascend 910C NPUs: up to 1.5x longer sequences and 3.6x SLO-compliant throughput (system-level, not comparable)",
     }

@@ -216,6 +216,91 @@ int  relaygr_ctx_profile_enable(relaygr_ctx* ctx, uint32_t class_mask);
  * of launches of one class since the last enable.  Synchronises with the GPU. */
 int  relaygr_ctx_profile_read(relaygr_ctx* ctx, int32_t kernel_class, double* total_ms, int64_t* launches);
 
+/* ---- DRAM tier (Section 3.4, memory-aware expander) ------------------------------------ */
+
+/* Bytes of the pool extent holding the entry (page-rounded): the size of its spill image.  0 if stale. */
+size_t relaygr_kv_pool_entry_bytes(relaygr_kv_pool* pool, relaygr_kv_handle handle);
+/* Enqueues on hip_stream a copy of the entry's extent into host_dst (HOST memory, pinned for an
+ * asynchronous copy; host_bytes must equal relaygr_kv_pool_entry_bytes).  The entry stays live.  The
+ * image is position independent: it can be reloaded into any pool of the same model shape and page size. */
+int  relaygr_kv_pool_spill(relaygr_kv_pool* pool, relaygr_kv_handle handle, void* host_dst, size_t host_bytes,
+                           void* hip_stream);
+/* Allocates an entry for user_id / prefix_len and enqueues on hip_stream the copy of a spill image
+ * into it (the `load` step of the paper's latency breakdown).  RELAYGR_ENOSPC as for alloc. */
+int  relaygr_kv_pool_reload(relaygr_kv_pool* pool, uint64_t user_id, int32_t prefix_len, const void* host_src,
+                            size_t host_bytes, void* hip_stream, relaygr_kv_handle* out);
+
+/* The expander keeps consumed psi objects in server-local DRAM for short-term reuse across requests
+ * of the same user, behind a two-level lookup HBM -> DRAM.  Its DRAM is ONE pinned host arena of
+ * dram_budget_bytes (rounded down to whole pool pages; 0 = no DRAM tier) allocated at creation and
+ * freed at destruction; images are placed in it like entries in the pool, least recently used
+ * dropped first when an image does not fit.  At most max_inflight_reloads reloads are in flight and
+ * a user has at most one copy per tier.  Calls are thread-safe; copies run on a stream the expander
+ * owns (default priority), ordered against the caller's streams with events, never host waits. */
+typedef struct relaygr_expander relaygr_expander;
+int  relaygr_expander_create(relaygr_kv_pool* pool, size_t dram_budget_bytes, int32_t max_inflight_reloads,
+                             relaygr_expander** out);
+/* Waits for the expander's outstanding copies, frees its DRAM.  Pool entries stay as they are. */
+void relaygr_expander_destroy(relaygr_expander* ex);
+/* After ranking has consumed an entry: once hip_stream has passed this point the entry is copied to
+ * DRAM on the expander's own copy stream, and its HBM extent is released when that copy has completed
+ * (observed at a later expander call).  The caller must not use the handle in work enqueued after
+ * this call unless a later relaygr_expander_lookup returns it again.  RELAYGR_ENOSPC if the image
+ * cannot be placed in DRAM (the entry is then only freed, once hip_stream has passed this point). */
+int  relaygr_expander_retire(relaygr_expander* ex, relaygr_kv_handle handle, void* hip_stream);
+/* The idempotent probe issued before every rank (pseudo-pre-infer): *source = 0 and the live handle if
+ * psi is in HBM (a pending retire of it is cancelled); *source = 1 if it was found in DRAM, in which
+ * case an entry is allocated, the reload is enqueued on the copy stream and hip_stream is made to wait
+ * for it (no host wait); RELAYGR_ENOENT if neither tier has it (the caller ranks by full recompute
+ * or pre-infers); RELAYGR_EBUSY if the reload limit is reached (the caller falls back, nothing queued). */
+int  relaygr_expander_lookup(relaygr_expander* ex, uint64_t user_id, void* hip_stream, relaygr_kv_handle* out,
+                             int32_t* source);
+/* Counters since creation: [0] HBM hits, [1] DRAM hits (reloads), [2] misses, [3] refusals (busy),
+ * [4] spills, [5] DRAM evictions, [6] DRAM bytes in use, [7] DRAM entries. */
+int  relaygr_expander_stats(relaygr_expander* ex, int64_t stats[8]);
+
+/* ---- sequence-aware trigger, host side (Section 3.2, Eq. 1-3) --------------------------- */
+
+typedef struct {
+  double  q_m;            /* sustainable pre-infer throughput of one model slot, queries/s          */
+  int32_t model_slots;    /* M: concurrent model slots of a special instance                        */
+  double  kv_p99_bytes;   /* P99 footprint of psi per admitted user                                 */
+  double  hbm_bytes;      /* HBM of the instance                                                    */
+  double  r1;             /* fraction of HBM reserved for live caches, in (0, 1]                    */
+  int32_t n_instances;    /* N: ranking instances in total                                          */
+  double  r2;             /* fraction of them designated special, in (0, 1]                         */
+  double  t_life_s;       /* lifecycle window: pre-infer issued -> ranking consumes psi, seconds    */
+} relaygr_admission_params;
+
+typedef struct {
+  double max_live_caches;   /* Eq. 2: floor(r1 * HBM / kv_p99)                                     */
+  double q_admit_hbm;       /* Eq. 1 with that bound: max_live_caches / T_life                     */
+  double q_admit_compute;   /* Eq. 3, first inequality: Q_m * M                                    */
+  double q_admit;           /* min of the two: admitted pre-infer rate per special instance        */
+  double q_max;             /* Eq. 3, second inequality: (Q_m * M) * (r2 * N), pool-wide           */
+} relaygr_admission_budget;
+
+int    relaygr_admission_budget_compute(const relaygr_admission_params* params, relaygr_admission_budget* out);
+/* floor(1000 / pre_infer_ms): queries/s one model slot sustains (the paper's Q_m estimate). */
+double relaygr_slot_throughput(double pre_infer_ms);
+
+#define RELAYGR_TRIGGER_ADMIT        1   /* send the pre-infer signal                               */
+#define RELAYGR_TRIGGER_NOT_AT_RISK  0   /* short prefix: zero extra work                            */
+#define RELAYGR_TRIGGER_REFUSED      2   /* at risk, but over the live-cache or rate budget          */
+#define RELAYGR_EBUSY              (-5)  /* a rate / concurrency limit is reached; retry or fall back */
+
+/* Admission gate of one special instance: a request is admitted iff its prefix has at least
+ * len_threshold tokens (the metadata risk test), the live-cache count stays within max_live_caches
+ * and a token bucket refilled at q_admit per second (one second deep) has a token. */
+typedef struct relaygr_trigger relaygr_trigger;
+int  relaygr_trigger_create(const relaygr_admission_budget* budget, int32_t len_threshold, relaygr_trigger** out);
+void relaygr_trigger_destroy(relaygr_trigger* t);
+/* Returns RELAYGR_TRIGGER_* (or a negative code on bad arguments).  now_s: caller's monotonic clock. */
+int  relaygr_trigger_admit(relaygr_trigger* t, double now_s, int32_t prefix_len);
+/* The admitted request's psi was consumed (or dropped): one live cache fewer. */
+int  relaygr_trigger_release(relaygr_trigger* t);
+int  relaygr_trigger_stats(relaygr_trigger* t, int64_t* live, int64_t* admitted, int64_t* refused, int64_t* not_at_risk);
+
 /* Text of the calling thread's last failure ("" if none).  Valid until the thread's next call. */
 const char* relaygr_last_error(void);
 

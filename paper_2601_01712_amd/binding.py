@@ -16,7 +16,8 @@ import torch
 
 from . import build as _build
 
-RELAYGR_OK, RELAYGR_EINVAL, RELAYGR_ENOSPC, RELAYGR_ENOENT, RELAYGR_EHIP = 0, -1, -2, -3, -4
+RELAYGR_OK, RELAYGR_EINVAL, RELAYGR_ENOSPC, RELAYGR_ENOENT, RELAYGR_EHIP, RELAYGR_EBUSY = 0, -1, -2, -3, -4, -5
+RELAYGR_TRIGGER_NOT_AT_RISK, RELAYGR_TRIGGER_ADMIT, RELAYGR_TRIGGER_REFUSED = 0, 1, 2
 RELAYGR_DTYPE_FP32, RELAYGR_DTYPE_BF16 = 0, 1
 RELAYGR_NO_CACHE = 0
 RELAYGR_TILE_TOKENS = 64
@@ -28,8 +29,15 @@ EXPORTS = [
     "relaygr_kv_pool_lookup", "relaygr_kv_pool_entry_len", "relaygr_kv_pool_stats", "relaygr_kv_pool_locate",
     "relaygr_prefill_prefix", "relaygr_rank_with_cache", "relaygr_rank_full_recompute",
     "relaygr_ctx_profile_enable", "relaygr_ctx_profile_read",
+    "relaygr_kv_pool_entry_bytes", "relaygr_kv_pool_spill", "relaygr_kv_pool_reload",
+    "relaygr_expander_create", "relaygr_expander_destroy", "relaygr_expander_retire",
+    "relaygr_expander_lookup", "relaygr_expander_stats",
+    "relaygr_admission_budget_compute", "relaygr_slot_throughput",
+    "relaygr_trigger_create", "relaygr_trigger_destroy", "relaygr_trigger_admit", "relaygr_trigger_release",
+    "relaygr_trigger_stats",
     "relaygr_last_error",
 ]
+EXPANDER_STATS = ["hbm_hits", "dram_hits", "misses", "refusals", "spills", "dram_evictions", "dram_bytes", "dram_entries"]
 KERNEL_CLASSES = ["setup", "ln", "f1", "attn", "gate", "f2", "score"]
 
 
@@ -55,6 +63,17 @@ class BatchC(C.Structure):
                 ("prefix_emb", C.c_void_p), ("prefix_off", C.POINTER(C.c_int32)),
                 ("suffix_emb", C.c_void_p), ("suffix_off", C.POINTER(C.c_int32)),
                 ("cand_emb", C.c_void_p), ("cand_off", C.POINTER(C.c_int32))]
+
+
+class AdmissionParamsC(C.Structure):
+    _fields_ = [("q_m", C.c_double), ("model_slots", C.c_int32), ("kv_p99_bytes", C.c_double),
+                ("hbm_bytes", C.c_double), ("r1", C.c_double), ("n_instances", C.c_int32),
+                ("r2", C.c_double), ("t_life_s", C.c_double)]
+
+
+class AdmissionBudgetC(C.Structure):
+    _fields_ = [(n, C.c_double) for n in
+                ("max_live_caches", "q_admit_hbm", "q_admit_compute", "q_admit", "q_max")]
 
 
 class RelayGRError(RuntimeError):
@@ -95,6 +114,21 @@ def load_library() -> C.CDLL:
         "relaygr_rank_full_recompute": (C.c_int, [vp, P(BatchC), vp, vp]),
         "relaygr_ctx_profile_enable": (C.c_int, [vp, C.c_uint32]),
         "relaygr_ctx_profile_read": (C.c_int, [vp, i32, P(C.c_double), P(i64)]),
+        "relaygr_kv_pool_entry_bytes": (sz, [vp, u64]),
+        "relaygr_kv_pool_spill": (C.c_int, [vp, u64, vp, sz, vp]),
+        "relaygr_kv_pool_reload": (C.c_int, [vp, u64, i32, vp, sz, vp, P(u64)]),
+        "relaygr_expander_create": (C.c_int, [vp, sz, i32, P(vp)]),
+        "relaygr_expander_destroy": (None, [vp]),
+        "relaygr_expander_retire": (C.c_int, [vp, u64, vp]),
+        "relaygr_expander_lookup": (C.c_int, [vp, u64, vp, P(u64), P(i32)]),
+        "relaygr_expander_stats": (C.c_int, [vp, P(i64)]),
+        "relaygr_admission_budget_compute": (C.c_int, [P(AdmissionParamsC), P(AdmissionBudgetC)]),
+        "relaygr_slot_throughput": (C.c_double, [C.c_double]),
+        "relaygr_trigger_create": (C.c_int, [P(AdmissionBudgetC), i32, P(vp)]),
+        "relaygr_trigger_destroy": (None, [vp]),
+        "relaygr_trigger_admit": (C.c_int, [vp, C.c_double, i32]),
+        "relaygr_trigger_release": (C.c_int, [vp]),
+        "relaygr_trigger_stats": (C.c_int, [vp, P(i64), P(i64), P(i64), P(i64)]),
         "relaygr_last_error": (C.c_char_p, []),
     }
     for name, (res, args) in sig.items():
@@ -268,6 +302,123 @@ def relaygr_kv_pool_locate(pool: KvPool, handle: int, layer: int, token: int, fe
     k, v = C.c_int64(), C.c_int64()
     _check(load_library().relaygr_kv_pool_locate(pool.handle, handle, layer, token, feature, C.byref(k), C.byref(v)))
     return k.value, v.value
+
+
+# ---- DRAM tier -------------------------------------------------------------------------------
+def relaygr_kv_pool_entry_bytes(pool: KvPool, handle: int) -> int:
+    return load_library().relaygr_kv_pool_entry_bytes(pool.handle, handle)
+
+
+def relaygr_kv_pool_spill(pool: KvPool, handle: int, host: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Enqueues the copy of the entry's extent into a pinned uint8 host tensor (made here if not given)."""
+    n = relaygr_kv_pool_entry_bytes(pool, handle)
+    if host is None:
+        host = torch.empty(n, dtype=torch.uint8, pin_memory=True)
+    _check(load_library().relaygr_kv_pool_spill(pool.handle, handle, host.data_ptr(), host.numel(), _stream_ptr(stream)))
+    return host
+
+
+def relaygr_kv_pool_reload(pool: KvPool, user_id: int, prefix_len: int, host: torch.Tensor, stream=None) -> int:
+    out = C.c_uint64(0)
+    _check(load_library().relaygr_kv_pool_reload(pool.handle, user_id, prefix_len, host.data_ptr(), host.numel(),
+                                                 _stream_ptr(stream), C.byref(out)))
+    return out.value
+
+
+class Expander:
+    """relaygr_expander over a KvPool."""
+
+    def __init__(self, pool: KvPool, dram_budget_bytes: int, max_inflight_reloads: int = 4):
+        self.pool = pool
+        h = C.c_void_p()
+        _check(load_library().relaygr_expander_create(pool.handle, dram_budget_bytes, max_inflight_reloads, C.byref(h)))
+        self.handle = h
+
+    def close(self):
+        if getattr(self, "handle", None):
+            load_library().relaygr_expander_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def relaygr_expander_retire(ex: Expander, handle: int, stream=None) -> None:
+    _check(load_library().relaygr_expander_retire(ex.handle, handle, _stream_ptr(stream)))
+
+
+def relaygr_expander_lookup(ex: Expander, user_id: int, stream=None):
+    """(handle, source) with source 0 = HBM, 1 = reloaded from DRAM; raises RelayGRError with code
+    RELAYGR_ENOENT (in neither tier) or RELAYGR_EBUSY (reload limit reached)."""
+    out, src = C.c_uint64(0), C.c_int32(-1)
+    _check(load_library().relaygr_expander_lookup(ex.handle, user_id, _stream_ptr(stream), C.byref(out), C.byref(src)))
+    return out.value, src.value
+
+
+def relaygr_expander_stats(ex: Expander) -> dict:
+    a = (C.c_int64 * 8)()
+    _check(load_library().relaygr_expander_stats(ex.handle, a))
+    return dict(zip(EXPANDER_STATS, list(a)))
+
+
+# ---- sequence-aware trigger (host arithmetic only) ---------------------------------------------
+def relaygr_admission_budget_compute(q_m: float, model_slots: int, kv_p99_bytes: float, hbm_bytes: float, r1: float,
+                                     n_instances: int, r2: float, t_life_s: float) -> dict:
+    p = AdmissionParamsC(q_m, model_slots, kv_p99_bytes, hbm_bytes, r1, n_instances, r2, t_life_s)
+    b = AdmissionBudgetC()
+    rc = load_library().relaygr_admission_budget_compute(C.byref(p), C.byref(b))
+    if rc != RELAYGR_OK:
+        raise RelayGRError(rc, "relaygr_admission_budget_compute: parameter out of range")
+    return {n: getattr(b, n) for n, _ in AdmissionBudgetC._fields_}
+
+
+def relaygr_slot_throughput(pre_infer_ms: float) -> float:
+    return load_library().relaygr_slot_throughput(pre_infer_ms)
+
+
+class Trigger:
+    """relaygr_trigger: the admission gate of one special instance."""
+
+    def __init__(self, budget: dict, len_threshold: int):
+        b = AdmissionBudgetC(*[budget[n] for n, _ in AdmissionBudgetC._fields_])
+        h = C.c_void_p()
+        rc = load_library().relaygr_trigger_create(C.byref(b), len_threshold, C.byref(h))
+        if rc != RELAYGR_OK:
+            raise RelayGRError(rc, "relaygr_trigger_create: bad budget or threshold")
+        self.handle = h
+
+    def close(self):
+        if getattr(self, "handle", None):
+            load_library().relaygr_trigger_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def relaygr_trigger_admit(t: Trigger, now_s: float, prefix_len: int) -> int:
+    rc = load_library().relaygr_trigger_admit(t.handle, now_s, prefix_len)
+    if rc < 0:
+        raise RelayGRError(rc, "relaygr_trigger_admit: bad argument")
+    return rc
+
+
+def relaygr_trigger_release(t: Trigger) -> None:
+    rc = load_library().relaygr_trigger_release(t.handle)
+    if rc != RELAYGR_OK:
+        raise RelayGRError(rc, "relaygr_trigger_release: no live cache to release")
+
+
+def relaygr_trigger_stats(t: Trigger) -> dict:
+    a, b, c, d = C.c_int64(), C.c_int64(), C.c_int64(), C.c_int64()
+    load_library().relaygr_trigger_stats(t.handle, C.byref(a), C.byref(b), C.byref(c), C.byref(d))
+    return {"live": a.value, "admitted": b.value, "refused": c.value, "not_at_risk": d.value}
 
 
 class Batch:

@@ -15,6 +15,7 @@
 #include "../../include/relaygr.h"
 #include "attention.h"
 #include "common.h"
+#include "errors.h"
 #include "gemm.h"
 #include "gemm_bf16.h"
 #include "kv_pool.h"
@@ -25,7 +26,7 @@ using namespace relaygr;
 // ---- errors -----------------------------------------------------------------------------------
 static thread_local char g_err[512] = "";
 
-static int fail(int code, const char* fmt, ...) {
+int relaygr::fail(int code, const char* fmt, ...) {
   va_list ap;
   va_start(ap, fmt);
   vsnprintf(g_err, sizeof(g_err), fmt, ap);

@@ -1,0 +1,273 @@
+"""GPU tests of the DRAM tier (Section 3.4, memory-aware expander): spill / reload of pool extents and
+the two-level lookup HBM -> DRAM.  A reloaded psi must be the same bytes, wherever in the pool it
+lands, and ranking with it must give bit-identical scores; ranking is still checked against the
+CPU oracle so that "identical" cannot mean "identically wrong"."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2601_01712_amd as rg
+import synth
+from gpu_util import Harness, build_case, oracle_scores
+
+pytestmark = pytest.mark.gpu
+
+CFG = synth.ModelConfig(2, 128, 2, "bf16")
+LENS = ([300, 129, 200, 64], [5, 0, 3, 0], [40, 66, 10, 7])
+
+
+def _harness(page_tokens=64, extra=8, lens=LENS, seed=131):
+    weights, batch = build_case(CFG, seed, *lens)
+    h = Harness(CFG, weights, batch, page_tokens, pool_extra_pages=extra)
+    return h, weights, batch
+
+
+def _rank_user(h, u, handle, stream=None):
+    sub = h.sub_batch([u])
+    sub.set_handles([handle])
+    s = rg.relaygr_rank_with_cache(h.ctx, h.pool, sub, stream=stream)
+    torch.cuda.synchronize()
+    return s.cpu().numpy()
+
+
+def _uid(batch, u):
+    return int(batch["user_ids"][u])
+
+
+def test_spill_free_reload_round_trip_is_bit_exact():
+    h, weights, batch = _harness()
+    try:
+        h.prefill()
+        want = oracle_scores(CFG, weights, batch, users=[0])
+        before = _rank_user(h, 0, int(h.handles[0]))
+        n = rg.relaygr_kv_pool_entry_bytes(h.pool, int(h.handles[0]))
+        assert n == 5 * rg.relaygr_kv_pool_bytes_for(h.ctx.cfg, 64, 64)       # 300 tokens = 5 pages of 64
+        image = rg.relaygr_kv_pool_spill(h.pool, int(h.handles[0]))
+        torch.cuda.synchronize()
+        rg.relaygr_kv_pool_free(h.pool, int(h.handles[0]))
+        assert rg.relaygr_kv_pool_entry_bytes(h.pool, int(h.handles[0])) == 0  # stale
+        # take the head of the freed extent so that the reload lands somewhere else, and poison the slab's free part
+        filler = rg.relaygr_kv_pool_alloc(h.pool, 999, 70)
+        k0_old = rg.relaygr_kv_pool_locate(h.pool, filler, 0, 0, 0)[0]
+        h2 = rg.relaygr_kv_pool_reload(h.pool, _uid(batch, 0), 300, image)
+        torch.cuda.synchronize()
+        assert rg.relaygr_kv_pool_locate(h.pool, h2, 0, 0, 0)[0] != k0_old
+        assert rg.relaygr_kv_pool_entry_len(h.pool, h2) == 300
+        after = _rank_user(h, 0, h2)
+        assert np.array_equal(before, after)
+        from gpu_util import assert_close
+        assert_close(after, want[0], "bf16", "rank after reload")
+        again = rg.relaygr_kv_pool_spill(h.pool, h2)
+        torch.cuda.synchronize()
+        assert torch.equal(image, again)
+        # wrong sizes are refused before anything is enqueued or allocated
+        with pytest.raises(rg.RelayGRError) as ei:
+            rg.relaygr_kv_pool_reload(h.pool, 12345, 64, image)
+        assert ei.value.code == rg.RELAYGR_EINVAL
+        assert rg.relaygr_kv_pool_lookup(h.pool, 12345) == rg.RELAYGR_NO_CACHE
+        with pytest.raises(rg.RelayGRError):
+            rg.relaygr_kv_pool_spill(h.pool, h2, host=torch.empty(n - 1, dtype=torch.uint8, pin_memory=True))
+    finally:
+        h.close()
+
+
+def test_fp32_round_trip():
+    cfg = synth.ModelConfig(2, 64, 2, "fp32")
+    weights, batch = build_case(cfg, 133, [150], [2], [9])
+    h = Harness(cfg, weights, batch, 64, pool_extra_pages=4)
+    try:
+        h.prefill()
+        before = h.rank_cached()
+        image = rg.relaygr_kv_pool_spill(h.pool, int(h.handles[0]))
+        torch.cuda.synchronize()
+        rg.relaygr_kv_pool_free(h.pool, int(h.handles[0]))
+        rg.relaygr_kv_pool_alloc(h.pool, 7, 64)
+        h.handles[0] = rg.relaygr_kv_pool_reload(h.pool, _uid(batch, 0), 150, image)
+        assert np.array_equal(before, h.rank_cached())
+    finally:
+        h.close()
+
+
+def test_expander_two_level_lookup():
+    h, weights, batch = _harness()
+    page = rg.relaygr_kv_pool_bytes_for(h.ctx.cfg, 64, 64)
+    ex = rg.Expander(h.pool, 64 * page, max_inflight_reloads=4)
+    try:
+        h.prefill()
+        base = {u: _rank_user(h, u, int(h.handles[u])) for u in range(4)}
+        live0 = rg.relaygr_kv_pool_stats(h.pool)["live_entries"]
+        assert live0 == 4
+        for u in range(3):
+            rg.relaygr_expander_retire(ex, int(h.handles[u]))
+        torch.cuda.synchronize()
+        st = rg.relaygr_expander_stats(ex)             # also observes the finished spills
+        assert st["spills"] == 3 and st["dram_entries"] == 3 and st["dram_bytes"] == (5 + 3 + 4) * page
+        assert rg.relaygr_kv_pool_stats(h.pool)["live_entries"] == 1
+        for u in range(3):
+            assert rg.relaygr_kv_pool_lookup(h.pool, _uid(batch, u)) == rg.RELAYGR_NO_CACHE
+        # level 2 hit: reloaded, the caller's stream is ordered behind the copy without a host wait
+        h0, src = rg.relaygr_expander_lookup(ex, _uid(batch, 0))
+        assert src == 1 and h0 != int(h.handles[0])
+        assert np.array_equal(_rank_user(h, 0, h0), base[0])
+        # level 1 hit: same handle again, nothing copied
+        h0b, src = rg.relaygr_expander_lookup(ex, _uid(batch, 0))
+        assert (h0b, src) == (h0, 0)
+        # user 3 was never retired: plain HBM hit
+        h3, src = rg.relaygr_expander_lookup(ex, _uid(batch, 3))
+        assert (h3, src) == (int(h.handles[3]), 0)
+        # neither tier
+        with pytest.raises(rg.RelayGRError) as ei:
+            rg.relaygr_expander_lookup(ex, 424242)
+        assert ei.value.code == rg.RELAYGR_ENOENT
+        # the others come back too, in any order
+        for u in (2, 1):
+            hu, src = rg.relaygr_expander_lookup(ex, _uid(batch, u))
+            assert src == 1
+            assert np.array_equal(_rank_user(h, u, hu), base[u])
+        st = rg.relaygr_expander_stats(ex)
+        assert (st["hbm_hits"], st["dram_hits"], st["misses"], st["refusals"]) == (2, 3, 1, 0)
+        assert rg.relaygr_kv_pool_stats(h.pool)["live_entries"] == 4
+    finally:
+        ex.close()
+        h.close()
+
+
+def test_expander_retire_then_reuse_and_second_retire():
+    """An entry looked up again while its retirement is pending stays live; a second retire supersedes
+    the first, so the extent is not released before the work that used it in between."""
+    h, weights, batch = _harness()
+    page = rg.relaygr_kv_pool_bytes_for(h.ctx.cfg, 64, 64)
+    ex = rg.Expander(h.pool, 32 * page)
+    try:
+        h.prefill()
+        base = _rank_user(h, 1, int(h.handles[1]))
+        rg.relaygr_expander_retire(ex, int(h.handles[1]))
+        hh, src = rg.relaygr_expander_lookup(ex, _uid(batch, 1))      # 0 if still pending, 1 if already spilled and freed
+        assert src in (0, 1)
+        assert np.array_equal(_rank_user(h, 1, hh), base)
+        rg.relaygr_expander_retire(ex, hh)
+        torch.cuda.synchronize()
+        rg.relaygr_expander_stats(ex)
+        assert rg.relaygr_kv_pool_lookup(h.pool, _uid(batch, 1)) == rg.RELAYGR_NO_CACHE
+        with pytest.raises(rg.RelayGRError) as ei:                     # the handle is stale now
+            rg.relaygr_expander_retire(ex, hh)
+        assert ei.value.code == rg.RELAYGR_ENOENT
+        hh2, src = rg.relaygr_expander_lookup(ex, _uid(batch, 1))
+        assert src == 1
+        assert np.array_equal(_rank_user(h, 1, hh2), base)
+        assert rg.relaygr_expander_stats(ex)["dram_entries"] == 1      # one image per user
+    finally:
+        ex.close()
+        h.close()
+
+
+def test_expander_evicts_least_recently_used_image():
+    lens = ([128, 128, 128], [0, 0, 0], [5, 6, 7])
+    h, weights, batch = _harness(lens=lens, seed=137)
+    page = rg.relaygr_kv_pool_bytes_for(h.ctx.cfg, 64, 64)
+    ex = rg.Expander(h.pool, 4 * page + 100)          # room for two 2-page images
+    try:
+        h.prefill()
+        base = {u: _rank_user(h, u, int(h.handles[u])) for u in range(3)}
+        A, B, Cc = (_uid(batch, u) for u in range(3))
+        rg.relaygr_expander_retire(ex, int(h.handles[0]))
+        rg.relaygr_expander_retire(ex, int(h.handles[1]))
+        torch.cuda.synchronize()
+        ha, src = rg.relaygr_expander_lookup(ex, A)    # touches A: B is now the older image
+        assert src == 1
+        rg.relaygr_expander_retire(ex, ha)             # same length: A's slot is reused
+        torch.cuda.synchronize()
+        assert rg.relaygr_expander_stats(ex)["dram_evictions"] == 0
+        rg.relaygr_expander_retire(ex, int(h.handles[2]))
+        torch.cuda.synchronize()
+        st = rg.relaygr_expander_stats(ex)
+        assert st["dram_evictions"] == 1 and st["dram_entries"] == 2 and st["dram_bytes"] == 4 * page
+        with pytest.raises(rg.RelayGRError) as ei:
+            rg.relaygr_expander_lookup(ex, B)
+        assert ei.value.code == rg.RELAYGR_ENOENT
+        for u, uid in ((0, A), (2, Cc)):
+            hu, src = rg.relaygr_expander_lookup(ex, uid)
+            assert src == 1
+            assert np.array_equal(_rank_user(h, u, hu), base[u])
+    finally:
+        ex.close()
+        h.close()
+
+
+def test_expander_without_room_only_frees():
+    h, weights, batch = _harness()
+    page = rg.relaygr_kv_pool_bytes_for(h.ctx.cfg, 64, 64)
+    ex = rg.Expander(h.pool, 2 * page)                # user 0 needs 5 pages
+    ex0 = rg.Expander(h.pool, 0)                      # no DRAM tier at all
+    try:
+        h.prefill()
+        for e, u in ((ex, 0), (ex0, 1)):
+            with pytest.raises(rg.RelayGRError) as ei:
+                rg.relaygr_expander_retire(e, int(h.handles[u]))
+            assert ei.value.code == rg.RELAYGR_ENOSPC
+            torch.cuda.synchronize()
+            assert rg.relaygr_expander_stats(e)["dram_entries"] == 0
+            assert rg.relaygr_kv_pool_lookup(h.pool, _uid(batch, u)) == rg.RELAYGR_NO_CACHE
+            with pytest.raises(rg.RelayGRError) as ei:
+                rg.relaygr_expander_lookup(e, _uid(batch, u))
+            assert ei.value.code == rg.RELAYGR_ENOENT
+    finally:
+        ex.close()
+        ex0.close()
+        h.close()
+
+
+def test_expander_reload_needs_a_free_extent():
+    h, weights, batch = _harness(extra=0)
+    page = rg.relaygr_kv_pool_bytes_for(h.ctx.cfg, 64, 64)
+    ex = rg.Expander(h.pool, 32 * page)
+    try:
+        h.prefill()
+        rg.relaygr_expander_retire(ex, int(h.handles[0]))
+        torch.cuda.synchronize()
+        rg.relaygr_expander_stats(ex)
+        filler = rg.relaygr_kv_pool_alloc(h.pool, 555, 300)       # takes the 5 pages user 0 left
+        with pytest.raises(rg.RelayGRError) as ei:
+            rg.relaygr_expander_lookup(ex, _uid(batch, 0))
+        assert ei.value.code == rg.RELAYGR_ENOSPC                  # invariant I2: no live entry is displaced
+        rg.relaygr_kv_pool_free(h.pool, filler)
+        hh, src = rg.relaygr_expander_lookup(ex, _uid(batch, 0))
+        assert src == 1
+    finally:
+        ex.close()
+        h.close()
+
+
+def test_expander_bounds_reloads_in_flight():
+    """With one reload allowed, a second DRAM hit is refused while the first is still queued behind
+    the caller's own work; every kernel involved runs to completion."""
+    h, weights, batch = _harness()
+    page = rg.relaygr_kv_pool_bytes_for(h.ctx.cfg, 64, 64)
+    ex = rg.Expander(h.pool, 32 * page, max_inflight_reloads=1)
+    try:
+        h.prefill()
+        base = {u: _rank_user(h, u, int(h.handles[u])) for u in range(3)}
+        rg.relaygr_expander_retire(ex, int(h.handles[0]))
+        rg.relaygr_expander_retire(ex, int(h.handles[1]))
+        torch.cuda.synchronize()
+        rg.relaygr_expander_stats(ex)
+        # queue a few milliseconds of work on the stream, then retire user 2 behind it: the copy
+        # stream now waits for that work, and so does every reload queued after it
+        torch.cuda._sleep(20_000_000)                # a bounded spin kernel on the current stream
+        for _ in range(4):
+            rg.relaygr_rank_full_recompute(h.ctx, h.dbatch)
+        rg.relaygr_expander_retire(ex, int(h.handles[2]))
+        h0, src = rg.relaygr_expander_lookup(ex, _uid(batch, 0))
+        assert src == 1
+        with pytest.raises(rg.RelayGRError) as ei:
+            rg.relaygr_expander_lookup(ex, _uid(batch, 1))
+        assert ei.value.code == rg.RELAYGR_EBUSY
+        torch.cuda.synchronize()
+        assert rg.relaygr_expander_stats(ex)["refusals"] == 1
+        h1, src = rg.relaygr_expander_lookup(ex, _uid(batch, 1))   # the first reload has finished
+        assert src == 1
+        assert np.array_equal(_rank_user(h, 0, h0), base[0])
+        assert np.array_equal(_rank_user(h, 1, h1), base[1])
+    finally:
+        ex.close()
+        h.close()
