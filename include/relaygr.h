@@ -243,21 +243,33 @@ int  relaygr_expander_create(relaygr_kv_pool* pool, size_t dram_budget_bytes, in
 /* Waits for the expander's outstanding copies, frees its DRAM.  Pool entries stay as they are. */
 void relaygr_expander_destroy(relaygr_expander* ex);
 /* After ranking has consumed an entry: once hip_stream has passed this point the entry is copied to
- * DRAM on the expander's own copy stream, and its HBM extent is released when that copy has completed
- * (observed at a later expander call).  The caller must not use the handle in work enqueued after
- * this call unless a later relaygr_expander_lookup returns it again.  RELAYGR_ENOSPC if the image
- * cannot be placed in DRAM (the entry is then only freed, once hip_stream has passed this point). */
+ * DRAM on the expander's own copy stream.  When that copy has completed (observed at a later
+ * expander call) the entry becomes RECLAIMABLE: it stays in HBM, still found by
+ * relaygr_expander_lookup (which makes it live again), until relaygr_expander_alloc or a reload
+ * needs its pages; reclaimable entries leave oldest retirement first.  The caller must not use the
+ * handle in work enqueued after this call unless a later relaygr_expander_lookup returns it again.
+ * RELAYGR_ENOSPC if the image cannot be placed in DRAM (the entry then becomes reclaimable without
+ * an image, once hip_stream has passed this point). */
 int  relaygr_expander_retire(relaygr_expander* ex, relaygr_kv_handle handle, void* hip_stream);
+/* Allocation for pre-inference under the sliding-window policy (Section 3.3, "HBM as a lifecycle
+ * window"): a free extent if there is one; otherwise reclaimable entries are released, oldest
+ * retirement first, until the extent fits.  An entry that was never retired is never displaced:
+ * RELAYGR_ENOSPC when live entries alone leave no room (Section 3.1, invariant I2).  A reclaimable
+ * entry of the same user is replaced; RELAYGR_EINVAL if the user has a live one. */
+int  relaygr_expander_alloc(relaygr_expander* ex, uint64_t user_id, int32_t prefix_len, relaygr_kv_handle* out);
+/* Releases reclaimable entries, oldest retirement first, until at most `keep` remain in HBM. */
+int  relaygr_expander_trim(relaygr_expander* ex, int32_t keep);
 /* The idempotent probe issued before every rank (pseudo-pre-infer): *source = 0 and the live handle if
  * psi is in HBM (a pending retire of it is cancelled); *source = 1 if it was found in DRAM, in which
- * case an entry is allocated, the reload is enqueued on the copy stream and hip_stream is made to wait
+ * case an entry is allocated (as by relaygr_expander_alloc), the reload is enqueued on the copy stream and hip_stream is made to wait
  * for it (no host wait); RELAYGR_ENOENT if neither tier has it (the caller ranks by full recompute
  * or pre-infers); RELAYGR_EBUSY if the reload limit is reached (the caller falls back, nothing queued). */
 int  relaygr_expander_lookup(relaygr_expander* ex, uint64_t user_id, void* hip_stream, relaygr_kv_handle* out,
                              int32_t* source);
 /* Counters since creation: [0] HBM hits, [1] DRAM hits (reloads), [2] misses, [3] refusals (busy),
- * [4] spills, [5] DRAM evictions, [6] DRAM bytes in use, [7] DRAM entries. */
-int  relaygr_expander_stats(relaygr_expander* ex, int64_t stats[8]);
+ * [4] spills, [5] DRAM evictions, [6] DRAM bytes in use, [7] DRAM entries, [8] HBM entries released
+ * by the window policy, [9] reclaimable HBM entries now. */
+int  relaygr_expander_stats(relaygr_expander* ex, int64_t stats[10]);
 
 /* ---- sequence-aware trigger, host side (Section 3.2, Eq. 1-3) --------------------------- */
 

@@ -31,13 +31,14 @@ EXPORTS = [
     "relaygr_ctx_profile_enable", "relaygr_ctx_profile_read",
     "relaygr_kv_pool_entry_bytes", "relaygr_kv_pool_spill", "relaygr_kv_pool_reload",
     "relaygr_expander_create", "relaygr_expander_destroy", "relaygr_expander_retire",
-    "relaygr_expander_lookup", "relaygr_expander_stats",
+    "relaygr_expander_alloc", "relaygr_expander_trim", "relaygr_expander_lookup", "relaygr_expander_stats",
     "relaygr_admission_budget_compute", "relaygr_slot_throughput",
     "relaygr_trigger_create", "relaygr_trigger_destroy", "relaygr_trigger_admit", "relaygr_trigger_release",
     "relaygr_trigger_stats",
     "relaygr_last_error",
 ]
-EXPANDER_STATS = ["hbm_hits", "dram_hits", "misses", "refusals", "spills", "dram_evictions", "dram_bytes", "dram_entries"]
+EXPANDER_STATS = ["hbm_hits", "dram_hits", "misses", "refusals", "spills", "dram_evictions", "dram_bytes", "dram_entries",
+                  "hbm_evictions", "hbm_reclaimable"]
 KERNEL_CLASSES = ["setup", "ln", "f1", "attn", "gate", "f2", "score"]
 
 
@@ -120,6 +121,8 @@ def load_library() -> C.CDLL:
         "relaygr_expander_create": (C.c_int, [vp, sz, i32, P(vp)]),
         "relaygr_expander_destroy": (None, [vp]),
         "relaygr_expander_retire": (C.c_int, [vp, u64, vp]),
+        "relaygr_expander_alloc": (C.c_int, [vp, u64, i32, P(u64)]),
+        "relaygr_expander_trim": (C.c_int, [vp, i32]),
         "relaygr_expander_lookup": (C.c_int, [vp, u64, vp, P(u64), P(i32)]),
         "relaygr_expander_stats": (C.c_int, [vp, P(i64)]),
         "relaygr_admission_budget_compute": (C.c_int, [P(AdmissionParamsC), P(AdmissionBudgetC)]),
@@ -350,6 +353,16 @@ def relaygr_expander_retire(ex: Expander, handle: int, stream=None) -> None:
     _check(load_library().relaygr_expander_retire(ex.handle, handle, _stream_ptr(stream)))
 
 
+def relaygr_expander_alloc(ex: Expander, user_id: int, prefix_len: int) -> int:
+    out = C.c_uint64(0)
+    _check(load_library().relaygr_expander_alloc(ex.handle, user_id, prefix_len, C.byref(out)))
+    return out.value
+
+
+def relaygr_expander_trim(ex: Expander, keep: int = 0) -> None:
+    _check(load_library().relaygr_expander_trim(ex.handle, keep))
+
+
 def relaygr_expander_lookup(ex: Expander, user_id: int, stream=None):
     """(handle, source) with source 0 = HBM, 1 = reloaded from DRAM; raises RelayGRError with code
     RELAYGR_ENOENT (in neither tier) or RELAYGR_EBUSY (reload limit reached)."""
@@ -359,7 +372,7 @@ def relaygr_expander_lookup(ex: Expander, user_id: int, stream=None):
 
 
 def relaygr_expander_stats(ex: Expander) -> dict:
-    a = (C.c_int64 * 8)()
+    a = (C.c_int64 * 10)()
     _check(load_library().relaygr_expander_stats(ex.handle, a))
     return dict(zip(EXPANDER_STATS, list(a)))
 

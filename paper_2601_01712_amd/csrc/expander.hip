@@ -5,6 +5,8 @@
 // extent), so its byte image can be reloaded anywhere in a pool of the same shape and page size.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+#include <deque>
 #include <mutex>
 #include <new>
 #include <unordered_map>
@@ -70,8 +72,12 @@ extern "C" int relaygr_kv_pool_reload(relaygr_kv_pool* pool, uint64_t user_id, i
 // The DRAM tier is a second pool of the same page geometry whose slab is one pinned host arena
 // allocated at creation: no allocation happens on the serving path.  Only the expander's copy
 // stream ever touches the arena, and copies on one stream run in order, so DRAM slots can be
-// recycled without waiting.  HBM extents are read by the caller's streams, so an extent is
-// released only after the event that follows its spill has completed.
+// recycled without waiting.  HBM extents are read by the caller's streams, so an extent becomes
+// reclaimable only after the event that follows its spill has completed.  Reclaimable entries stay
+// in HBM (a repeat request still hits them) until an allocation needs their pages: the HBM pool is
+// then a sliding window over users, consumed entries leaving it oldest retirement first (Section
+// 3.3, "HBM as a lifecycle window"), while an entry that was never retired is never displaced
+// (Section 3.1, invariant I2).
 namespace {
 struct PendingFree {
   relaygr_kv_handle handle;
@@ -87,11 +93,13 @@ struct relaygr_expander {
   int max_inflight = 1;
   hipStream_t copy_stream = nullptr;
   std::unordered_map<uint64_t, uint64_t> last_use;   // DRAM-resident user -> LRU stamp
-  std::vector<PendingFree> pending_free;
+  std::vector<PendingFree> pending_free;        // retired, spill not yet known to be complete
+  std::deque<relaygr_kv_handle> reclaimable;    // retired and spilled: still in HBM, oldest first
   std::vector<hipEvent_t> reloads;      // reloads that may still be in flight
   std::vector<hipEvent_t> spare_events;
   uint64_t clock = 0;
   int64_t stats[6] = {};
+  int64_t hbm_evictions = 0;
   std::mutex mu;
 };
 
@@ -102,12 +110,12 @@ static hipEvent_t get_event(relaygr_expander* ex) {
   return e;
 }
 
-// Retires what has completed: frees HBM extents whose spill has landed, forgets finished reloads.
+// Retires what has completed: entries whose spill has landed become reclaimable, finished reloads are forgotten.
 static void poll(relaygr_expander* ex) {
   for (size_t i = 0; i < ex->pending_free.size();) {
     PendingFree& pf = ex->pending_free[i];
     if (hipEventQuery(pf.spilled) == hipSuccess) {
-      if (!pf.cancelled) ex->hbm->release(pf.handle);
+      if (!pf.cancelled) ex->reclaimable.push_back(pf.handle);
       ex->spare_events.push_back(pf.spilled);
       ex->pending_free[i] = ex->pending_free.back();
       ex->pending_free.pop_back();
@@ -153,6 +161,27 @@ static bool dram_slot(relaygr_expander* ex, uint64_t user, int32_t prefix_len, P
   }
   ex->dram.resolve(h, slot);
   return true;
+}
+
+static void forget_reclaimable(relaygr_expander* ex, relaygr_kv_handle h) {
+  auto it = std::find(ex->reclaimable.begin(), ex->reclaimable.end(), h);
+  if (it != ex->reclaimable.end()) ex->reclaimable.erase(it);
+}
+
+// Pool allocation under the sliding-window policy: when nothing fits, reclaimable entries are
+// released oldest first until the extent fits or none is left.
+static int alloc_in_window(relaygr_expander* ex, uint64_t user, int32_t prefix_len, relaygr_kv_handle* h) {
+  for (;;) {
+    int rc = ex->hbm->alloc(user, prefix_len, h);
+    if (rc != RELAYGR_ENOSPC) return rc;
+    bool freed = false;
+    while (!freed && !ex->reclaimable.empty()) {
+      relaygr_kv_handle v = ex->reclaimable.front();
+      ex->reclaimable.pop_front();
+      if (ex->hbm->release(v) == RELAYGR_OK) { ex->hbm_evictions += 1; freed = true; }   // stale: the caller freed it itself
+    }
+    if (!freed) return RELAYGR_ENOSPC;
+  }
 }
 
 extern "C" int relaygr_expander_create(relaygr_kv_pool* pool, size_t dram_budget_bytes, int32_t max_inflight_reloads,
@@ -211,6 +240,7 @@ extern "C" int relaygr_expander_retire(relaygr_expander* ex, relaygr_kv_handle h
   // that release would come too early.  This retire supersedes it.
   for (auto& pf : ex->pending_free)
     if (pf.handle == h) pf.cancelled = true;
+  forget_reclaimable(ex, h);
   const size_t bytes = (size_t)e.npages * page_bytes(ex->hbm);
   hipEvent_t consumed = get_event(ex), spilled = get_event(ex);
   if (!consumed || !spilled) return fail(RELAYGR_EHIP, "expander_retire: cannot create events");
@@ -224,8 +254,8 @@ extern "C" int relaygr_expander_retire(relaygr_expander* ex, relaygr_kv_handle h
     ex->last_use[e.user_id] = ++ex->clock;
     ex->stats[4] += 1;
   } else {
-    // no DRAM for it: the entry is just released once the stream has consumed it
-    rc = fail(RELAYGR_ENOSPC, "expander_retire: no DRAM for %zu bytes; the entry is only freed", bytes);
+    // no DRAM for it: the entry still becomes reclaimable once the stream has consumed it
+    rc = fail(RELAYGR_ENOSPC, "expander_retire: no DRAM for %zu bytes; the entry has no image", bytes);
   }
   HIP_TRY(hipEventRecord(spilled, ex->copy_stream));
   ex->pending_free.push_back({h, spilled, false});
@@ -241,6 +271,7 @@ extern "C" int relaygr_expander_lookup(relaygr_expander* ex, uint64_t user_id, v
   if (ex->hbm->lookup(user_id, &h) == RELAYGR_OK) {         // level 1: HBM
     for (auto& pf : ex->pending_free)
       if (pf.handle == h) pf.cancelled = true;              // keep it live; its DRAM copy still completes
+    forget_reclaimable(ex, h);                              // live again until it is retired again
     // a reload of this entry may still be in flight on the copy stream: order the caller behind it
     hipEvent_t ev = get_event(ex);
     if (!ev) return fail(RELAYGR_EHIP, "expander_lookup: cannot create an event");
@@ -261,8 +292,8 @@ extern "C" int relaygr_expander_lookup(relaygr_expander* ex, uint64_t user_id, v
     return fail(RELAYGR_ENOENT, "expander_lookup: user %llu is in neither tier", (unsigned long long)user_id);
   }
   if ((int)ex->reloads.size() >= ex->max_inflight) { ex->stats[3] += 1; return fail(RELAYGR_EBUSY, "expander_lookup: %d reloads already in flight", ex->max_inflight); }
-  int rc = ex->hbm->alloc(user_id, slot.prefix_len, &h);
-  if (rc != RELAYGR_OK) return fail(rc, "expander_lookup: no free extent to reload %d tokens", slot.prefix_len);
+  int rc = alloc_in_window(ex, user_id, slot.prefix_len, &h);
+  if (rc != RELAYGR_OK) return fail(rc, "expander_lookup: no free or reclaimable extent to reload %d tokens", slot.prefix_len);
   PoolEntry e;
   ex->hbm->resolve(h, &e);
   hipEvent_t done = get_event(ex);
@@ -281,7 +312,39 @@ extern "C" int relaygr_expander_lookup(relaygr_expander* ex, uint64_t user_id, v
   return RELAYGR_OK;
 }
 
-extern "C" int relaygr_expander_stats(relaygr_expander* ex, int64_t stats[8]) {
+extern "C" int relaygr_expander_alloc(relaygr_expander* ex, uint64_t user_id, int32_t prefix_len, relaygr_kv_handle* out) {
+  if (!ex || !out) return fail(RELAYGR_EINVAL, "expander_alloc: null argument");
+  *out = RELAYGR_NO_CACHE;
+  std::lock_guard<std::mutex> lk(ex->mu);
+  poll(ex);
+  // a reclaimable entry of the same user is superseded by the new pre-inference
+  relaygr_kv_handle old;
+  if (ex->hbm->lookup(user_id, &old) == RELAYGR_OK) {
+    auto it = std::find(ex->reclaimable.begin(), ex->reclaimable.end(), old);
+    if (it == ex->reclaimable.end()) return fail(RELAYGR_EINVAL, "expander_alloc: user %llu already has a live entry", (unsigned long long)user_id);
+    ex->reclaimable.erase(it);
+    ex->hbm->release(old);
+    ex->hbm_evictions += 1;
+  }
+  int rc = alloc_in_window(ex, user_id, prefix_len, out);
+  if (rc == RELAYGR_ENOSPC) return fail(rc, "expander_alloc: live entries leave no extent for %d tokens", prefix_len);
+  if (rc != RELAYGR_OK) return fail(rc, "expander_alloc: prefix_len < 1");
+  return RELAYGR_OK;
+}
+
+extern "C" int relaygr_expander_trim(relaygr_expander* ex, int32_t keep) {
+  if (!ex || keep < 0) return fail(RELAYGR_EINVAL, "expander_trim: null expander or keep < 0");
+  std::lock_guard<std::mutex> lk(ex->mu);
+  poll(ex);
+  while ((int64_t)ex->reclaimable.size() > keep) {
+    relaygr_kv_handle v = ex->reclaimable.front();
+    ex->reclaimable.pop_front();
+    if (ex->hbm->release(v) == RELAYGR_OK) ex->hbm_evictions += 1;
+  }
+  return RELAYGR_OK;
+}
+
+extern "C" int relaygr_expander_stats(relaygr_expander* ex, int64_t stats[10]) {
   if (!ex || !stats) return fail(RELAYGR_EINVAL, "expander_stats: null argument");
   std::lock_guard<std::mutex> lk(ex->mu);
   poll(ex);
@@ -290,5 +353,7 @@ extern "C" int relaygr_expander_stats(relaygr_expander* ex, int64_t stats[8]) {
   ex->dram.stats(&total, &free_pages, &live, nullptr);
   stats[6] = (total - free_pages) * (int64_t)page_bytes(ex->hbm);
   stats[7] = live;
+  stats[8] = ex->hbm_evictions;
+  stats[9] = (int64_t)ex->reclaimable.size();
   return RELAYGR_OK;
 }

@@ -88,6 +88,12 @@ def test_fp32_round_trip():
         h.close()
 
 
+def _settle(ex):
+    """Waits for the GPU and lets the expander observe finished spills and reloads."""
+    torch.cuda.synchronize()
+    return rg.relaygr_expander_stats(ex)
+
+
 def test_expander_two_level_lookup():
     h, weights, batch = _harness()
     page = rg.relaygr_kv_pool_bytes_for(h.ctx.cfg, 64, 64)
@@ -95,13 +101,22 @@ def test_expander_two_level_lookup():
     try:
         h.prefill()
         base = {u: _rank_user(h, u, int(h.handles[u])) for u in range(4)}
-        live0 = rg.relaygr_kv_pool_stats(h.pool)["live_entries"]
-        assert live0 == 4
+        assert rg.relaygr_kv_pool_stats(h.pool)["live_entries"] == 4
         for u in range(3):
             rg.relaygr_expander_retire(ex, int(h.handles[u]))
-        torch.cuda.synchronize()
-        st = rg.relaygr_expander_stats(ex)             # also observes the finished spills
+        st = _settle(ex)
         assert st["spills"] == 3 and st["dram_entries"] == 3 and st["dram_bytes"] == (5 + 3 + 4) * page
+        # retired entries stay in HBM, reclaimable, and a repeat request still hits them there
+        assert st["hbm_reclaimable"] == 3 and rg.relaygr_kv_pool_stats(h.pool)["live_entries"] == 4
+        h2, src = rg.relaygr_expander_lookup(ex, _uid(batch, 2))
+        assert (h2, src) == (int(h.handles[2]), 0)
+        assert rg.relaygr_expander_stats(ex)["hbm_reclaimable"] == 2
+        rg.relaygr_expander_retire(ex, h2)
+        assert _settle(ex)["hbm_reclaimable"] == 3
+        # the window moves on: all reclaimable entries leave HBM, the live one stays
+        rg.relaygr_expander_trim(ex, 0)
+        st = rg.relaygr_expander_stats(ex)
+        assert st["hbm_evictions"] == 3 and st["hbm_reclaimable"] == 0
         assert rg.relaygr_kv_pool_stats(h.pool)["live_entries"] == 1
         for u in range(3):
             assert rg.relaygr_kv_pool_lookup(h.pool, _uid(batch, u)) == rg.RELAYGR_NO_CACHE
@@ -125,7 +140,7 @@ def test_expander_two_level_lookup():
             assert src == 1
             assert np.array_equal(_rank_user(h, u, hu), base[u])
         st = rg.relaygr_expander_stats(ex)
-        assert (st["hbm_hits"], st["dram_hits"], st["misses"], st["refusals"]) == (2, 3, 1, 0)
+        assert (st["hbm_hits"], st["dram_hits"], st["misses"], st["refusals"]) == (3, 3, 1, 0)
         assert rg.relaygr_kv_pool_stats(h.pool)["live_entries"] == 4
     finally:
         ex.close()
@@ -134,7 +149,7 @@ def test_expander_two_level_lookup():
 
 def test_expander_retire_then_reuse_and_second_retire():
     """An entry looked up again while its retirement is pending stays live; a second retire supersedes
-    the first, so the extent is not released before the work that used it in between."""
+    the first, so the extent does not become reclaimable before the work that used it in between."""
     h, weights, batch = _harness()
     page = rg.relaygr_kv_pool_bytes_for(h.ctx.cfg, 64, 64)
     ex = rg.Expander(h.pool, 32 * page)
@@ -142,12 +157,15 @@ def test_expander_retire_then_reuse_and_second_retire():
         h.prefill()
         base = _rank_user(h, 1, int(h.handles[1]))
         rg.relaygr_expander_retire(ex, int(h.handles[1]))
-        hh, src = rg.relaygr_expander_lookup(ex, _uid(batch, 1))      # 0 if still pending, 1 if already spilled and freed
-        assert src in (0, 1)
+        hh, src = rg.relaygr_expander_lookup(ex, _uid(batch, 1))
+        assert (hh, src) == (int(h.handles[1]), 0)
         assert np.array_equal(_rank_user(h, 1, hh), base)
+        assert _settle(ex)["hbm_reclaimable"] == 0                     # the cancelled retirement leaves it live
+        rg.relaygr_expander_trim(ex, 0)
+        assert rg.relaygr_kv_pool_lookup(h.pool, _uid(batch, 1)) == hh
         rg.relaygr_expander_retire(ex, hh)
-        torch.cuda.synchronize()
-        rg.relaygr_expander_stats(ex)
+        assert _settle(ex)["hbm_reclaimable"] == 1
+        rg.relaygr_expander_trim(ex, 0)
         assert rg.relaygr_kv_pool_lookup(h.pool, _uid(batch, 1)) == rg.RELAYGR_NO_CACHE
         with pytest.raises(rg.RelayGRError) as ei:                     # the handle is stale now
             rg.relaygr_expander_retire(ex, hh)
@@ -156,6 +174,59 @@ def test_expander_retire_then_reuse_and_second_retire():
         assert src == 1
         assert np.array_equal(_rank_user(h, 1, hh2), base)
         assert rg.relaygr_expander_stats(ex)["dram_entries"] == 1      # one image per user
+    finally:
+        ex.close()
+        h.close()
+
+
+def test_window_allocation_displaces_consumed_entries_oldest_first_and_never_a_live_one():
+    """Section 3.3 (HBM as a lifecycle window) with Section 3.1's invariant I2."""
+    lens = ([128, 128, 128, 128], [0, 0, 0, 0], [5, 6, 7, 8])
+    h, weights, batch = _harness(lens=lens, seed=139, extra=0)        # a pool of exactly 8 pages, all in use
+    page = rg.relaygr_kv_pool_bytes_for(h.ctx.cfg, 64, 64)
+    ex = rg.Expander(h.pool, 64 * page)
+    try:
+        h.prefill()
+        base = {u: _rank_user(h, u, int(h.handles[u])) for u in range(4)}
+        with pytest.raises(rg.RelayGRError) as ei:                     # everything is live: no room, nothing displaced
+            rg.relaygr_expander_alloc(ex, 7001, 128)
+        assert ei.value.code == rg.RELAYGR_ENOSPC
+        assert rg.relaygr_kv_pool_stats(h.pool)["live_entries"] == 4
+        for u in (2, 0, 1):                                            # retirement order: 2, 0, 1; user 3 stays live
+            rg.relaygr_expander_retire(ex, int(h.handles[u]))
+            _settle(ex)
+        n1 = rg.relaygr_expander_alloc(ex, 7001, 128)                  # displaces user 2, the oldest retirement
+        assert rg.relaygr_kv_pool_lookup(h.pool, _uid(batch, 2)) == rg.RELAYGR_NO_CACHE
+        assert rg.relaygr_kv_pool_lookup(h.pool, _uid(batch, 0)) == int(h.handles[0])
+        n2 = rg.relaygr_expander_alloc(ex, 7002, 200)                  # 4 pages: users 0 and 1 both go
+        assert rg.relaygr_kv_pool_entry_len(h.pool, n2) == 200
+        for u in (0, 1):
+            assert rg.relaygr_kv_pool_lookup(h.pool, _uid(batch, u)) == rg.RELAYGR_NO_CACHE
+        st = rg.relaygr_expander_stats(ex)
+        assert st["hbm_evictions"] == 3 and st["hbm_reclaimable"] == 0
+        with pytest.raises(rg.RelayGRError) as ei:                     # only live entries are left
+            rg.relaygr_expander_alloc(ex, 7003, 64)
+        assert ei.value.code == rg.RELAYGR_ENOSPC
+        assert np.array_equal(_rank_user(h, 3, int(h.handles[3])), base[3])
+        with pytest.raises(rg.RelayGRError) as ei:                     # a live user cannot be allocated twice
+            rg.relaygr_expander_alloc(ex, _uid(batch, 3), 128)
+        assert ei.value.code == rg.RELAYGR_EINVAL
+        # the displaced users are still in DRAM: give one its pages back
+        rg.relaygr_kv_pool_free(h.pool, n1)
+        h2, src = rg.relaygr_expander_lookup(ex, _uid(batch, 2))
+        assert src == 1
+        assert np.array_equal(_rank_user(h, 2, h2), base[2])
+        # a reload displaces reclaimable entries too
+        rg.relaygr_expander_retire(ex, h2)
+        _settle(ex)
+        h0, src = rg.relaygr_expander_lookup(ex, _uid(batch, 0))
+        assert src == 1 and rg.relaygr_kv_pool_lookup(h.pool, _uid(batch, 2)) == rg.RELAYGR_NO_CACHE
+        assert np.array_equal(_rank_user(h, 0, h0), base[0])
+        # pre-inference again for a user whose old entry is reclaimable replaces that entry
+        rg.relaygr_expander_retire(ex, h0)
+        _settle(ex)
+        h0n = rg.relaygr_expander_alloc(ex, _uid(batch, 0), 128)
+        assert h0n != h0 and rg.relaygr_kv_pool_lookup(h.pool, _uid(batch, 0)) == h0n
     finally:
         ex.close()
         h.close()
@@ -172,16 +243,16 @@ def test_expander_evicts_least_recently_used_image():
         A, B, Cc = (_uid(batch, u) for u in range(3))
         rg.relaygr_expander_retire(ex, int(h.handles[0]))
         rg.relaygr_expander_retire(ex, int(h.handles[1]))
-        torch.cuda.synchronize()
+        _settle(ex)
+        rg.relaygr_expander_trim(ex, 0)
         ha, src = rg.relaygr_expander_lookup(ex, A)    # touches A: B is now the older image
         assert src == 1
         rg.relaygr_expander_retire(ex, ha)             # same length: A's slot is reused
-        torch.cuda.synchronize()
-        assert rg.relaygr_expander_stats(ex)["dram_evictions"] == 0
+        assert _settle(ex)["dram_evictions"] == 0
         rg.relaygr_expander_retire(ex, int(h.handles[2]))
-        torch.cuda.synchronize()
-        st = rg.relaygr_expander_stats(ex)
+        st = _settle(ex)
         assert st["dram_evictions"] == 1 and st["dram_entries"] == 2 and st["dram_bytes"] == 4 * page
+        rg.relaygr_expander_trim(ex, 0)
         with pytest.raises(rg.RelayGRError) as ei:
             rg.relaygr_expander_lookup(ex, B)
         assert ei.value.code == rg.RELAYGR_ENOENT
@@ -194,7 +265,7 @@ def test_expander_evicts_least_recently_used_image():
         h.close()
 
 
-def test_expander_without_room_only_frees():
+def test_expander_without_room_keeps_no_image():
     h, weights, batch = _harness()
     page = rg.relaygr_kv_pool_bytes_for(h.ctx.cfg, 64, 64)
     ex = rg.Expander(h.pool, 2 * page)                # user 0 needs 5 pages
@@ -205,9 +276,14 @@ def test_expander_without_room_only_frees():
             with pytest.raises(rg.RelayGRError) as ei:
                 rg.relaygr_expander_retire(e, int(h.handles[u]))
             assert ei.value.code == rg.RELAYGR_ENOSPC
-            torch.cuda.synchronize()
-            assert rg.relaygr_expander_stats(e)["dram_entries"] == 0
-            assert rg.relaygr_kv_pool_lookup(h.pool, _uid(batch, u)) == rg.RELAYGR_NO_CACHE
+            st = _settle(e)
+            assert st["dram_entries"] == 0 and st["hbm_reclaimable"] == 1
+            hh, src = rg.relaygr_expander_lookup(e, _uid(batch, u))       # still in HBM
+            assert (hh, src) == (int(h.handles[u]), 0)
+            with pytest.raises(rg.RelayGRError):
+                rg.relaygr_expander_retire(e, hh)
+            _settle(e)
+            rg.relaygr_expander_trim(e, 0)
             with pytest.raises(rg.RelayGRError) as ei:
                 rg.relaygr_expander_lookup(e, _uid(batch, u))
             assert ei.value.code == rg.RELAYGR_ENOENT
@@ -224,9 +300,8 @@ def test_expander_reload_needs_a_free_extent():
     try:
         h.prefill()
         rg.relaygr_expander_retire(ex, int(h.handles[0]))
-        torch.cuda.synchronize()
-        rg.relaygr_expander_stats(ex)
-        filler = rg.relaygr_kv_pool_alloc(h.pool, 555, 300)       # takes the 5 pages user 0 left
+        _settle(ex)
+        filler = rg.relaygr_expander_alloc(ex, 555, 300)          # takes the 5 pages of user 0
         with pytest.raises(rg.RelayGRError) as ei:
             rg.relaygr_expander_lookup(ex, _uid(batch, 0))
         assert ei.value.code == rg.RELAYGR_ENOSPC                  # invariant I2: no live entry is displaced
@@ -249,8 +324,8 @@ def test_expander_bounds_reloads_in_flight():
         base = {u: _rank_user(h, u, int(h.handles[u])) for u in range(3)}
         rg.relaygr_expander_retire(ex, int(h.handles[0]))
         rg.relaygr_expander_retire(ex, int(h.handles[1]))
-        torch.cuda.synchronize()
-        rg.relaygr_expander_stats(ex)
+        _settle(ex)
+        rg.relaygr_expander_trim(ex, 0)
         # queue a few milliseconds of work on the stream, then retire user 2 behind it: the copy
         # stream now waits for that work, and so does every reload queued after it
         torch.cuda._sleep(20_000_000)                # a bounded spin kernel on the current stream
@@ -262,8 +337,7 @@ def test_expander_bounds_reloads_in_flight():
         with pytest.raises(rg.RelayGRError) as ei:
             rg.relaygr_expander_lookup(ex, _uid(batch, 1))
         assert ei.value.code == rg.RELAYGR_EBUSY
-        torch.cuda.synchronize()
-        assert rg.relaygr_expander_stats(ex)["refusals"] == 1
+        assert _settle(ex)["refusals"] == 1
         h1, src = rg.relaygr_expander_lookup(ex, _uid(batch, 1))   # the first reload has finished
         assert src == 1
         assert np.array_equal(_rank_user(h, 0, h0), base[0])

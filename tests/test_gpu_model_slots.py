@@ -1,0 +1,64 @@
+"""Two model slots on one GPU (Section 3.2, "Concurrency inside a special instance"): pre-inference
+for some users runs on one stream while ranking for other users runs on another, both against the
+same HBM pool.  Scores must equal those of the same calls run alone, bit for bit, and the oracle's."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2601_01712_amd as rg
+import synth
+from gpu_util import Harness, assert_close, build_case, oracle_scores
+
+pytestmark = pytest.mark.gpu
+
+
+def test_prefill_and_rank_on_two_streams_share_one_pool():
+    cfg = synth.ModelConfig(3, 256, 4, "bf16")
+    L, S, M = [700, 300, 1500, 900], [10, 0, 4, 0], [150, 40, 260, 33]
+    weights, batch = build_case(cfg, 141, L, S, M)
+    want = oracle_scores(cfg, weights, batch)
+    h = Harness(cfg, weights, batch, page_tokens=128)
+    ctx2 = rg.Context(cfg, weights, 4, sum(L), sum(S) + sum(M))      # the second slot: its own scratch
+    try:
+        # solo reference runs: everything on the current stream
+        h.prefill([0, 1, 2, 3])
+        solo = h.rank_cached()
+        h.check(solo, want, "solo")
+        for u in (2, 3):
+            rg.relaygr_kv_pool_free(h.pool, int(h.handles[u]))
+        h.pool.slab.view(torch.int16)[:] = 0x7FC1                      # poison, then restore users 0 and 1 only
+        h.handles[2] = h.handles[3] = 0
+        for u in (0, 1):
+            rg.relaygr_kv_pool_free(h.pool, int(h.handles[u]))
+        h.prefill([0, 1])
+
+        s_rank, s_pre = torch.cuda.Stream(), torch.cuda.Stream()       # default priority
+        rank01 = h.sub_batch([0, 1]); rank01.set_handles([h.handles[0], h.handles[1]])
+        new = [rg.relaygr_kv_pool_alloc(h.pool, int(batch["user_ids"][u]), L[u]) for u in (2, 3)]
+        pre23 = h.sub_batch([2, 3]); pre23.set_handles(new)
+        torch.cuda.synchronize()
+        outs = []
+        for i in range(6):                                             # slot 1 ranks users 0,1 over and over ...
+            outs.append(rg.relaygr_rank_with_cache(h.ctx, h.pool, rank01, stream=s_rank))
+            if i % 2 == 0:                                             # ... while slot 2 pre-infers users 2,3
+                rg.relaygr_prefill_prefix(ctx2, h.pool, pre23, stream=s_pre)
+        torch.cuda.synchronize()
+        co = batch["cand_off"]
+        for o in outs:
+            assert np.array_equal(o.cpu().numpy(), solo[:co[2]])
+        # what slot 2 left in the pool serves ranking of users 2,3, from either slot
+        h.handles[2], h.handles[3] = new
+        both = h.rank_cached()
+        assert np.array_equal(both, solo)
+        h.check(both, want, "after concurrent pre-inference")
+        rank23 = h.sub_batch([2, 3]); rank23.set_handles(new)
+        s = rg.relaygr_rank_with_cache(ctx2, h.pool, rank23, stream=s_pre)
+        torch.cuda.synchronize()
+        # another batch composition may split the key range differently (another fp32 summation order, and
+        # through bf16 rounding of intermediates another last bit), so this one is held to the oracle's bound
+        got = s.cpu().numpy()
+        for i, u in enumerate((2, 3)):
+            assert_close(got[co[u] - co[2]:co[u + 1] - co[2]], want[u], "bf16", f"slot 2 ranking user {u}")
+    finally:
+        ctx2.close()
+        h.close()
