@@ -663,6 +663,8 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
   const int R = p.n_rows;
   constexpr bool kPanel = !std::is_same<T, float>::value;   // bf16: xh / y are written as MFMA panels
 
+  // bf16: the output projection also applies the next layer's input LayerNorm (one pass over x less)
+  const bool fuse_ln = bf16 && (d == 128 || d == 256 || d == 512 || d == 1024);
   for (int l = 0; l < NL; ++l) {
     const relaygr_layer_weights& lw = c->layers[l];
     const bool last = (l == NL - 1);
@@ -670,8 +672,9 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
     const int a0 = last ? p.n_prows : 0;
     const bool have_active = a0 < R;
 
-    // step 1: input LayerNorm (first layer also gathers the embeddings into the residual stream)
-    {
+    // step 1: input LayerNorm (first layer also gathers the embeddings into the residual stream);
+    // later layers of the fused bf16 path got it from the previous layer's output projection
+    if (l == 0 || !fuse_ln) {
       ProfScope ps(c, RELAYGR_K_LN, st);
       dim3 grid((R + kRowsPerBlock - 1) / kRowsPerBlock);
       bool ok = dispatch_e(d, [&](auto e) {
@@ -747,11 +750,40 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
         ColMap one = {1, {0, 0, 0, 0}, d};
         GemmLaunch<T>::run(xh, (const T*)lw.w2, d, a0, R, one, e2, st);
       } else {
-        F2Params fp;
-        fp.A = (const uint16_t*)xh; fp.W = c->w2_packed[l]; fp.bias = (const uint16_t*)lw.b2; fp.x = x; fp.rt = rt; fp.d = d;
-        fp.row_begin = a0; fp.row_end = R; fp.n_mtiles = (R - a0 + 64 * kF2TM - 1) / (64 * kF2TM);
-        int total = fp.n_mtiles * (d / (64 * kF2TN));
-        hipLaunchKernelGGL(f2_gemm_bf16_kernel, dim3((total + 7) / 8 * 8), dim3(256), 0, st, fp);
+        if (fuse_ln) {
+          F2LnParams fp;
+          fp.A = (const uint16_t*)xh; fp.W = c->w2_packed[l]; fp.bias = (const uint16_t*)lw.b2; fp.x = x; fp.rt = rt;
+          fp.xh = last ? nullptr : (uint16_t*)xh;
+          fp.gain = last ? nullptr : (const uint16_t*)c->layers[l + 1].ln_in_g;
+          fp.offs = last ? nullptr : (const uint16_t*)c->layers[l + 1].ln_in_b;
+          fp.row_begin = a0; fp.row_end = R; fp.eps = cfg.ln_eps;
+          // two row blocks per workgroup halve the passes over W2 once that still leaves every
+          // compute unit two workgroups
+          const int rows = R - a0;
+          const bool rb2 = d <= 512 && rows >= 64 * 512;
+          dim3 grid((rows + (rb2 ? 63 : 31)) / (rb2 ? 64 : 32));
+          switch (d) {
+            case 128:
+              if (rb2) hipLaunchKernelGGL((f2_ln_bf16_kernel<128, 4, 2>), grid, dim3(256), 0, st, fp);
+              else hipLaunchKernelGGL((f2_ln_bf16_kernel<128, 4, 1>), grid, dim3(256), 0, st, fp);
+              break;
+            case 256:
+              if (rb2) hipLaunchKernelGGL((f2_ln_bf16_kernel<256, 8, 2>), grid, dim3(512), 0, st, fp);
+              else hipLaunchKernelGGL((f2_ln_bf16_kernel<256, 8, 1>), grid, dim3(512), 0, st, fp);
+              break;
+            case 512:
+              if (rb2) hipLaunchKernelGGL((f2_ln_bf16_kernel<512, 8, 2>), grid, dim3(512), 0, st, fp);
+              else hipLaunchKernelGGL((f2_ln_bf16_kernel<512, 8, 1>), grid, dim3(512), 0, st, fp);
+              break;
+            default: hipLaunchKernelGGL((f2_ln_bf16_kernel<1024, 8, 1>), grid, dim3(512), 0, st, fp); break;
+          }
+        } else {
+          F2Params fp;
+          fp.A = (const uint16_t*)xh; fp.W = c->w2_packed[l]; fp.bias = (const uint16_t*)lw.b2; fp.x = x; fp.rt = rt; fp.d = d;
+          fp.row_begin = a0; fp.row_end = R; fp.n_mtiles = (R - a0 + 64 * kF2TM - 1) / (64 * kF2TM);
+          int total = fp.n_mtiles * (d / (64 * kF2TN));
+          hipLaunchKernelGGL(f2_gemm_bf16_kernel, dim3((total + 7) / 8 * 8), dim3(256), 0, st, fp);
+        }
       }
     }
     LAUNCH_CHECK("f2");

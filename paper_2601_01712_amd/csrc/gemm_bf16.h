@@ -347,4 +347,178 @@ __global__ __launch_bounds__(256, 2) void f2_gemm_bf16_kernel(F2Params p) {
   }
 }
 
+// ---- f2 fused with the next layer's input LayerNorm -------------------------------------------
+// x <- x + y W2^T + b2, then xh <- LN(x; next layer's gain, offset), for 32*RB rows per
+// workgroup over the full width D.  Everything after the attention of one layer up to the
+// projections of the next is local to a row, so the residual row is read and written once and the
+// separate LayerNorm pass (one more read of x) disappears.  The 32 tokens' y sit in LDS in
+// fragment order (shared by all wavefronts); a wavefront owns D/32/NW feature blocks and streams
+// its own slice of the packed W2 from L2 straight into registers (no wavefront shares weights with
+// another, so LDS would add nothing), PF k-steps ahead.  Feature-major product: a lane ends up
+// with one token and runs of 4 features, so the row statistics are a lane-local sum, one
+// cross-half shuffle and one exchange between wavefronts through LDS.
+struct F2LnParams {
+  const uint16_t* A;        // y panels (gate output); may alias xh
+  const uint16_t* W;        // packed W2 [D, D]
+  const uint16_t* bias;     // b2 [D]
+  float* x;                 // residual stream [rows, D], updated in place
+  uint16_t* xh;             // LN(x) panels for the next layer; nullptr: none wanted (last layer)
+  const uint16_t* gain;     // next layer's input LayerNorm
+  const uint16_t* offs;
+  RowTables rt;
+  int row_begin, row_end;   // row_begin is a multiple of 32
+  float eps;
+};
+
+template <int D, int NW, int RB>
+__global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
+  constexpr int KS = D / 16;            // k-steps
+  constexpr int FB = D / 32 / NW;       // 32-feature blocks per wavefront
+  constexpr int PF = FB >= 4 ? 4 : 8;   // k-steps of weight fragments in flight per wavefront
+  constexpr int ROWS = 32 * RB;         // rows per workgroup: RB blocks of 32 share one pass over W2
+  static_assert(FB >= 1 && FB * NW * 32 == D && KS % PF == 0, "shape");
+  static_assert(RB * KS * 1024 <= 65536, "token fragments fit static LDS");
+  __shared__ __attribute__((aligned(16))) uint16_t tok[RB * KS * 512];   // ROWS tokens x D, fragment order
+  float* red = reinterpret_cast<float*>(tok);                             // reused after the product: [2][NW][ROWS]
+  const int row0 = p.row_begin + blockIdx.x * ROWS;
+  if (row0 >= p.row_end) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, g = lane >> 5;
+
+  // the workgroup's tokens: (row block b, k-step ks) is one 1 KiB fragment of the panel holding the block
+#pragma unroll
+  for (int b = 0; b < RB; ++b) {
+    const uint16_t* abase = p.A + panel_off(row0 + 32 * b, 0, D) + lane * 8;
+    for (int ks = wave; ks < KS; ks += NW)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(abase + (size_t)ks * 2048),
+                                       (__attribute__((address_space(3))) void*)(&tok[(b * KS + ks) * 512]), 16, 0, 0);
+  }
+
+  // this wavefront's weight fragments: feature block fb lives in panel fb/4, row block fb%4
+  const uint16_t* wbase[FB];
+#pragma unroll
+  for (int j = 0; j < FB; ++j) {
+    const int fb = wave * FB + j;
+    wbase[j] = p.W + (size_t)(fb >> 2) * KS * 2048 + (fb & 3) * 512 + lane * 8;
+  }
+  bf16x8_t wf[PF][FB];
+#pragma unroll
+  for (int i = 0; i < PF; ++i)
+#pragma unroll
+    for (int j = 0; j < FB; ++j) wf[i][j] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(wbase[j] + (size_t)i * 2048));
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+
+  // The accumulators start from the residual row plus the bias, fetched now so that the product
+  // hides the latency: element e of acc[b][j] is feature (wave*FB + j)*32 + 8*(e/4) + 4*g + e%4 of
+  // token row0 + 32*b + l32.
+  bool in_range[RB], live[RB];
+  float* xrow[RB];
+  f32x16_t acc[RB][FB];
+#pragma unroll
+  for (int b = 0; b < RB; ++b) {
+    const int row = row0 + 32 * b + l32;
+    in_range[b] = row < p.row_end;
+    live[b] = in_range[b] && p.rt.kind[in_range[b] ? row : row0] != kRowPad;
+    xrow[b] = p.x + (size_t)(in_range[b] ? row : row0) * D;
+#pragma unroll
+    for (int j = 0; j < FB; ++j)
+#pragma unroll
+      for (int e4 = 0; e4 < 4; ++e4) {
+        const int c = (wave * FB + j) * 32 + 8 * e4 + 4 * g;
+        const uint2 bb = *reinterpret_cast<const uint2*>(p.bias + c);
+        const float4 v = live[b] ? *reinterpret_cast<const float4*>(xrow[b] + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+        acc[b][j][4 * e4] = v.x + bf16_bits_to_float(bb.x & 0xFFFF);
+        acc[b][j][4 * e4 + 1] = v.y + bf16_bits_to_float(bb.x >> 16);
+        acc[b][j][4 * e4 + 2] = v.z + bf16_bits_to_float(bb.y & 0xFFFF);
+        acc[b][j][4 * e4 + 3] = v.w + bf16_bits_to_float(bb.y >> 16);
+      }
+  }
+
+  for (int ks0 = 0; ks0 < KS; ks0 += PF) {
+#pragma unroll
+    for (int i = 0; i < PF; ++i) {
+      const int ks = ks0 + i;
+      bf16x8_t tf[RB];
+#pragma unroll
+      for (int b = 0; b < RB; ++b) tf[b] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(&tok[(b * KS + ks) * 512 + lane * 8]));
+#pragma unroll
+      for (int j = 0; j < FB; ++j)
+#pragma unroll
+        for (int b = 0; b < RB; ++b) acc[b][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i][j], tf[b], acc[b][j], 0, 0, 0);
+      if (ks + PF < KS) {
+#pragma unroll
+        for (int j = 0; j < FB; ++j) wf[i][j] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(wbase[j] + (size_t)(ks + PF) * 2048));
+      }
+    }
+  }
+
+  // the new residual rows go back; their sums start the LayerNorm statistics
+  float s1[RB];
+#pragma unroll
+  for (int b = 0; b < RB; ++b) {
+    s1[b] = 0.f;
+#pragma unroll
+    for (int j = 0; j < FB; ++j)
+#pragma unroll
+      for (int e4 = 0; e4 < 4; ++e4) {
+        const int c = (wave * FB + j) * 32 + 8 * e4 + 4 * g;
+        const float4 v = make_float4(acc[b][j][4 * e4], acc[b][j][4 * e4 + 1], acc[b][j][4 * e4 + 2], acc[b][j][4 * e4 + 3]);
+        if (live[b]) *reinterpret_cast<float4*>(xrow[b] + c) = v;
+        s1[b] += (v.x + v.y) + (v.z + v.w);
+      }
+  }
+  if (p.xh == nullptr) return;          // uniform over the grid
+
+  // LayerNorm of the new residual rows: two passes over the registers, sums exchanged through LDS
+  __syncthreads();                      // every wavefront is done reading tok
+#pragma unroll
+  for (int b = 0; b < RB; ++b) {
+    s1[b] += __shfl_xor(s1[b], 32, 64);
+    if (g == 0) red[wave * ROWS + 32 * b + l32] = s1[b];
+  }
+  __syncthreads();
+  float mean[RB], s2[RB];
+#pragma unroll
+  for (int b = 0; b < RB; ++b) {
+    mean[b] = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) mean[b] += red[w * ROWS + 32 * b + l32];
+    mean[b] *= 1.0f / (float)D;
+    s2[b] = 0.f;
+#pragma unroll
+    for (int j = 0; j < FB; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { const float c = acc[b][j][e] - mean[b]; s2[b] += c * c; }
+    s2[b] += __shfl_xor(s2[b], 32, 64);
+    if (g == 0) red[(NW + wave) * ROWS + 32 * b + l32] = s2[b];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int b = 0; b < RB; ++b) {
+    float var = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) var += red[(NW + w) * ROWS + 32 * b + l32];
+    const float rstd = rsqrtf(var * (1.0f / (float)D) + p.eps);
+    if (!in_range[b]) continue;
+    const int row = row0 + 32 * b + l32;
+#pragma unroll
+    for (int j = 0; j < FB; ++j)
+#pragma unroll
+      for (int e4 = 0; e4 < 4; ++e4) {
+        const int c = (wave * FB + j) * 32 + 8 * e4 + 4 * g;
+        const uint2 gg = *reinterpret_cast<const uint2*>(p.gain + c), oo = *reinterpret_cast<const uint2*>(p.offs + c);
+        float z0 = (acc[b][j][4 * e4] - mean[b]) * rstd * bf16_bits_to_float(gg.x & 0xFFFF) + bf16_bits_to_float(oo.x & 0xFFFF);
+        float z1 = (acc[b][j][4 * e4 + 1] - mean[b]) * rstd * bf16_bits_to_float(gg.x >> 16) + bf16_bits_to_float(oo.x >> 16);
+        float z2 = (acc[b][j][4 * e4 + 2] - mean[b]) * rstd * bf16_bits_to_float(gg.y & 0xFFFF) + bf16_bits_to_float(oo.y & 0xFFFF);
+        float z3 = (acc[b][j][4 * e4 + 3] - mean[b]) * rstd * bf16_bits_to_float(gg.y >> 16) + bf16_bits_to_float(oo.y >> 16);
+        if (!live[b]) z0 = z1 = z2 = z3 = 0.f;     // filler rows stay finite
+        f32x2_t lo = {z0, z1}, hi = {z2, z3};
+        uint2 out;
+        out.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2_t));
+        out.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2_t));
+        *reinterpret_cast<uint2*>(p.xh + panel_off(row, c, D)) = out;
+      }
+  }
+}
+
 }  // namespace relaygr
