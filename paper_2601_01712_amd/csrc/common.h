@@ -127,4 +127,31 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
+// v + (v of the lane the DPP control selects), on the vector ALU (no LDS crossbar round trip).
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v) {
+  return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+// Sum over each group of 2, 4, 8, 16 consecutive lanes, left in every lane of the group:
+// quad_perm [1,0,3,2], quad_perm [2,3,0,1], row_half_mirror, row_mirror.
+__device__ __forceinline__ float lanes2_sum(float v) { return dpp_add<0xB1>(v); }
+__device__ __forceinline__ float lanes4_sum(float v) { return dpp_add<0x4E>(lanes2_sum(v)); }
+__device__ __forceinline__ float lanes8_sum(float v) { return dpp_add<0x141>(lanes4_sum(v)); }
+__device__ __forceinline__ float lanes16_sum(float v) { return dpp_add<0x140>(lanes8_sum(v)); }
+// Sum over each half of the wavefront, in every lane of the half.
+__device__ __forceinline__ float lanes32_sum(float v) {
+  v = lanes16_sum(v);
+  const int b = __float_as_int(v);
+  const float lo = __int_as_float(__builtin_amdgcn_readlane(b, 0)) + __int_as_float(__builtin_amdgcn_readlane(b, 16));
+  const float hi = __int_as_float(__builtin_amdgcn_readlane(b, 32)) + __int_as_float(__builtin_amdgcn_readlane(b, 48));
+  return (threadIdx.x & 32) ? hi : lo;
+}
+// Sum over the wavefront, in every lane: 16-lane sums by DPP, the four of them through scalar registers.
+__device__ __forceinline__ float wave_sum_dpp(float v) {
+  v = lanes16_sum(v);
+  const int b = __float_as_int(v);
+  return (__int_as_float(__builtin_amdgcn_readlane(b, 0)) + __int_as_float(__builtin_amdgcn_readlane(b, 16))) +
+         (__int_as_float(__builtin_amdgcn_readlane(b, 32)) + __int_as_float(__builtin_amdgcn_readlane(b, 48)));
+}
+
 }  // namespace relaygr

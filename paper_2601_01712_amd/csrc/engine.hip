@@ -730,8 +730,8 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
       rc = launch_attention<T>(cfg, ap, nt, nq, st);
       if (rc != RELAYGR_OK) return rc;
     }
-    // steps 3-4: combine splits, self term, 1/n, LayerNorm, gate by u
-    {
+    // steps 3-4: combine splits, self term, 1/n, LayerNorm, gate by u (part of the fused kernel below otherwise)
+    if (!fuse_ln) {
       ProfScope ps(c, RELAYGR_K_GATE, st);
       dim3 grid((R - a0 + kRowsPerBlock - 1) / kRowsPerBlock);
       dispatch_e(d, [&](auto e) {
@@ -752,11 +752,15 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
       } else {
         if (fuse_ln) {
           F2LnParams fp;
-          fp.A = (const uint16_t*)xh; fp.W = c->w2_packed[l]; fp.bias = (const uint16_t*)lw.b2; fp.x = x; fp.rt = rt;
+          fp.W = c->w2_packed[l]; fp.bias = (const uint16_t*)lw.b2; fp.x = x; fp.rt = rt;
           fp.xh = last ? nullptr : (uint16_t*)xh;
           fp.gain = last ? nullptr : (const uint16_t*)c->layers[l + 1].ln_in_g;
           fp.offs = last ? nullptr : (const uint16_t*)c->layers[l + 1].ln_in_b;
           fp.row_begin = a0; fp.row_end = R; fp.eps = cfg.ln_eps;
+          fp.part = part; fp.nsplit = p.nsplit; fp.split_stride = (size_t)R * d;
+          fp.u = (const uint16_t*)ubuf; fp.q = (const uint16_t*)qbuf; fp.knew = (const uint16_t*)knew; fp.vnew = (const uint16_t*)vnew;
+          fp.gate_gain = (const uint16_t*)lw.ln_at_g; fp.gate_offs = (const uint16_t*)lw.ln_at_b;
+          fp.n_prows = p.n_prows; fp.dh = dh; fp.qk_mul = gate_mul;
           // two row blocks per workgroup halve the passes over W2 once that still leaves every
           // compute unit two workgroups
           const int rows = R - a0;

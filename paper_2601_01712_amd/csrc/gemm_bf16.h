@@ -347,18 +347,33 @@ __global__ __launch_bounds__(256, 2) void f2_gemm_bf16_kernel(F2Params p) {
   }
 }
 
-// ---- f2 fused with the next layer's input LayerNorm -------------------------------------------
-// x <- x + y W2^T + b2, then xh <- LN(x; next layer's gain, offset), for 32*RB rows per
-// workgroup over the full width D.  Everything after the attention of one layer up to the
-// projections of the next is local to a row, so the residual row is read and written once and the
-// separate LayerNorm pass (one more read of x) disappears.  The 32 tokens' y sit in LDS in
-// fragment order (shared by all wavefronts); a wavefront owns D/32/NW feature blocks and streams
-// its own slice of the packed W2 from L2 straight into registers (no wavefront shares weights with
-// another, so LDS would add nothing), PF k-steps ahead.  Feature-major product: a lane ends up
-// with one token and runs of 4 features, so the row statistics are a lane-local sum, one
-// cross-half shuffle and one exchange between wavefronts through LDS.
+// ---- gate + f2 + next layer's input LayerNorm in one kernel ------------------------------------
+// Everything between the attention of one layer and the projections of the next is local to a row:
+//   y  = LN((sum of key-split partial sums + a candidate's self term) / n; g_at, b_at) * u
+//   x <- x + y W2^T + b2
+//   xh = LN(x; next layer's g_in, b_in)
+// so one workgroup takes 32*RB rows over the full width D and does all three: y never goes to HBM,
+// the residual row is read and written once, and two row-wise passes disappear.  Each wavefront
+// gates ROWS/NW rows (lane = D/64 consecutive features, DPP reductions) and writes them into LDS as
+// MFMA token fragments shared by all wavefronts; it owns D/32/NW feature blocks of the product and
+// streams its own slice of the packed W2 from L2 straight into registers (no wavefront shares
+// weights with another, so LDS would add nothing), PF k-steps ahead.  Feature-major product: a lane
+// ends up with one token and runs of 4 features, so the row statistics of the second LayerNorm are
+// a lane-local sum, one cross-half shuffle and one exchange between wavefronts through LDS.  Every
+// global load that does not depend on a result is issued before the first wait.
 struct F2LnParams {
-  const uint16_t* A;        // y panels (gate output); may alias xh
+  // gate inputs
+  const float* part;        // [nsplit][rows][D] unnormalised attention sums
+  int nsplit;
+  size_t split_stride;
+  const uint16_t* u;        // [rows, D]
+  const uint16_t* q;        // [rows, D] (pre-scaled)
+  const uint16_t* knew;     // [new rows, D] row-major k and v of suffix and candidate rows
+  const uint16_t* vnew;
+  const uint16_t* gate_gain;
+  const uint16_t* gate_offs;
+  int n_prows, dh;
+  float qk_mul;             // stored q . k -> alpha <q, k>
   const uint16_t* W;        // packed W2 [D, D]
   const uint16_t* bias;     // b2 [D]
   float* x;                 // residual stream [rows, D], updated in place
@@ -370,11 +385,142 @@ struct F2LnParams {
   float eps;
 };
 
+
+// E consecutive bf16 values (E = 2, 4, 8 or 16; address aligned to 2*E bytes, at most 16) as packed words.
+template <int E>
+__device__ __forceinline__ void ld_bf16_run(const uint16_t* src, uint32_t (&w)[E / 2]) {
+  if constexpr (E == 2) {
+    w[0] = *reinterpret_cast<const uint32_t*>(src);
+  } else if constexpr (E == 4) {
+    const uint2 v = *reinterpret_cast<const uint2*>(src);
+    w[0] = v.x; w[1] = v.y;
+  } else {
+#pragma unroll
+    for (int c = 0; c < E / 8; ++c) {
+      const uint4 v = *reinterpret_cast<const uint4*>(src + 8 * c);
+      w[4 * c] = v.x; w[4 * c + 1] = v.y; w[4 * c + 2] = v.z; w[4 * c + 3] = v.w;
+    }
+  }
+}
+__device__ __forceinline__ float bf16_of_word(uint32_t w, int i) { return __uint_as_float((i & 1) ? (w & 0xFFFF0000u) : (w << 16)); }
+
+// One row of the attention combine + gate, by one wavefront, lane owning features [lane*E, lane*E+E):
+// loads are issued by load_gate_row for several rows before any of them is reduced.
+template <int E>
+struct GateRow {
+  float o[E];
+  uint32_t ub[E / 2], qb[E / 2], kb[E / 2], vb[E / 2];
+  int n, kind;
+};
+
+template <int D>
+__device__ __forceinline__ void load_gate_row(const F2LnParams& p, int row, bool ok, int lane, GateRow<D / 64>& gr) {
+  constexpr int E = D / 64;
+  // nothing here waits for the row's kind: every load of the row is issued at once
+  gr.kind = ok ? p.rt.kind[row] : kRowPad;
+  gr.n = ok ? p.rt.lim[row] : 1;
+#pragma unroll
+  for (int i = 0; i < E; ++i) gr.o[i] = 0.f;
+#pragma unroll
+  for (int i = 0; i < E / 2; ++i) gr.ub[i] = gr.qb[i] = gr.kb[i] = gr.vb[i] = 0u;
+  if (!ok) return;
+  const size_t base = (size_t)row * D + lane * E;
+  for (int s = 0; s < p.nsplit; ++s) {
+    const float* src = p.part + s * p.split_stride + base;
+    if constexpr (E == 2) {
+      const float2 v = *reinterpret_cast<const float2*>(src);
+      gr.o[0] += v.x; gr.o[1] += v.y;
+    } else {
+#pragma unroll
+      for (int c = 0; c < E / 4; ++c) {
+        const float4 v = *reinterpret_cast<const float4*>(src + 4 * c);
+        gr.o[4 * c] += v.x; gr.o[4 * c + 1] += v.y; gr.o[4 * c + 2] += v.z; gr.o[4 * c + 3] += v.w;
+      }
+    }
+  }
+  ld_bf16_run<E>(p.u + base, gr.ub);
+  if (row >= p.n_prows) {           // suffix and candidate rows have row-major q, k, v (only candidates use them)
+    const size_t nb = (size_t)(row - p.n_prows) * D + lane * E;
+    ld_bf16_run<E>(p.q + base, gr.qb);
+    ld_bf16_run<E>(p.knew + nb, gr.kb);
+    ld_bf16_run<E>(p.vnew + nb, gr.vb);
+  }
+}
+
+// Finishes G rows at once (their reductions interleave) and writes y (bf16) into the token
+// fragments: local row lr0 + i of the workgroup goes to row block (lr0+i)/32, row (lr0+i)%32.
+template <int D, int G>
+__device__ __forceinline__ void finish_gate_rows(const F2LnParams& p, GateRow<D / 64> (&gr)[G], int lane, uint16_t* tok, int lr0,
+                                                 const uint32_t (&gw)[D / 128], const uint32_t (&ow)[D / 128]) {
+  constexpr int E = D / 64, KS = D / 16;
+  float s[G], inv_n[G];
+#pragma unroll
+  for (int r = 0; r < G; ++r) {
+    int n = gr[r].n;
+    if (gr[r].kind == kRowCand) {      // the candidate's own key: SiLU(alpha <q_c, k_c>) v_c per head
+      float dot = 0.f;
+#pragma unroll
+      for (int i = 0; i < E; ++i) dot += bf16_of_word(gr[r].qb[i >> 1], i) * bf16_of_word(gr[r].kb[i >> 1], i);
+      // the lanes of one head are dh/E consecutive lanes
+      const int hl = p.dh / E;
+      if (hl == 2) dot = lanes2_sum(dot);
+      else if (hl == 4) dot = lanes4_sum(dot);
+      else if (hl == 8) dot = lanes8_sum(dot);
+      else if (hl == 16) dot = lanes16_sum(dot);
+      else if (hl == 32) dot = lanes32_sum(dot);
+      else if (hl == 64) dot = wave_sum_dpp(dot);
+      const float pself = silu_f32(dot * p.qk_mul);
+#pragma unroll
+      for (int i = 0; i < E; ++i) gr[r].o[i] += pself * bf16_of_word(gr[r].vb[i >> 1], i);
+      n += 1;
+    }
+    inv_n[r] = 1.0f / (float)(n > 0 ? n : 1);
+    s[r] = 0.f;
+#pragma unroll
+    for (int i = 0; i < E; ++i) { gr[r].o[i] *= inv_n[r]; s[r] += gr[r].o[i]; }
+  }
+  float mean[G], qv[G];
+#pragma unroll
+  for (int r = 0; r < G; ++r) mean[r] = wave_sum_dpp(s[r]) * (1.0f / (float)D);
+#pragma unroll
+  for (int r = 0; r < G; ++r) {
+    qv[r] = 0.f;
+#pragma unroll
+    for (int i = 0; i < E; ++i) { const float c = gr[r].o[i] - mean[r]; qv[r] += c * c; }
+  }
+#pragma unroll
+  for (int r = 0; r < G; ++r) {
+    const float rstd = rsqrtf(wave_sum_dpp(qv[r]) * (1.0f / (float)D) + p.eps);
+    uint32_t yw[E / 2];
+#pragma unroll
+    for (int i = 0; i < E / 2; ++i) {
+      float z0 = (gr[r].o[2 * i] - mean[r]) * rstd * bf16_of_word(gw[i], 0) + bf16_of_word(ow[i], 0);
+      float z1 = (gr[r].o[2 * i + 1] - mean[r]) * rstd * bf16_of_word(gw[i], 1) + bf16_of_word(ow[i], 1);
+      f32x2_t two = {z0 * bf16_of_word(gr[r].ub[i], 0), z1 * bf16_of_word(gr[r].ub[i], 1)};
+      if (gr[r].kind == kRowPad) { two[0] = 0.f; two[1] = 0.f; }
+      yw[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2_t));
+    }
+    // feature f of a row block's local row rr sits at fragment f/16, lane (f/8 % 2)*32 + rr, element f%8
+    const int lr = lr0 + r;
+    uint16_t* tokb = tok + (lr >> 5) * KS * 512;
+    const int rr = lr & 31;
+    constexpr int RUN = E < 8 ? E : 8;
+#pragma unroll
+    for (int c = 0; c < E; c += RUN) {
+      const int f = lane * E + c;
+      uint16_t* dst = tokb + (f >> 4) * 512 + (((f >> 3) & 1) * 32 + rr) * 8 + (f & 7);
+      if constexpr (RUN == 2) *reinterpret_cast<uint32_t*>(dst) = yw[c / 2];
+      else if constexpr (RUN == 4) *reinterpret_cast<uint2*>(dst) = make_uint2(yw[c / 2], yw[c / 2 + 1]);
+      else *reinterpret_cast<uint4*>(dst) = make_uint4(yw[c / 2], yw[c / 2 + 1], yw[c / 2 + 2], yw[c / 2 + 3]);
+    }
+  }
+}
+
 template <int D, int NW, int RB>
 __global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
   constexpr int KS = D / 16;            // k-steps
   constexpr int FB = D / 32 / NW;       // 32-feature blocks per wavefront
-  constexpr int PF = FB >= 4 ? 4 : 8;   // k-steps of weight fragments in flight per wavefront
+  constexpr int PF = FB >= 4 ? 2 : 8;   // k-steps of weight fragments in flight per wavefront
   constexpr int ROWS = 32 * RB;         // rows per workgroup: RB blocks of 32 share one pass over W2
   static_assert(FB >= 1 && FB * NW * 32 == D && KS % PF == 0, "shape");
   static_assert(RB * KS * 1024 <= 65536, "token fragments fit static LDS");
@@ -384,14 +530,20 @@ __global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
   if (row0 >= p.row_end) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, g = lane >> 5;
 
-  // the workgroup's tokens: (row block b, k-step ks) is one 1 KiB fragment of the panel holding the block
+  // The gate makes the tokens: each wavefront takes ROWS/NW rows, a few at a time
+  // so that their loads are in flight together.  The first group's loads go out before anything
+  // else, since they are what the workgroup needs first.
+  constexpr int RPW = ROWS / NW, GMAX = RB * FB >= 4 ? (D >= 1024 ? 1 : 2) : 4, GROUP = RPW < GMAX ? RPW : GMAX;
+  static_assert(RPW >= 1 && RPW % GROUP == 0, "rows per wavefront");
+  GateRow<D / 64> gr[GROUP];
+  uint32_t gw[D / 128], ow[D / 128];
 #pragma unroll
-  for (int b = 0; b < RB; ++b) {
-    const uint16_t* abase = p.A + panel_off(row0 + 32 * b, 0, D) + lane * 8;
-    for (int ks = wave; ks < KS; ks += NW)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(abase + (size_t)ks * 2048),
-                                       (__attribute__((address_space(3))) void*)(&tok[(b * KS + ks) * 512]), 16, 0, 0);
+  for (int i = 0; i < GROUP; ++i) {
+    const int lr = wave * RPW + i;
+    load_gate_row<D>(p, row0 + lr, row0 + lr < p.row_end, lane, gr[i]);
   }
+  ld_bf16_run<D / 64>(p.gate_gain + lane * (D / 64), gw);
+  ld_bf16_run<D / 64>(p.gate_offs + lane * (D / 64), ow);
 
   // this wavefront's weight fragments: feature block fb lives in panel fb/4, row block fb%4
   const uint16_t* wbase[FB];
@@ -405,20 +557,18 @@ __global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
   for (int i = 0; i < PF; ++i)
 #pragma unroll
     for (int j = 0; j < FB; ++j) wf[i][j] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(wbase[j] + (size_t)i * 2048));
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
-
-  // The accumulators start from the residual row plus the bias, fetched now so that the product
-  // hides the latency: element e of acc[b][j] is feature (wave*FB + j)*32 + 8*(e/4) + 4*g + e%4 of
-  // token row0 + 32*b + l32.
+  // The accumulators start from the residual row plus the bias, fetched now so that the gate and
+  // the product hide the latency (the row's kind is only needed when results are stored): element
+  // e of acc[b][j] is feature (wave*FB + j)*32 + 8*(e/4) + 4*g + e%4 of token row0 + 32*b + l32.
   bool in_range[RB], live[RB];
   float* xrow[RB];
+  int kind_ep[RB];
   f32x16_t acc[RB][FB];
 #pragma unroll
   for (int b = 0; b < RB; ++b) {
     const int row = row0 + 32 * b + l32;
     in_range[b] = row < p.row_end;
-    live[b] = in_range[b] && p.rt.kind[in_range[b] ? row : row0] != kRowPad;
+    kind_ep[b] = p.rt.kind[in_range[b] ? row : row0];
     xrow[b] = p.x + (size_t)(in_range[b] ? row : row0) * D;
 #pragma unroll
     for (int j = 0; j < FB; ++j)
@@ -426,13 +576,28 @@ __global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
       for (int e4 = 0; e4 < 4; ++e4) {
         const int c = (wave * FB + j) * 32 + 8 * e4 + 4 * g;
         const uint2 bb = *reinterpret_cast<const uint2*>(p.bias + c);
-        const float4 v = live[b] ? *reinterpret_cast<const float4*>(xrow[b] + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+        const float4 v = *reinterpret_cast<const float4*>(xrow[b] + c);
         acc[b][j][4 * e4] = v.x + bf16_bits_to_float(bb.x & 0xFFFF);
         acc[b][j][4 * e4 + 1] = v.y + bf16_bits_to_float(bb.x >> 16);
         acc[b][j][4 * e4 + 2] = v.z + bf16_bits_to_float(bb.y & 0xFFFF);
         acc[b][j][4 * e4 + 3] = v.w + bf16_bits_to_float(bb.y >> 16);
       }
   }
+
+  // now that everything else is in flight behind them, the first rows are reduced and written as
+  // token fragments; further groups of rows follow
+  finish_gate_rows<D, GROUP>(p, gr, lane, tok, wave * RPW, gw, ow);
+#pragma unroll
+  for (int r0 = GROUP; r0 < RPW; r0 += GROUP) {
+#pragma unroll
+    for (int i = 0; i < GROUP; ++i) {
+      const int lr = wave * RPW + r0 + i;
+      load_gate_row<D>(p, row0 + lr, row0 + lr < p.row_end, lane, gr[i]);
+    }
+    finish_gate_rows<D, GROUP>(p, gr, lane, tok, wave * RPW + r0, gw, ow);
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
 
   for (int ks0 = 0; ks0 < KS; ks0 += PF) {
 #pragma unroll
@@ -456,6 +621,7 @@ __global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
   float s1[RB];
 #pragma unroll
   for (int b = 0; b < RB; ++b) {
+    live[b] = in_range[b] && kind_ep[b] != kRowPad;
     s1[b] = 0.f;
 #pragma unroll
     for (int j = 0; j < FB; ++j)
