@@ -39,6 +39,8 @@ WORKLOAD_TEXT = {
     "C3": "C3: bf16, 8 layers, d=512, 8 heads; 16 users x (prefix 4096, 512 candidates), K/V resident in the HBM pool",
     "C4": "C4: bf16, 8 layers, d=512, 8 heads; 32 users x (prefix 8192, 1000 candidates)",
     "C5": "C5: bf16, 8 layers, d=512, 8 heads; 64 users, prefix lognormal in [512,16384], 200-2000 candidates, suffix 0-64, ~30% uncached",
+    "X1": "X1 (width axis): bf16, 8 layers, d=1024, 8 heads; 16 users x (prefix 4096, 512 candidates)",
+    "X2": "X2 (depth axis): bf16, 16 layers, d=512, 8 heads; 16 users x (prefix 4096, 512 candidates)",
 }
 
 
@@ -341,6 +343,15 @@ def main() -> int:
             "algorithmic_GBps": round(kv_bytes / (avg_ms * 1e-3) / 1e9, 1),
             "hbm_frac_of_8TBps": round(kv_bytes / (avg_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4),
         }
+
+    # ---- what the chip sustains on this MFMA in a pure MFMA loop (its power limit lowers the clock as operand bits
+    # toggle): context for the fraction of the published peak above
+    if roof is not None and cfg.dtype == "bf16":
+        torch.cuda.synchronize()
+        pc, pr = rg.relaygr_probe_mfma(False), rg.relaygr_probe_mfma(True)
+        roof["mfma_loop_sustained"] = {"constant_operands_TFLOPs": round(pc["tflops"], 1), "constant_operands_GHz": round(pc["shader_ghz"], 3),
+                                       "random_operands_TFLOPs": round(pr["tflops"], 1), "random_operands_GHz": round(pr["shader_ghz"], 3)}
+        roof["frac_of_sustained_random"] = round(roof["achieved"] / pr["tflops"], 4)
 
     # ---- CPU oracle on a bounded sample: one user of this workload, full recompute
     cpu = None

@@ -35,6 +35,7 @@ EXPORTS = [
     "relaygr_admission_budget_compute", "relaygr_slot_throughput",
     "relaygr_trigger_create", "relaygr_trigger_destroy", "relaygr_trigger_admit", "relaygr_trigger_release",
     "relaygr_trigger_stats",
+    "relaygr_probe_bytes", "relaygr_probe_mfma",
     "relaygr_last_error",
 ]
 EXPANDER_STATS = ["hbm_hits", "dram_hits", "misses", "refusals", "spills", "dram_evictions", "dram_bytes", "dram_entries",
@@ -132,6 +133,8 @@ def load_library() -> C.CDLL:
         "relaygr_trigger_admit": (C.c_int, [vp, C.c_double, i32]),
         "relaygr_trigger_release": (C.c_int, [vp]),
         "relaygr_trigger_stats": (C.c_int, [vp, P(i64), P(i64), P(i64), P(i64)]),
+        "relaygr_probe_bytes": (sz, []),
+        "relaygr_probe_mfma": (C.c_int, [vp, sz, i32, i32, vp, P(C.c_double), P(C.c_double)]),
         "relaygr_last_error": (C.c_char_p, []),
     }
     for name, (res, args) in sig.items():
@@ -432,6 +435,20 @@ def relaygr_trigger_stats(t: Trigger) -> dict:
     a, b, c, d = C.c_int64(), C.c_int64(), C.c_int64(), C.c_int64()
     load_library().relaygr_trigger_stats(t.handle, C.byref(a), C.byref(b), C.byref(c), C.byref(d))
     return {"live": a.value, "admitted": b.value, "refused": c.value, "not_at_risk": d.value}
+
+
+# ---- diagnostics -------------------------------------------------------------------------------
+def relaygr_probe_bytes() -> int:
+    return load_library().relaygr_probe_bytes()
+
+
+def relaygr_probe_mfma(random_data: bool, iters: int = 20000, device: str = "cuda:0", stream=None) -> dict:
+    """Sustained dense TFLOP/s and shader clock (GHz) of a pure MFMA loop."""
+    work = torch.empty(relaygr_probe_bytes(), dtype=torch.uint8, device=device)
+    tf, ghz = C.c_double(), C.c_double()
+    _check(load_library().relaygr_probe_mfma(work.data_ptr(), work.numel(), int(bool(random_data)), iters, _stream_ptr(stream),
+                                             C.byref(tf), C.byref(ghz)))
+    return {"tflops": tf.value, "shader_ghz": ghz.value}
 
 
 class Batch:

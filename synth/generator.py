@@ -155,6 +155,11 @@ WORKLOADS: Dict[str, Workload] = {
                    prefix_len=8192, n_cands=1000, n_suffix=0),
     "C5": Workload("C5", ModelConfig(8, 512, 8, "bf16"), seed=5, n_users=64,
                    prefix_len=None, n_cands=None, n_suffix=None, miss_tenths=3),
+    # the paper's extensibility axes (Section 5.4): embedding width up to 1024, depth 8 -> 16 layers
+    "X1": Workload("X1", ModelConfig(8, 1024, 8, "bf16"), seed=6, n_users=16,
+                   prefix_len=4096, n_cands=512, n_suffix=0),
+    "X2": Workload("X2", ModelConfig(16, 512, 8, "bf16"), seed=7, n_users=16,
+                   prefix_len=4096, n_cands=512, n_suffix=0),
 }
 
 

@@ -60,6 +60,16 @@ def test_c4_full_size_sampled_user_and_kv_footprint():
     assert rg.relaygr_kv_footprint_bytes(cfg, 8192) == 134217728     # per-user KV bytes of this workload
 
 
+def test_x1_width_1024():
+    """Section 5.4's width axis: d = 1024 (d_head = 128)."""
+    run_full("X1", sample_users=[3])
+
+
+def test_x2_depth_16_layers():
+    """Section 5.4's depth axis: 16 layers."""
+    run_full("X2", sample_users=[7])
+
+
 def test_c5_jagged_batch_with_uncached_users():
     wl = synth.WORKLOADS["C5"]
     L, S, M, cached = synth.make_lengths(wl, 0)
