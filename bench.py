@@ -101,6 +101,60 @@ def small_m_sweep(torch, rg, synth, n_users=128, L=8192, Ms=(16, 32, 64, 128), s
             "points": out}
 
 
+def single_request_breakdown(torch, rg, synth, cfg, weights, shapes=((4096, 512), (8192, 512), (8192, 2048), (15360, 512)), reps=15):
+    """The paper's per-request latency components (Section 5.2, pre / load / rank) for ONE user per call on the
+    benchmark model: prefix pre-inference, reload of psi from pinned host memory, ranking on the cached prefix,
+    and the baseline's full inference inline.  Median of `reps` calls each, HIP events on the call's stream."""
+    Lmax = max(L for L, _ in shapes)
+    Mmax = max(M for _, M in shapes)
+    ctx = rg.Context(cfg, weights, 1, Lmax, Mmax)
+    page = 256
+    pool = rg.KvPool(ctx.cfg, cfg.dtype, 2 * rg.relaygr_kv_pool_bytes_for(ctx.cfg, Lmax, page), page)
+    ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
+
+    def timed(fn):
+        ts = []
+        for i in range(reps + 2):
+            a, b = ev(), ev()
+            a.record(); fn(); b.record()
+            torch.cuda.synchronize()
+            if i >= 2:
+                ts.append(a.elapsed_time(b))
+        return round(percentile(ts, 50), 4)
+
+    out = []
+    for L, M in shapes:
+        wl = synth.Workload("one", cfg, seed=900 + L + M, n_users=1, prefix_len=L, n_cands=M, n_suffix=0)
+        b = synth.make_batch(wl, 0)
+        db = rg.Batch(b, cfg.dtype)
+        h = rg.relaygr_kv_pool_alloc(pool, int(b["user_ids"][0]), L)
+        db.set_handles([h])
+        scores = torch.empty(M, dtype=torch.float32, device="cuda:0")
+        pre = timed(lambda: rg.relaygr_prefill_prefix(ctx, pool, db))
+        rank = timed(lambda: rg.relaygr_rank_with_cache(ctx, pool, db, scores))
+        cached = scores.cpu().numpy().copy()
+        image = rg.relaygr_kv_pool_spill(pool, h)
+        torch.cuda.synchronize()
+        state = {"h": h}
+
+        def reload():
+            rg.relaygr_kv_pool_free(pool, state["h"])
+            state["h"] = rg.relaygr_kv_pool_reload(pool, int(b["user_ids"][0]), L, image)
+        load = timed(reload)
+        db.set_handles([state["h"]])
+        rg.relaygr_rank_with_cache(ctx, pool, db, scores)
+        torch.cuda.synchronize()
+        same = bool(np.array_equal(scores.cpu().numpy(), cached))
+        db.set_handles([0])
+        full = timed(lambda: rg.relaygr_rank_full_recompute(ctx, db, scores))
+        rg.relaygr_kv_pool_free(pool, state["h"])
+        out.append({"prefix": L, "candidates": M, "pre_ms": pre, "load_ms": load, "rank_ms": rank, "full_inference_ms": full,
+                    "psi_MB": round(rg.relaygr_kv_footprint_bytes(ctx.cfg, L) / 1e6, 1), "scores_identical_after_reload": same})
+    ctx.close()
+    pool.close()
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -115,6 +169,7 @@ def main() -> int:
                     help="also run one plain 1 GiB device copy, the known-size reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE")
     ap.add_argument("--no-concurrent", action="store_true", help="skip the rank-beside-prefill measurement on two streams")
     ap.add_argument("--no-dram", action="store_true", help="skip the spill / reload (DRAM tier) measurement")
+    ap.add_argument("--no-single", action="store_true", help="skip the one-user-per-call latency breakdown (pre / load / rank)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the small-M sweep of the attention kernel (its HBM-bound regime)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -371,12 +426,16 @@ def main() -> int:
 
     kv_bytes = {"min": int(rg.relaygr_kv_footprint_bytes(ctx.cfg, int(L.min()))),
                 "max": int(rg.relaygr_kv_footprint_bytes(ctx.cfg, int(L.max())))}
-    sweep = None
-    if not args.no_sweep and cfg.dtype == "bf16":
+    sweep = single = None
+    if not (args.no_sweep and args.no_single) and cfg.dtype == "bf16":
         ctx.close(); pool.close()
         del ctx, pool, db, pre
         torch.cuda.empty_cache()
-        sweep = small_m_sweep(torch, rg, synth)
+        if not args.no_single:
+            single = single_request_breakdown(torch, rg, synth, cfg, weights)
+            torch.cuda.empty_cache()
+        if not args.no_sweep:
+            sweep = small_m_sweep(torch, rg, synth)
 
     out = {
         "metric": "candidates scored/sec, ranking on the cached prefix (rank stage); p99 rank latency and full recompute beside it",
@@ -400,6 +459,7 @@ def main() -> int:
         "rank_beside_prefill": concurrent,
         "attention_small_m_sweep": sweep,
         "dram_tier": dram,
+        "single_request_latency": single,
         "cpu_baseline": cpu,
         "paper_context": "RelayGR on Ascend 910C NPUs: up to 1.5x longer sequences and 3.6x SLO-compliant throughput (system-level, not comparable)",
     }
