@@ -212,6 +212,10 @@ int  relaygr_rank_full_recompute(relaygr_ctx* ctx, const relaygr_batch* batch,
  * clears the accumulated figures.  While on, each launch of a selected class is bracketed by a
  * pair of HIP events recorded on the call's stream. */
 int  relaygr_ctx_profile_enable(relaygr_ctx* ctx, uint32_t class_mask);
+/* Times the launches of every n-th compute call only (default 1: every call), counting from this
+ * call on: an event pair costs a few microseconds on the stream, which a throughput measurement
+ * running beside the timing should not pay on every call. */
+int  relaygr_ctx_profile_sample(relaygr_ctx* ctx, int32_t every_n_calls);
 /* Waits for the recorded events and returns the summed kernel time (milliseconds) and the number
  * of launches of one class since the last enable.  Synchronises with the GPU. */
 int  relaygr_ctx_profile_read(relaygr_ctx* ctx, int32_t kernel_class, double* total_ms, int64_t* launches);

@@ -28,7 +28,7 @@ EXPORTS = [
     "relaygr_kv_pool_create", "relaygr_kv_pool_destroy", "relaygr_kv_pool_alloc", "relaygr_kv_pool_free",
     "relaygr_kv_pool_lookup", "relaygr_kv_pool_entry_len", "relaygr_kv_pool_stats", "relaygr_kv_pool_locate",
     "relaygr_prefill_prefix", "relaygr_rank_with_cache", "relaygr_rank_full_recompute",
-    "relaygr_ctx_profile_enable", "relaygr_ctx_profile_read",
+    "relaygr_ctx_profile_enable", "relaygr_ctx_profile_sample", "relaygr_ctx_profile_read",
     "relaygr_kv_pool_entry_bytes", "relaygr_kv_pool_spill", "relaygr_kv_pool_reload",
     "relaygr_expander_create", "relaygr_expander_destroy", "relaygr_expander_retire",
     "relaygr_expander_alloc", "relaygr_expander_trim", "relaygr_expander_lookup", "relaygr_expander_stats",
@@ -115,6 +115,7 @@ def load_library() -> C.CDLL:
         "relaygr_rank_with_cache": (C.c_int, [vp, vp, P(BatchC), vp, vp]),
         "relaygr_rank_full_recompute": (C.c_int, [vp, P(BatchC), vp, vp]),
         "relaygr_ctx_profile_enable": (C.c_int, [vp, C.c_uint32]),
+        "relaygr_ctx_profile_sample": (C.c_int, [vp, i32]),
         "relaygr_ctx_profile_read": (C.c_int, [vp, i32, P(C.c_double), P(i64)]),
         "relaygr_kv_pool_entry_bytes": (sz, [vp, u64]),
         "relaygr_kv_pool_spill": (C.c_int, [vp, u64, vp, sz, vp]),
@@ -234,6 +235,10 @@ def relaygr_ctx_profile_enable(ctx: Context, classes: Sequence[str]) -> None:
     for c in classes:
         mask |= 1 << KERNEL_CLASSES.index(c)
     _check(load_library().relaygr_ctx_profile_enable(ctx.handle, mask))
+
+
+def relaygr_ctx_profile_sample(ctx: Context, every_n_calls: int) -> None:
+    _check(load_library().relaygr_ctx_profile_sample(ctx.handle, every_n_calls))
 
 
 def relaygr_ctx_profile_read(ctx: Context, kernel_class: str):

@@ -174,6 +174,9 @@ struct ProfRec { int cls; hipEvent_t a, b; };
 
 struct relaygr_ctx {
   uint32_t prof_mask = 0;
+  int prof_every = 1;                   // time the launches of every n-th call only
+  int64_t prof_calls = 0;
+  bool prof_this_call = true;
   std::vector<ProfRec> prof_recs;       // recorded, not yet resolved
   std::vector<hipEvent_t> prof_free;    // events ready for reuse
   double prof_ms[RELAYGR_K_COUNT] = {};
@@ -263,7 +266,7 @@ static int staging_acquire(relaygr_ctx* c, size_t bytes, StagingSlot** out) {
 struct ProfScope {
   relaygr_ctx* c; int cls; hipStream_t st; hipEvent_t a = nullptr, b = nullptr;
   ProfScope(relaygr_ctx* c_, int cls_, hipStream_t st_) : c(c_), cls(cls_), st(st_) {
-    if (!(c->prof_mask & (1u << cls))) return;
+    if (!(c->prof_mask & (1u << cls)) || !c->prof_this_call) return;
     auto get = [&]() -> hipEvent_t {
       hipEvent_t e = nullptr;
       if (!c->prof_free.empty()) { e = c->prof_free.back(); c->prof_free.pop_back(); }
@@ -300,6 +303,13 @@ extern "C" int relaygr_ctx_profile_enable(relaygr_ctx* c, uint32_t class_mask) {
   if (rc != RELAYGR_OK) return rc;
   c->prof_mask = class_mask & ((1u << RELAYGR_K_COUNT) - 1);
   for (int k = 0; k < RELAYGR_K_COUNT; ++k) { c->prof_ms[k] = 0.0; c->prof_n[k] = 0; }
+  return RELAYGR_OK;
+}
+
+extern "C" int relaygr_ctx_profile_sample(relaygr_ctx* c, int32_t every_n_calls) {
+  if (!c || every_n_calls < 1) return fail(RELAYGR_EINVAL, "profile_sample: null context or every_n_calls < 1");
+  c->prof_every = every_n_calls;
+  c->prof_calls = 0;
   return RELAYGR_OK;
 }
 
@@ -753,9 +763,12 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
         if (fuse_ln) {
           F2LnParams fp;
           fp.W = c->w2_packed[l]; fp.bias = (const uint16_t*)lw.b2; fp.x = x; fp.rt = rt;
+          // the last layer of a ranking call ends in the score head instead of the next layer's LayerNorm
+          const bool score_here = last && mode != kPrefill && scores != nullptr;
           fp.xh = last ? nullptr : (uint16_t*)xh;
-          fp.gain = last ? nullptr : (const uint16_t*)c->layers[l + 1].ln_in_g;
-          fp.offs = last ? nullptr : (const uint16_t*)c->layers[l + 1].ln_in_b;
+          fp.gain = last ? (const uint16_t*)c->ln_out_g : (const uint16_t*)c->layers[l + 1].ln_in_g;
+          fp.offs = last ? (const uint16_t*)c->ln_out_b : (const uint16_t*)c->layers[l + 1].ln_in_b;
+          fp.w_score = (const uint16_t*)c->w_score; fp.b_score = c->b_score; fp.scores = score_here ? scores : nullptr;
           fp.row_begin = a0; fp.row_end = R; fp.eps = cfg.ln_eps;
           fp.part = part; fp.nsplit = p.nsplit; fp.split_stride = (size_t)R * d;
           fp.u = (const uint16_t*)ubuf; fp.q = (const uint16_t*)qbuf; fp.knew = (const uint16_t*)knew; fp.vnew = (const uint16_t*)vnew;
@@ -793,7 +806,7 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
     LAUNCH_CHECK("f2");
   }
 
-  if (mode != kPrefill && p.n_nrows) {
+  if (mode != kPrefill && p.n_nrows && !fuse_ln) {   // the fused bf16 tail kernel has written the scores already
     ProfScope ps(c, RELAYGR_K_SCORE, st);
     dim3 grid((p.n_nrows + kRowsPerBlock - 1) / kRowsPerBlock);
     dispatch_e(d, [&](auto e) {
@@ -810,6 +823,7 @@ static int run(relaygr_ctx* c, relaygr_kv_pool* pool, const relaygr_batch* b, Mo
   if (!c || !b) return fail(RELAYGR_EINVAL, "null context or batch");
   if (b->n_users < 0) return fail(RELAYGR_EINVAL, "n_users < 0");
   if (b->n_users == 0) return RELAYGR_OK;
+  c->prof_this_call = (c->prof_calls++ % c->prof_every) == 0;
   int rc;
   if ((rc = check_offsets(b->prefix_off, b->n_users, "prefix")) != RELAYGR_OK) return rc;
   if ((rc = check_offsets(b->suffix_off, b->n_users, "suffix")) != RELAYGR_OK) return rc;

@@ -383,6 +383,11 @@ struct F2LnParams {
   RowTables rt;
   int row_begin, row_end;   // row_begin is a multiple of 32
   float eps;
+  // last layer of a ranking call: instead of xh, score_c = <w_score, LN(x; gain, offs)> + b_score for
+  // candidate rows, written at the candidate's position in the caller's order (scores != nullptr)
+  const uint16_t* w_score;
+  float b_score;
+  float* scores;
 };
 
 
@@ -618,6 +623,7 @@ __global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
   }
 
   // the new residual rows go back; their sums start the LayerNorm statistics
+  const bool want_score = p.scores != nullptr;
   float s1[RB];
 #pragma unroll
   for (int b = 0; b < RB; ++b) {
@@ -629,11 +635,11 @@ __global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
       for (int e4 = 0; e4 < 4; ++e4) {
         const int c = (wave * FB + j) * 32 + 8 * e4 + 4 * g;
         const float4 v = make_float4(acc[b][j][4 * e4], acc[b][j][4 * e4 + 1], acc[b][j][4 * e4 + 2], acc[b][j][4 * e4 + 3]);
-        if (live[b]) *reinterpret_cast<float4*>(xrow[b] + c) = v;
+        if (live[b] && !want_score) *reinterpret_cast<float4*>(xrow[b] + c) = v;   // nothing reads x after the score head
         s1[b] += (v.x + v.y) + (v.z + v.w);
       }
   }
-  if (p.xh == nullptr) return;          // uniform over the grid
+  if (p.xh == nullptr && !want_score) return;          // uniform over the grid
 
   // LayerNorm of the new residual rows: two passes over the registers, sums exchanged through LDS
   __syncthreads();                      // every wavefront is done reading tok
@@ -659,12 +665,30 @@ __global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
     if (g == 0) red[(NW + wave) * ROWS + 32 * b + l32] = s2[b];
   }
   __syncthreads();
+  float score_part[RB];
 #pragma unroll
   for (int b = 0; b < RB; ++b) {
     float var = 0.f;
 #pragma unroll
     for (int w = 0; w < NW; ++w) var += red[(NW + w) * ROWS + 32 * b + l32];
     const float rstd = rsqrtf(var * (1.0f / (float)D) + p.eps);
+    if (want_score) {       // uniform over the grid: the score head's dot product, reduced like the statistics below
+      float sc = 0.f;
+#pragma unroll
+      for (int j = 0; j < FB; ++j)
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+          const int c = (wave * FB + j) * 32 + 8 * e4 + 4 * g;
+          const uint2 gg = *reinterpret_cast<const uint2*>(p.gain + c), oo = *reinterpret_cast<const uint2*>(p.offs + c);
+          const uint2 ww = *reinterpret_cast<const uint2*>(p.w_score + c);
+          sc += ((acc[b][j][4 * e4] - mean[b]) * rstd * bf16_bits_to_float(gg.x & 0xFFFF) + bf16_bits_to_float(oo.x & 0xFFFF)) * bf16_bits_to_float(ww.x & 0xFFFF);
+          sc += ((acc[b][j][4 * e4 + 1] - mean[b]) * rstd * bf16_bits_to_float(gg.x >> 16) + bf16_bits_to_float(oo.x >> 16)) * bf16_bits_to_float(ww.x >> 16);
+          sc += ((acc[b][j][4 * e4 + 2] - mean[b]) * rstd * bf16_bits_to_float(gg.y & 0xFFFF) + bf16_bits_to_float(oo.y & 0xFFFF)) * bf16_bits_to_float(ww.y & 0xFFFF);
+          sc += ((acc[b][j][4 * e4 + 3] - mean[b]) * rstd * bf16_bits_to_float(gg.y >> 16) + bf16_bits_to_float(oo.y >> 16)) * bf16_bits_to_float(ww.y >> 16);
+        }
+      score_part[b] = sc + __shfl_xor(sc, 32, 64);
+      continue;
+    }
     if (!in_range[b]) continue;
     const int row = row0 + 32 * b + l32;
 #pragma unroll
@@ -684,6 +708,23 @@ __global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
         out.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2_t));
         *reinterpret_cast<uint2*>(p.xh + panel_off(row, c, D)) = out;
       }
+  }
+  if (want_score) {
+    __syncthreads();                    // the variance sums have been read
+#pragma unroll
+    for (int b = 0; b < RB; ++b)
+      if (g == 0) red[wave * ROWS + 32 * b + l32] = score_part[b];
+    __syncthreads();
+    if (wave == 0 && g == 0) {
+#pragma unroll
+      for (int b = 0; b < RB; ++b) {
+        float total = p.b_score;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) total += red[w * ROWS + 32 * b + l32];
+        const int row = row0 + 32 * b + l32;
+        if (in_range[b] && kind_ep[b] == kRowCand) p.scores[p.rt.src[row]] = total;
+      }
+    }
   }
 }
 
