@@ -132,7 +132,7 @@ static void carve(const relaygr_model_config& c, Plan& p) {
 static int wanted_splits(int n_tiles, int n_heads, int min_key_tiles) {
   if (n_tiles <= 0) return 1;
   int wgs = n_tiles * n_heads;
-  int s = (256 + wgs - 1) / wgs;
+  int s = (512 + wgs - 1) / wgs;
   s = std::min(s, 8);
   s = std::min(s, std::max(1, min_key_tiles));
   return std::max(s, 1);
