@@ -30,8 +30,8 @@ PEAK_FP32_TFLOPS = 157.3     # fp32 vector
 PEAK_HBM_GBPS = 8000.0
 
 # HBM bytes per attention launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs), scaled by
-# what the same counters read for a plain 1 GiB copy (x2.0 and x1.0); profiles/rank_with_cache_C3_kernels.md.
-MEASURED_ATTN_TRAFFIC_BYTES = {"C3": (69841 * 2 + 16384) * 1024}
+# what the same counters read for a plain 1 GiB copy (x2.0 and x1.0); profiles/bench_C3_kernels.md.
+MEASURED_ATTN_TRAFFIC_BYTES = {"C3": (73939 * 2 + 32770) * 1024}
 
 WORKLOAD_TEXT = {
     "C1": "C1: fp32, 2 layers, d=64, 2 heads; 1 user, prefix 256, 16 candidates",
@@ -158,11 +158,11 @@ def single_request_breakdown(torch, rg, synth, cfg, weights, shapes=((4096, 512)
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="C3", choices=sorted(WORKLOAD_TEXT))
-    ap.add_argument("--full-steps", type=int, default=10, help="timed full-recompute calls")
-    ap.add_argument("--prefill-steps", type=int, default=5, help="timed prefill calls")
+    ap.add_argument("--full-steps", type=int, default=None, help="timed full-recompute calls (default 100; 20 for C4, C5, X1, X2)")
+    ap.add_argument("--prefill-steps", type=int, default=10, help="timed prefill calls")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-all", action="store_true", help="time every kernel class, not only attention")
     ap.add_argument("--calib-copy", action="store_true",
@@ -172,6 +172,8 @@ def main() -> int:
     ap.add_argument("--no-single", action="store_true", help="skip the one-user-per-call latency breakdown (pre / load / rank)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the small-M sweep of the attention kernel (its HBM-bound regime)")
     args = ap.parse_args()
+    if args.full_steps is None:
+        args.full_steps = 100 if args.config in ("C1", "C2", "C3") else 20
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (users shard by hash across GPUs with no "
               "collective; see DESIGN.md); run with --gpus 1", file=sys.stderr)
