@@ -169,9 +169,13 @@ def main() -> int:
                     help="also run one plain 1 GiB device copy, the known-size reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE")
     ap.add_argument("--no-concurrent", action="store_true", help="skip the rank-beside-prefill measurement on two streams")
     ap.add_argument("--no-dram", action="store_true", help="skip the spill / reload (DRAM tier) measurement")
+    ap.add_argument("--batches", type=int, default=None,
+                    help="distinct seeded batches the timed rank calls cycle through (default 8 for the jagged C5, else 1)")
     ap.add_argument("--no-single", action="store_true", help="skip the one-user-per-call latency breakdown (pre / load / rank)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the small-M sweep of the attention kernel (its HBM-bound regime)")
     args = ap.parse_args()
+    if args.batches is None:
+        args.batches = 8 if args.config == "C5" else 1
     if args.full_steps is None:
         args.full_steps = 100 if args.config in ("C1", "C2", "C3") else 20
     if args.gpus != 1:
@@ -208,9 +212,22 @@ def main() -> int:
     print(f"[bench] {args.config}: inputs generated in {time.time() - t0:.1f}s "
           f"(users {n}, prefix tokens {sumL}, suffix {sumS}, candidates {sumM})", file=sys.stderr, flush=True)
 
-    ctx = rg.Context(cfg, weights, n, sumL, sumS + sumM)
+    # further batches of the same workload (other seeds): only the timed rank calls cycle through them, so that the
+    # latency percentiles of a jagged workload see its shape variance; everything else is measured on batch 0
+    extra = []
+    for bi in range(1, args.batches):
+        t1 = time.time()
+        eb = synth.make_batch(wl, bi)
+        eL, eS, eM, ecached = synth.make_lengths(wl, bi)
+        extra.append({"batch": eb, "L": eL, "S": eS, "M": eM, "cached": ecached})
+        print(f"[bench] {args.config}: batch {bi} generated in {time.time() - t1:.1f}s (prefix tokens {int(eL.sum())}, "
+              f"candidates {int(eM.sum())})", file=sys.stderr, flush=True)
+    max_L = max([sumL] + [int(e["L"].sum()) for e in extra])
+    max_new = max([sumS + sumM] + [int(e["S"].sum() + e["M"].sum()) for e in extra])
+    ctx = rg.Context(cfg, weights, n, max_L, max_new)
     page_tokens = 256
     pool_bytes = sum(rg.relaygr_kv_pool_bytes_for(ctx.cfg, int(l), page_tokens) for l in L)
+    pool_bytes += sum(rg.relaygr_kv_pool_bytes_for(ctx.cfg, int(l), page_tokens) for e in extra for l in e["L"])
     pool = rg.KvPool(ctx.cfg, cfg.dtype, pool_bytes, page_tokens)
     db = rg.Batch(batch, cfg.dtype)
 
@@ -219,10 +236,12 @@ def main() -> int:
     handles = np.zeros(n, dtype=np.uint64)
     for u in hit:
         handles[u] = rg.relaygr_kv_pool_alloc(pool, int(batch["user_ids"][u]), int(L[u]))
+    handles_of_batch0 = handles
     from synth.generator import user_slices
 
-    def sub_batch(users):
+    def sub_batch(users, batch=batch, handles=None):
         d = cfg.d_model
+        handles = handles_of_batch0 if handles is None else handles
         segs = [user_slices(batch, u) for u in users]
 
         def off(k):
@@ -252,7 +271,17 @@ def main() -> int:
         prefill_kernels = {c: round(rg.relaygr_ctx_profile_read(ctx, c)[0], 4) for c in rg.binding.KERNEL_CLASSES}
         rg.relaygr_ctx_profile_enable(ctx, [])
     db.set_handles(handles)
-    scores = torch.empty(sumM, dtype=torch.float32, device="cuda:0")
+    cycle = [(db, sumM)]
+    for e in extra:
+        eh = np.zeros(n, dtype=np.uint64)
+        ehit = [u for u in range(n) if e["cached"][u] and e["L"][u] > 0]
+        for u in ehit:
+            eh[u] = rg.relaygr_kv_pool_alloc(pool, int(e["batch"]["user_ids"][u]), int(e["L"][u]))
+        rg.relaygr_prefill_prefix(ctx, pool, sub_batch(ehit, e["batch"], eh))
+        torch.cuda.synchronize()
+        e["handles"] = eh
+        cycle.append((rg.Batch(e["batch"], cfg.dtype, handles=eh), int(e["M"].sum())))
+    scores = torch.empty(max(m for _, m in cycle), dtype=torch.float32, device="cuda:0")
 
     # ---- the timed region: K rank calls on the cached prefix.  The interpreter's cyclic collector is parked first: a
     # full collection over the input generator's heap otherwise lands inside one call (about 30 ms once per few
@@ -260,8 +289,8 @@ def main() -> int:
     import gc
     gc.collect()
     gc.freeze()
-    for _ in range(args.warmup):
-        rg.relaygr_rank_with_cache(ctx, pool, db, scores)
+    for i in range(args.warmup):
+        rg.relaygr_rank_with_cache(ctx, pool, cycle[i % len(cycle)][0], scores)
     torch.cuda.synchronize()
     classes = rg.binding.KERNEL_CLASSES if args.profile_all else ["attn"]
     rg.relaygr_ctx_profile_enable(ctx, classes)
@@ -270,20 +299,24 @@ def main() -> int:
     evs = [(ev(), ev()) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t_start = time.perf_counter()
-    for a, b in evs:
+    for i, (a, b) in enumerate(evs):
         a.record()
-        rg.relaygr_rank_with_cache(ctx, pool, db, scores)
+        rg.relaygr_rank_with_cache(ctx, pool, cycle[i % len(cycle)][0], scores)
         b.record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
+    cands_scored = sum(cycle[i % len(cycle)][1] for i in range(args.steps))
     lat = [a.elapsed_time(b) for a, b in evs]
     kernel_ms = {c: rg.relaygr_ctx_profile_read(ctx, c) for c in classes}
     rg.relaygr_ctx_profile_enable(ctx, [])
     rg.relaygr_ctx_profile_sample(ctx, 1)
     timed_calls = (args.steps + 3) // 4 if not args.profile_all else args.steps
     ms_per_step = elapsed * 1e3 / args.steps
-    value = sumM * args.steps / elapsed
-    cached_scores = scores.cpu().numpy().copy()
+    value = cands_scored / elapsed
+    if len(cycle) > 1:      # the comparisons below are on batch 0
+        rg.relaygr_rank_with_cache(ctx, pool, db, scores)
+        torch.cuda.synchronize()
+    cached_scores = scores[:sumM].cpu().numpy().copy()
 
     # ---- the baseline in the same run: full inference inline
     full_ms = []
@@ -301,7 +334,7 @@ def main() -> int:
         rg.relaygr_rank_full_recompute(ctx, db, scores)
         full_kernels = {c: round(rg.relaygr_ctx_profile_read(ctx, c)[0], 4) for c in rg.binding.KERNEL_CLASSES}
         rg.relaygr_ctx_profile_enable(ctx, [])
-    full_scores = scores.cpu().numpy()
+    full_scores = scores[:sumM].cpu().numpy()
     full_mean = float(np.mean(full_ms)) if full_ms else None
     max_diff = float(np.abs(full_scores - cached_scores).max()) if (sumM and full_ms) else None
 
@@ -336,7 +369,7 @@ def main() -> int:
         wall2 = time.perf_counter() - t2
         lat2 = [a.elapsed_time(b) for a, b in evs2]
         pre_lat = [a.elapsed_time(b) for a, b in pe]
-        same = bool(np.array_equal(scores.cpu().numpy(), cached_scores))
+        same = bool(np.array_equal(scores[:sumM].cpu().numpy(), cached_scores))
         concurrent = {"rank_calls": n_conc, "prefill_calls": len(pe),
                       "rank_latency_ms": {"p50": round(percentile(lat2, 50), 4), "p99": round(percentile(lat2, 99), 4)},
                       "prefill_latency_ms": {"p50": round(percentile(pre_lat, 50), 4), "max": round(max(pre_lat), 4)},
@@ -378,22 +411,30 @@ def main() -> int:
         dram = {"user_prefix_tokens": int(L[u]), "image_bytes": int(nbytes),
                 "spill_ms": round(float(np.mean(spill_ms)), 4), "load_ms": round(float(np.mean(load_ms)), 4),
                 "load_GBps": round(nbytes / (float(np.mean(load_ms)) * 1e-3) / 1e9, 1),
-                "scores_identical_after_reload": bool(np.array_equal(scores.cpu().numpy(), cached_scores))}
+                "scores_identical_after_reload": bool(np.array_equal(scores[:sumM].cpu().numpy(), cached_scores))}
 
     # ---- roofline of the dominant kernel (attention over the cached prefix + suffix)
     d = cfg.d_model
     e = cfg.elem_bytes
     # keys each new row visits: candidates see L+S, suffix row t sees L+t+1
-    key_visits = sum(int(M[u]) * int(L[u] + S[u]) + sum(int(L[u]) + t + 1 for t in range(int(S[u]))) for u in range(n))
-    flops_per_launch = 4.0 * d * key_visits
+    def attn_flops_per_layer(L, S, M, handles):
+        """FLOP of the attention launches of one rank call on a batch: 4 d per (row, visible key), candidates see L+S
+        keys, suffix row t sees L+t+1; layers but the last also carry the uncached users' causal prefix pass."""
+        key_visits = sum(int(M[u]) * int(L[u] + S[u]) + sum(int(L[u]) + t + 1 for t in range(int(S[u]))) for u in range(n))
+        causal_visits = sum(int(L[u]) * (int(L[u]) + 1) // 2 for u in range(n) if not handles[u])
+        new_rows = 4.0 * d * key_visits
+        return [new_rows + 4.0 * d * causal_visits] * (cfg.n_layers - 1) + [new_rows]
+
+    per_batch = [attn_flops_per_layer(L, S, M, handles)] + [attn_flops_per_layer(e["L"], e["S"], e["M"], e["handles"]) for e in extra]
+    flops_per_launch = per_batch[0][-1]
     miss_L = sum(int(L[u]) for u in range(n) if not handles[u])
     attn_ms, attn_n = kernel_ms["attn"]
     roof = None
     if attn_n:
-        # launches that also carry the uncached users' causal prefix pass are averaged in
-        causal_visits = sum(int(L[u]) * (int(L[u]) + 1) // 2 for u in range(n) if not handles[u])
-        per_layer = [flops_per_launch + 4.0 * d * causal_visits] * (cfg.n_layers - 1) + [flops_per_launch]
-        avg_flops = float(np.mean(per_layer))
+        # the launches timed live are those of every 4th call (every call with --profile-all); call i ran batch i mod N
+        stride = 1 if args.profile_all else 4
+        timed_layers = [f for i in range(0, args.steps, stride) for f in per_batch[i % len(per_batch)]]
+        avg_flops = float(np.mean(timed_layers))
         avg_ms = attn_ms / attn_n
         peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_FP32_TFLOPS
         achieved = avg_flops / (avg_ms * 1e-3) / 1e12
@@ -454,7 +495,8 @@ def main() -> int:
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": WORKLOAD_TEXT[args.config], "users": n, "prefix_tokens": sumL, "suffix_tokens": sumS,
-                   "candidates": sumM, "uncached_users": int(n - len(hit)), "page_tokens": page_tokens},
+                   "candidates": sumM, "uncached_users": int(n - len(hit)), "page_tokens": page_tokens,
+                   "batches_cycled": args.batches},
         "rank_latency_ms": {"p50": round(percentile(lat, 50), 4), "p99": round(percentile(lat, 99), 4),
                             "mean": round(float(np.mean(lat)), 4)},
         "full_recompute": {"ms": round(full_mean, 4) if full_mean else None,
