@@ -41,6 +41,7 @@ WORKLOAD_TEXT = {
     "C5": "C5: bf16, 8 layers, d=512, 8 heads; 64 users, prefix lognormal in [512,16384], 200-2000 candidates, suffix 0-64, ~30% uncached",
     "X1": "X1 (width axis): bf16, 8 layers, d=1024, 8 heads; 16 users x (prefix 4096, 512 candidates)",
     "X2": "X2 (depth axis): bf16, 16 layers, d=512, 8 heads; 16 users x (prefix 4096, 512 candidates)",
+    "X3": "X3 (half precision): fp16, 8 layers, d=512, 8 heads; 16 users x (prefix 4096, 512 candidates)",
 }
 
 
@@ -177,7 +178,7 @@ def main() -> int:
     if args.batches is None:
         args.batches = 8 if args.config == "C5" else 1
     if args.full_steps is None:
-        args.full_steps = 100 if args.config in ("C1", "C2", "C3") else 20
+        args.full_steps = 100 if args.config in ("C1", "C2", "C3", "X3") else 20
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (users shard by hash across GPUs with no "
               "collective; see DESIGN.md); run with --gpus 1", file=sys.stderr)
@@ -203,6 +204,7 @@ def main() -> int:
 
     wl = synth.WORKLOADS[args.config]
     cfg = wl.model
+    half16 = cfg.dtype in ("bf16", "fp16")     # the MFMA path
     t0 = time.time()
     weights = synth.make_weights(cfg, wl.seed)
     batch = synth.make_batch(wl, 0)
@@ -342,7 +344,7 @@ def main() -> int:
     # users runs beside ranking on the same accelerator.  A second context and pool pre-infer the same prefixes on a
     # second stream of default priority while the first keeps ranking; what is reported is the rank latency under that load.
     concurrent = None
-    if not args.no_concurrent and hit and cfg.dtype == "bf16":
+    if not args.no_concurrent and hit and half16:
         ctx2 = rg.Context(cfg, weights, n, sumL, 0)
         pool2 = rg.KvPool(ctx2.cfg, cfg.dtype, pool_bytes, page_tokens)
         h2 = [rg.relaygr_kv_pool_alloc(pool2, int(batch["user_ids"][u]), int(L[u])) for u in hit]
@@ -436,12 +438,12 @@ def main() -> int:
         timed_layers = [f for i in range(0, args.steps, stride) for f in per_batch[i % len(per_batch)]]
         avg_flops = float(np.mean(timed_layers))
         avg_ms = attn_ms / attn_n
-        peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_FP32_TFLOPS
+        peak = PEAK_BF16_TFLOPS if half16 else PEAK_FP32_TFLOPS   # fp16 and bf16 share the dense MFMA peak
         achieved = avg_flops / (avg_ms * 1e-3) / 1e12
         kv_bytes = 2.0 * (sumL + sumS) * d * e + (sumS + sumM) * d * (e + 4)   # K,V once; q in; fp32 partial out
         roof = {
-            "kernel": "attn_bf16_kernel" if cfg.dtype == "bf16" else "attn_f32_kernel",
-            "bound": "mfma" if cfg.dtype == "bf16" else "alu",
+            "kernel": "attn_bf16_kernel" if half16 else "attn_f32_kernel",
+            "bound": "mfma" if half16 else "alu",
             "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
             "traffic": MEASURED_ATTN_TRAFFIC_BYTES.get(args.config),
             "avg_launch_ms": round(avg_ms, 4), "launches": attn_n,
@@ -453,7 +455,7 @@ def main() -> int:
 
     # ---- what the chip sustains on this MFMA in a pure MFMA loop (its power limit lowers the clock as operand bits
     # toggle): context for the fraction of the published peak above
-    if roof is not None and cfg.dtype == "bf16":
+    if roof is not None and half16:
         torch.cuda.synchronize()
         pc, pr = rg.relaygr_probe_mfma(False), rg.relaygr_probe_mfma(True)
         roof["mfma_loop_sustained"] = {"constant_operands_TFLOPs": round(pc["tflops"], 1), "constant_operands_GHz": round(pc["shader_ghz"], 3),
@@ -479,7 +481,7 @@ def main() -> int:
     kv_bytes = {"min": int(rg.relaygr_kv_footprint_bytes(ctx.cfg, int(L.min()))),
                 "max": int(rg.relaygr_kv_footprint_bytes(ctx.cfg, int(L.max())))}
     sweep = single = None
-    if not (args.no_sweep and args.no_single) and cfg.dtype == "bf16":
+    if not (args.no_sweep and args.no_single) and half16:
         ctx.close(); pool.close()
         del ctx, pool, db, pre
         torch.cuda.empty_cache()

@@ -40,13 +40,15 @@
  *   - Every function returning int returns RELAYGR_OK or a negative code; the
  *     text of the last failure on the calling thread is relaygr_last_error().
  *   - dtype selects storage AND arithmetic: RELAYGR_DTYPE_FP32 keeps everything
- *     in fp32; RELAYGR_DTYPE_BF16 stores weights, embeddings, activations and
- *     cached K/V as bfloat16 and accumulates, normalises and keeps the residual
- *     stream in fp32.  Scores are always fp32.
+ *     in fp32; RELAYGR_DTYPE_BF16 and RELAYGR_DTYPE_FP16 store weights, embeddings,
+ *     activations and cached K/V as bfloat16 / IEEE half and accumulate, normalise and
+ *     keep the residual stream in fp32 (fp16 is the half precision the paper mentions,
+ *     Section 5.2; values beyond its range of 65504 are the caller's concern).  Scores
+ *     are always fp32.
  *   - Constraints checked at context creation: d_model in {64, 128, 256, 512, 1024}
- *     (bf16: at least 128); d_head = d_model / n_heads in {32, 64, 128} and at least
+ *     (bf16, fp16: at least 128); d_head = d_model / n_heads in {32, 64, 128} and at least
  *     d_model / 64.
- *   - In the bf16 mode the first bytes of the scratch buffer hold the weights re-packed
+ *   - In the 16-bit modes the first bytes of the scratch buffer hold the weights re-packed
  *     for the matrix cores (done once in relaygr_ctx_create, which synchronises the
  *     device); relaygr_scratch_bytes includes them.
  */
@@ -68,6 +70,7 @@ extern "C" {
 
 #define RELAYGR_DTYPE_FP32 0
 #define RELAYGR_DTYPE_BF16 1
+#define RELAYGR_DTYPE_FP16 2
 
 #define RELAYGR_TILE_TOKENS 64   /* cached K/V are laid out in tiles of 64 tokens */
 

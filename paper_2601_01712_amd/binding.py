@@ -18,7 +18,7 @@ from . import build as _build
 
 RELAYGR_OK, RELAYGR_EINVAL, RELAYGR_ENOSPC, RELAYGR_ENOENT, RELAYGR_EHIP, RELAYGR_EBUSY = 0, -1, -2, -3, -4, -5
 RELAYGR_TRIGGER_NOT_AT_RISK, RELAYGR_TRIGGER_ADMIT, RELAYGR_TRIGGER_REFUSED = 0, 1, 2
-RELAYGR_DTYPE_FP32, RELAYGR_DTYPE_BF16 = 0, 1
+RELAYGR_DTYPE_FP32, RELAYGR_DTYPE_BF16, RELAYGR_DTYPE_FP16 = 0, 1, 2
 RELAYGR_NO_CACHE = 0
 RELAYGR_TILE_TOKENS = 64
 
@@ -156,11 +156,11 @@ def relaygr_last_error() -> str:
 
 
 def _dtype_code(dtype: str) -> int:
-    return {"fp32": RELAYGR_DTYPE_FP32, "bf16": RELAYGR_DTYPE_BF16}[dtype]
+    return {"fp32": RELAYGR_DTYPE_FP32, "bf16": RELAYGR_DTYPE_BF16, "fp16": RELAYGR_DTYPE_FP16}[dtype]
 
 
 def _torch_dtype(dtype: str):
-    return {"fp32": torch.float32, "bf16": torch.bfloat16}[dtype]
+    return {"fp32": torch.float32, "bf16": torch.bfloat16, "fp16": torch.float16}[dtype]
 
 
 def make_config(n_layers: int, d_model: int, n_heads: int, dtype: str, ln_eps: float = 1e-5) -> ModelConfigC:

@@ -129,8 +129,8 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(AttnParams p) {
 // (quarter-rate) plus add, multiply and half a packed bf16 convert per score element, against
 // 2*DH/32 MFMA passes per 32 x 32 block.
 
-template <int DH, int NQ>
-__device__ __forceinline__ void attn_s_half(const uint16_t* __restrict__ khalf, const bf16x8_t (&qf)[NQ][DH / 16],
+template <typename H, int DH, int NQ>
+__device__ __forceinline__ void attn_s_half(const uint16_t* __restrict__ khalf, const uint4 (&qf)[NQ][DH / 16],
                                             f32x16_t (&s)[NQ]) {
   constexpr int KS = DH / 16;
 #pragma unroll
@@ -139,13 +139,13 @@ __device__ __forceinline__ void attn_s_half(const uint16_t* __restrict__ khalf, 
     for (int e = 0; e < 16; ++e) s[qb][e] = 0.f;
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) {
-    bf16x8_t kf = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(khalf + ks * 512));
+    const uint4 kf = *reinterpret_cast<const uint4*>(khalf + ks * 512);
 #pragma unroll
-    for (int qb = 0; qb < NQ; ++qb) s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], s[qb], 0, 0, 0);
+    for (int qb = 0; qb < NQ; ++qb) s[qb] = H::mfma(kf, qf[qb][ks], s[qb]);
   }
 }
 
-template <int DH, int NQ>
+template <typename H, int DH, int NQ>
 __device__ __forceinline__ void attn_pv_half(const uint16_t* __restrict__ vhalf, const uint32_t (&pk)[NQ][8],
                                              f32x16_t (&oacc)[DH / 32][NQ]) {
   constexpr int DB = DH / 32;
@@ -153,11 +153,11 @@ __device__ __forceinline__ void attn_pv_half(const uint16_t* __restrict__ vhalf,
   for (int m = 0; m < 2; ++m) {
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
-      bf16x8_t vf = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(vhalf + (db * 4 + m) * 512));
+      const uint4 vf = *reinterpret_cast<const uint4*>(vhalf + (db * 4 + m) * 512);
 #pragma unroll
       for (int qb = 0; qb < NQ; ++qb) {
         uint4 pp = make_uint4(pk[qb][4 * m], pk[qb][4 * m + 1], pk[qb][4 * m + 2], pk[qb][4 * m + 3]);
-        oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, __builtin_bit_cast(bf16x8_t, pp), oacc[db][qb], 0, 0, 0);
+        oacc[db][qb] = H::mfma(vf, pp, oacc[db][qb]);
       }
     }
   }
@@ -170,22 +170,22 @@ __device__ __forceinline__ void attn_pv_half(const uint16_t* __restrict__ vhalf,
 // previous one, so MFMAs placed back to back would leave the vector ALU idle behind them.  The
 // step is therefore cut into slots -- the SiLU of 128/DH score elements per row block, then NQ
 // MFMAs that take about as long -- and the scheduler is fenced between slots.
-template <int DH, int NQ, bool MASKED>
+template <typename H, int DH, int NQ, bool MASKED>
 __device__ __forceinline__ void attn_step(const uint16_t* __restrict__ khalf, const uint16_t* __restrict__ vhalf,
-                                          const bf16x8_t (&qf)[NQ][DH / 16], const f32x16_t (&s_in)[NQ], f32x16_t (&s_out)[NQ],
+                                          const uint4 (&qf)[NQ][DH / 16], const f32x16_t (&s_in)[NQ], f32x16_t (&s_out)[NQ],
                                           const uint32_t (&pk_in)[NQ][8], uint32_t (&pk_out)[NQ][8],
                                           f32x16_t (&oacc)[DH / 32][NQ], const int (&vis)[NQ]) {
   constexpr int KS = DH / 16, DB = DH / 32;
   constexpr int SLOTS = KS + 2 * DB;      // = DH / 8
   constexpr int EPS = 16 / SLOTS > 0 ? 16 / SLOTS : 1;   // score elements per row block and slot
   static_assert(SLOTS * EPS == 16 || (SLOTS == 16 && EPS == 1), "slot split");
-  bf16x8_t kf[KS], vf[2][DB];
+  uint4 kf[KS], vf[2][DB];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) kf[ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(khalf + ks * 512));
+  for (int ks = 0; ks < KS; ++ks) kf[ks] = *reinterpret_cast<const uint4*>(khalf + ks * 512);
 #pragma unroll
   for (int m = 0; m < 2; ++m)
 #pragma unroll
-    for (int db = 0; db < DB; ++db) vf[m][db] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(vhalf + (db * 4 + m) * 512));
+    for (int db = 0; db < DB; ++db) vf[m][db] = *reinterpret_cast<const uint4*>(vhalf + (db * 4 + m) * 512);
   float pv[NQ][16];
   const f32x16_t zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -202,7 +202,7 @@ __device__ __forceinline__ void attn_step(const uint16_t* __restrict__ khalf, co
         pv[qb][e] = pe;
         if (e & 1) {
           f32x2_t two = {pv[qb][e - 1], pv[qb][e]};
-          pk_out[qb][e >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2_t));   // one v_cvt_pk_bf16_f32
+          pk_out[qb][e >> 1] = H::pack2(two[0], two[1]);   // one packed convert
         }
       }
     }
@@ -212,20 +212,20 @@ __device__ __forceinline__ void attn_step(const uint16_t* __restrict__ khalf, co
     if (slot % 2 == 0) {
 #pragma unroll
       for (int qb = 0; qb < NQ; ++qb)
-        s_out[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[si], qf[qb][si], si == 0 ? zero : s_out[qb], 0, 0, 0);
+        s_out[qb] = H::mfma(kf[si], qf[qb][si], si == 0 ? zero : s_out[qb]);
     } else {
       const int m = si / DB, db = si % DB;
 #pragma unroll
       for (int qb = 0; qb < NQ; ++qb) {
         uint4 pp = make_uint4(pk_in[qb][4 * m], pk_in[qb][4 * m + 1], pk_in[qb][4 * m + 2], pk_in[qb][4 * m + 3]);
-        oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[m][db], __builtin_bit_cast(bf16x8_t, pp), oacc[db][qb], 0, 0, 0);
+        oacc[db][qb] = H::mfma(vf[m][db], pp, oacc[db][qb]);
       }
     }
     __builtin_amdgcn_sched_barrier(0);
   }
 }
 
-template <int DH, int NQ, int NW>
+template <typename H, int DH, int NQ, int NW>
 __global__ __launch_bounds__(NW * 64, 512 / (NW * 64)) void attn_bf16_kernel(AttnParams p) {
   constexpr int KS = DH / 16;              // k-steps of the first product
   constexpr int DB = DH / 32;              // 32-feature blocks of the output
@@ -251,7 +251,7 @@ __global__ __launch_bounds__(NW * 64, 512 / (NW * 64)) void attn_bf16_kernel(Att
 
   // this lane's rows: block qb covers rows wave*32*NQ + qb*32 + l32 of the work item
   int lim[NQ];
-  bf16x8_t qf[NQ][KS];
+  uint4 qf[NQ][KS];
   const uint16_t* qbase = reinterpret_cast<const uint16_t*>(p.q);
 #pragma unroll
   for (int qb = 0; qb < NQ; ++qb) {
@@ -261,7 +261,7 @@ __global__ __launch_bounds__(NW * 64, 512 / (NW * 64)) void attn_bf16_kernel(Att
     lim[qb] = ok ? p.rt.lim[row] : 0;
     const uint16_t* qr = qbase + (size_t)row * p.d + head * DH + g * 8;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(qr + ks * 16));
+    for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = *reinterpret_cast<const uint4*>(qr + ks * 16);
   }
 
   f32x16_t oacc[DB][NQ];
@@ -310,7 +310,7 @@ __global__ __launch_bounds__(NW * 64, 512 / (NW * 64)) void attn_bf16_kernel(Att
 #pragma unroll
       for (int e = 0; e < 8; ++e) pk_b[qb][e] = 0u;          // nothing owed yet: P = 0 adds nothing
     const uint16_t* vprev = &bufs[0][lane * 8] + kTile * DH;  // any finite V will do with P = 0
-    attn_s_half<DH, NQ>(&bufs[0][lane * 8], qf, s_cur);
+    attn_s_half<H, DH, NQ>(&bufs[0][lane * 8], qf, s_cur);
     int b = 0;                                                 // ring slot of tile i
 
     // one tile = two pipeline steps; MASKED tiles apply the per-element visibility test
@@ -328,7 +328,7 @@ __global__ __launch_bounds__(NW * 64, 512 / (NW * 64)) void attn_bf16_kernel(Att
       const uint16_t* kt = &bufs[b][lane * 8];
       const uint16_t* vt = kt + kTile * DH;
       // step 1: SiLU of the first half | first product of the second half, second product owed from before
-      if (wave_active) attn_step<DH, NQ, MASKED>(kt + KS * 512, vprev, qf, s_cur, s_nxt, pk_b, pk_a, oacc, vis);
+      if (wave_active) attn_step<H, DH, NQ, MASKED>(kt + KS * 512, vprev, qf, s_cur, s_nxt, pk_b, pk_a, oacc, vis);
       // the next tile must have landed before its first product; every wavefront is now past tile i-1
       const int bn = (b == 2) ? 0 : b + 1;
       const bool more = i + 1 < nt;
@@ -343,7 +343,7 @@ __global__ __launch_bounds__(NW * 64, 512 / (NW * 64)) void attn_bf16_kernel(Att
 #pragma unroll
         for (int qb = 0; qb < NQ; ++qb) vis[qb] -= 32;
       }
-      if (wave_active) attn_step<DH, NQ, MASKED>(more ? &bufs[bn][lane * 8] : kt, vt, qf, s_nxt, s_cur, pk_a, pk_b, oacc, vis);
+      if (wave_active) attn_step<H, DH, NQ, MASKED>(more ? &bufs[bn][lane * 8] : kt, vt, qf, s_nxt, s_cur, pk_a, pk_b, oacc, vis);
       vprev = vt + 2 * 512;
       b = bn;
     };
@@ -353,7 +353,7 @@ __global__ __launch_bounds__(NW * 64, 512 / (NW * 64)) void attn_bf16_kernel(Att
     int i = 0;
     for (; i < n_plain; ++i) tile_iter(std::false_type(), i);
     for (; i < nt; ++i) tile_iter(std::true_type(), i);
-    attn_pv_half<DH, NQ>(vprev, pk_b, oacc);                   // the last half's second product
+    attn_pv_half<H, DH, NQ>(vprev, pk_b, oacc);                   // the last half's second product
   }
 
   // element e of oacc[db][qb]: feature db*32 + 8*(e/4) + 4*g + e%4, row l32 of block qb

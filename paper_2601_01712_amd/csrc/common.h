@@ -28,6 +28,7 @@
 
 #include <hip/hip_runtime.h>
 #include <hip/hip_bf16.h>
+#include <hip/hip_fp16.h>
 #include <stdint.h>
 
 namespace relaygr {
@@ -76,7 +77,8 @@ template <> struct KvLayout<float> {
   static __host__ __device__ __forceinline__ int k_off(int r, int f, int dh) { return r * dh + f; }
   static __host__ __device__ __forceinline__ int v_off(int r, int f, int dh) { return kTile * dh + f * kTile + r; }
 };
-template <> struct KvLayout<__hip_bfloat16> {
+// both 16-bit storage types: MFMA fragment order
+struct KvLayout16 {
   static __host__ __device__ __forceinline__ int k_off(int r, int f, int dh) {
     int kb = r >> 5, l32 = r & 31, ks = f >> 4, g = (f >> 3) & 1, j = f & 7;
     return ((kb * (dh >> 4) + ks) * 64 + g * 32 + l32) * 8 + j;
@@ -87,6 +89,8 @@ template <> struct KvLayout<__hip_bfloat16> {
     return kTile * dh + (((db * 2 + kb) * 2 + m) * 64 + g * 32 + l32) * 8 + j;
   }
 };
+template <> struct KvLayout<__hip_bfloat16> : KvLayout16 {};
+template <> struct KvLayout<__half> : KvLayout16 {};
 
 // ---- element access in the two storage types ------------------------------------------------
 template <typename T> struct Elem;
@@ -99,6 +103,11 @@ template <> struct Elem<__hip_bfloat16> {
     return __uint_as_float(((uint32_t)(*reinterpret_cast<const uint16_t*>(p))) << 16);
   }
   static __device__ __forceinline__ void st(__hip_bfloat16* p, float v) { *p = __float2bfloat16(v); }
+};
+
+template <> struct Elem<__half> {
+  static __device__ __forceinline__ float ld(const __half* p) { return __half2float(*p); }
+  static __device__ __forceinline__ void st(__half* p, float v) { *p = __float2half(v); }
 };
 
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }

@@ -49,17 +49,19 @@ int relaygr::fail(int code, const char* fmt, ...) {
 extern "C" const char* relaygr_last_error(void) { return g_err; }
 
 // ---- config -----------------------------------------------------------------------------------
+static inline bool is_half16(const relaygr_model_config& c) { return c.dtype == RELAYGR_DTYPE_BF16 || c.dtype == RELAYGR_DTYPE_FP16; }
+
 static bool config_ok(const relaygr_model_config* c) {
   if (!c) return false;
   if (c->n_layers < 1 || c->n_heads < 1 || c->d_model < 64) return false;
-  if (c->dtype != RELAYGR_DTYPE_FP32 && c->dtype != RELAYGR_DTYPE_BF16) return false;
+  if (c->dtype != RELAYGR_DTYPE_FP32 && c->dtype != RELAYGR_DTYPE_BF16 && c->dtype != RELAYGR_DTYPE_FP16) return false;
   int d = c->d_model;
   if (d != 64 && d != 128 && d != 256 && d != 512 && d != 1024) return false;
   if (d % c->n_heads) return false;
   int dh = d / c->n_heads;
   if (dh != 32 && dh != 64 && dh != 128) return false;
   if (dh < d / 64) return false;                       // a head must span at least one lane in row-wise kernels
-  if (c->dtype == RELAYGR_DTYPE_BF16 && d < 128) return false;  // the MFMA GEMM tiles 128 output columns
+  if (is_half16(*c) && d < 128) return false;  // the MFMA GEMM tiles 128 output columns
   if (!(c->ln_eps > 0.f)) return false;
   return true;
 }
@@ -96,14 +98,14 @@ static int rows_per_attn_tile(const relaygr_model_config& c, int nq) { return c.
 // Lays the call's buffers out in scratch.  Everything is a function of the counts already in p.
 // Bytes at the start of scratch that hold the weights re-packed into MFMA panels (bf16 only).
 static size_t wpack_bytes(const relaygr_model_config& c) {
-  if (c.dtype != RELAYGR_DTYPE_BF16) return 0;
+  if (!is_half16(c)) return 0;
   const size_t d = c.d_model;
   return align_up((size_t)c.n_layers * 5 * d * d * 2);
 }
 
 // Prefix rows of a user start at a multiple of this in the row space (bf16: GEMM tiles of 256 rows
 // never straddle users, and 32-row MFMA blocks coincide with 32-token halves of K/V tiles).
-static int prefix_row_align(const relaygr_model_config& c) { return c.dtype == RELAYGR_DTYPE_BF16 ? kPrefixRowAlign : 1; }
+static int prefix_row_align(const relaygr_model_config& c) { return is_half16(c) ? kPrefixRowAlign : 1; }
 
 static void carve(const relaygr_model_config& c, Plan& p) {
   const size_t d = c.d_model, e = elem_bytes(c), R = p.n_rows;
@@ -211,7 +213,7 @@ extern "C" int relaygr_ctx_create(const relaygr_model_config* cfg, const relaygr
   c->ln_out_g = w->ln_out_g; c->ln_out_b = w->ln_out_b; c->w_score = w->w_score; c->b_score = w->b_score;
   c->scratch = (char*)scratch_dev;
   c->scratch_bytes = scratch_bytes;
-  if (cfg->dtype == RELAYGR_DTYPE_BF16) {
+  if (is_half16(*cfg)) {
     // re-pack W1 and W2 of every layer into MFMA panels, once
     const size_t d = cfg->d_model;
     if (scratch_bytes < wpack_bytes(*cfg)) { delete c; return fail(RELAYGR_ENOSPC, "ctx_create: scratch smaller than the packed weights"); }
@@ -220,10 +222,10 @@ extern "C" int relaygr_ctx_create(const relaygr_model_config* cfg, const relaygr
       uint16_t* w1p = wp + (size_t)l * 5 * d * d;
       uint16_t* w2p = w1p + 4 * d * d;
       int c1 = (int)(4 * d * d / 8), c2 = (int)(d * d / 8);
-      hipLaunchKernelGGL(pack_weight_kernel, dim3((c1 + 255) / 256), dim3(256), 0, 0, (const __hip_bfloat16*)c->layers[l].w1,
-                         (__hip_bfloat16*)w1p, (int)(4 * d), (int)d);
-      hipLaunchKernelGGL(pack_weight_kernel, dim3((c2 + 255) / 256), dim3(256), 0, 0, (const __hip_bfloat16*)c->layers[l].w2,
-                         (__hip_bfloat16*)w2p, (int)d, (int)d);
+      hipLaunchKernelGGL(pack_weight_kernel, dim3((c1 + 255) / 256), dim3(256), 0, 0, (const uint16_t*)c->layers[l].w1,
+                         (uint16_t*)w1p, (int)(4 * d), (int)d);
+      hipLaunchKernelGGL(pack_weight_kernel, dim3((c2 + 255) / 256), dim3(256), 0, 0, (const uint16_t*)c->layers[l].w2,
+                         (uint16_t*)w2p, (int)d, (int)d);
       c->w1_packed.push_back(w1p);
       c->w2_packed.push_back(w2p);
     }
@@ -405,8 +407,8 @@ extern "C" int relaygr_kv_pool_locate(relaygr_kv_pool* pool, relaygr_kv_handle h
     *k_index = base + KvLayout<float>::k_off(r, f, dh);
     *v_index = base + KvLayout<float>::v_off(r, f, dh);
   } else {
-    *k_index = base + KvLayout<__hip_bfloat16>::k_off(r, f, dh);
-    *v_index = base + KvLayout<__hip_bfloat16>::v_off(r, f, dh);
+    *k_index = base + KvLayout16::k_off(r, f, dh);
+    *v_index = base + KvLayout16::v_off(r, f, dh);
   }
   return RELAYGR_OK;
 }
@@ -442,6 +444,9 @@ template <> struct GemmLaunch<float> {
 template <> struct GemmLaunch<__hip_bfloat16> {
   static constexpr int BM = 64 * kF1TM;
 };
+template <> struct GemmLaunch<__half> {
+  static constexpr int BM = 64 * kF1TM;
+};
 
 template <typename T>
 static int launch_attention(const relaygr_model_config& cfg, const AttnParams& ap, int n_tiles, int nq, hipStream_t st);
@@ -459,21 +464,29 @@ int launch_attention<float>(const relaygr_model_config& cfg, const AttnParams& a
   return RELAYGR_OK;
 }
 
-template <>
-int launch_attention<__hip_bfloat16>(const relaygr_model_config& cfg, const AttnParams& ap, int n_tiles, int nq, hipStream_t st) {
+template <typename H>
+static int launch_attention16(const relaygr_model_config& cfg, const AttnParams& ap, int n_tiles, int nq, hipStream_t st) {
   int total = n_tiles * cfg.n_heads * ap.nsplit;
   dim3 grid((total + 7) / 8 * 8);
   switch (cfg.d_model / cfg.n_heads) {
-    case 32: hipLaunchKernelGGL((attn_bf16_kernel<32, 1, 4>), grid, dim3(256), 0, st, ap); break;
+    case 32: hipLaunchKernelGGL((attn_bf16_kernel<H, 32, 1, 4>), grid, dim3(256), 0, st, ap); break;
     case 64:
-      if (nq == 2) hipLaunchKernelGGL((attn_bf16_kernel<64, 2, 4>), grid, dim3(256), 0, st, ap);
-      else hipLaunchKernelGGL((attn_bf16_kernel<64, 1, 4>), grid, dim3(256), 0, st, ap);
+      if (nq == 2) hipLaunchKernelGGL((attn_bf16_kernel<H, 64, 2, 4>), grid, dim3(256), 0, st, ap);
+      else hipLaunchKernelGGL((attn_bf16_kernel<H, 64, 1, 4>), grid, dim3(256), 0, st, ap);
       break;
-    case 128: hipLaunchKernelGGL((attn_bf16_kernel<128, 1, 4>), grid, dim3(256), 0, st, ap); break;
+    case 128: hipLaunchKernelGGL((attn_bf16_kernel<H, 128, 1, 4>), grid, dim3(256), 0, st, ap); break;
     default: return fail(RELAYGR_EINVAL, "attention: unsupported d_head");
   }
-  LAUNCH_CHECK("attn_bf16");
+  LAUNCH_CHECK("attn (16-bit)");
   return RELAYGR_OK;
+}
+template <>
+int launch_attention<__hip_bfloat16>(const relaygr_model_config& cfg, const AttnParams& ap, int n_tiles, int nq, hipStream_t st) {
+  return launch_attention16<Bf16>(cfg, ap, n_tiles, nq, st);
+}
+template <>
+int launch_attention<__half>(const relaygr_model_config& cfg, const AttnParams& ap, int n_tiles, int nq, hipStream_t st) {
+  return launch_attention16<F16>(cfg, ap, n_tiles, nq, st);
 }
 
 static int check_offsets(const int32_t* off, int n, const char* what) {
@@ -488,7 +501,8 @@ template <typename T>
 static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode mode, float* scores, hipStream_t st) {
   const relaygr_model_config& cfg = c->cfg;
   const int d = cfg.d_model, H = cfg.n_heads, dh = d / H, NL = cfg.n_layers, n = b->n_users;
-  const bool bf16 = cfg.dtype == RELAYGR_DTYPE_BF16;
+  const bool bf16 = is_half16(cfg);   // either 16-bit type: the MFMA path
+  using HT = typename HalfOf<T>::type;
   const int palign = prefix_row_align(cfg);
 
   // -- per-user shapes and K/V sources
@@ -715,7 +729,7 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
         fp.row_begin = r0; fp.row_end = r1; fp.n_mtiles = (r1 - r0 + 64 * kF1TM - 1) / (64 * kF1TM);
         fp.cm = cm; fp.q_mul = q_mul;
         int total = fp.n_mtiles * cm.nblk * (d / (64 * kF1TN));
-        hipLaunchKernelGGL(f1_gemm_bf16_kernel, dim3((total + 7) / 8 * 8), dim3(256), 0, st, fp);
+        hipLaunchKernelGGL(f1_gemm_bf16_kernel<HT>, dim3((total + 7) / 8 * 8), dim3(256), 0, st, fp);
       }
     };
     if (last && p.n_prows) {
@@ -781,25 +795,25 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
           dim3 grid((rows + (rb2 ? 63 : 31)) / (rb2 ? 64 : 32));
           switch (d) {
             case 128:
-              if (rb2) hipLaunchKernelGGL((f2_ln_bf16_kernel<128, 4, 2>), grid, dim3(256), 0, st, fp);
-              else hipLaunchKernelGGL((f2_ln_bf16_kernel<128, 4, 1>), grid, dim3(256), 0, st, fp);
+              if (rb2) hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 128, 4, 2>), grid, dim3(256), 0, st, fp);
+              else hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 128, 4, 1>), grid, dim3(256), 0, st, fp);
               break;
             case 256:
-              if (rb2) hipLaunchKernelGGL((f2_ln_bf16_kernel<256, 8, 2>), grid, dim3(512), 0, st, fp);
-              else hipLaunchKernelGGL((f2_ln_bf16_kernel<256, 8, 1>), grid, dim3(512), 0, st, fp);
+              if (rb2) hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 256, 8, 2>), grid, dim3(512), 0, st, fp);
+              else hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 256, 8, 1>), grid, dim3(512), 0, st, fp);
               break;
             case 512:
-              if (rb2) hipLaunchKernelGGL((f2_ln_bf16_kernel<512, 8, 2>), grid, dim3(512), 0, st, fp);
-              else hipLaunchKernelGGL((f2_ln_bf16_kernel<512, 8, 1>), grid, dim3(512), 0, st, fp);
+              if (rb2) hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 512, 8, 2>), grid, dim3(512), 0, st, fp);
+              else hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 512, 8, 1>), grid, dim3(512), 0, st, fp);
               break;
-            default: hipLaunchKernelGGL((f2_ln_bf16_kernel<1024, 8, 1>), grid, dim3(512), 0, st, fp); break;
+            default: hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 1024, 8, 1>), grid, dim3(512), 0, st, fp); break;
           }
         } else {
           F2Params fp;
           fp.A = (const uint16_t*)xh; fp.W = c->w2_packed[l]; fp.bias = (const uint16_t*)lw.b2; fp.x = x; fp.rt = rt; fp.d = d;
           fp.row_begin = a0; fp.row_end = R; fp.n_mtiles = (R - a0 + 64 * kF2TM - 1) / (64 * kF2TM);
           int total = fp.n_mtiles * (d / (64 * kF2TN));
-          hipLaunchKernelGGL(f2_gemm_bf16_kernel, dim3((total + 7) / 8 * 8), dim3(256), 0, st, fp);
+          hipLaunchKernelGGL(f2_gemm_bf16_kernel<HT>, dim3((total + 7) / 8 * 8), dim3(256), 0, st, fp);
         }
       }
     }
@@ -836,6 +850,7 @@ static int run(relaygr_ctx* c, relaygr_kv_pool* pool, const relaygr_batch* b, Mo
   }
   hipStream_t st = (hipStream_t)stream;
   if (c->cfg.dtype == RELAYGR_DTYPE_FP32) return run_typed<float>(c, kp, b, mode, scores, st);
+  if (c->cfg.dtype == RELAYGR_DTYPE_FP16) return run_typed<__half>(c, kp, b, mode, scores, st);
   return run_typed<__hip_bfloat16>(c, kp, b, mode, scores, st);
 }
 

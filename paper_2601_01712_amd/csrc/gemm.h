@@ -16,6 +16,39 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+
+// The two 16-bit storage types of the MFMA path (bf16: the benchmark's; fp16: the half precision the
+// paper mentions as lowering the rank stage, Section 5.2).  Kernels are written against this
+// interface: bit patterns in, fp32 out; pack2 rounds to nearest even; mfma is the 32x32x16 product
+// of two 8-element fragments.
+struct Bf16 {
+  using elem = __hip_bfloat16;
+  static __device__ __forceinline__ float to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+  static __device__ __forceinline__ float of_word(uint32_t w, int i) { return __uint_as_float((i & 1) ? (w & 0xFFFF0000u) : (w << 16)); }
+  static __device__ __forceinline__ uint32_t pack2(float a, float b) {
+    f32x2_t v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));     // one v_cvt_pk_bf16_f32
+  }
+  static __device__ __forceinline__ f32x16_t mfma(uint4 a, uint4 b, f32x16_t c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+  }
+};
+struct F16 {
+  using elem = __half;
+  static __device__ __forceinline__ float to_f32(uint16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
+  static __device__ __forceinline__ float of_word(uint32_t w, int i) { return (float)__builtin_bit_cast(f16x2_t, w)[i & 1]; }
+  static __device__ __forceinline__ uint32_t pack2(float a, float b) {
+    f32x2_t v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2_t));      // one v_cvt_pk_f16_f32
+  }
+  static __device__ __forceinline__ f32x16_t mfma(uint4 a, uint4 b, f32x16_t c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+  }
+};
+template <typename T> struct HalfOf { using type = Bf16; };
+template <> struct HalfOf<__half> { using type = F16; };
 
 // Which output column blocks (of width d) a launch produces: block j of the launch is block
 // blk[j] of the weight (f1 on last-layer prefix rows needs only v and k).

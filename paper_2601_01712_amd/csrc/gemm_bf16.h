@@ -28,13 +28,13 @@ constexpr int kGemmKTile = 32;          // k per main-loop step (2 MFMA k-steps)
 constexpr int kPrefixRowAlign = 256;    // prefix rows of a user start at a multiple of this in the row space
 
 // Re-packs a row-major [N, K] weight into panels.
-__global__ void pack_weight_kernel(const __hip_bfloat16* __restrict__ w, __hip_bfloat16* __restrict__ packed, int N, int K) {
+__global__ void pack_weight_kernel(const uint16_t* __restrict__ w, uint16_t* __restrict__ packed, int N, int K) {
   int idx = blockIdx.x * blockDim.x + threadIdx.x;   // one 8-element chunk per thread
   int chunks_per_row = K >> 3;
   if (idx >= N * chunks_per_row) return;
   int n = idx / chunks_per_row, kc = idx - n * chunks_per_row;
-  uint4 v = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(w) + (size_t)n * K + kc * 8);
-  *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(packed) + panel_off(n, kc * 8, K)) = v;
+  uint4 v = *reinterpret_cast<const uint4*>(w + (size_t)n * K + kc * 8);
+  *reinterpret_cast<uint4*>(packed + panel_off(n, kc * 8, K)) = v;
 }
 
 // ---- main loop ----------------------------------------------------------------------------------
@@ -54,7 +54,7 @@ struct GemmTile {
 };
 
 // FEATURE_MAJOR: features are the MFMA row operand (lane = token column, 4-feature runs per lane).
-template <int TM, int TN, int NSTAGE, bool FEATURE_MAJOR>
+template <typename H, int TM, int TN, int NSTAGE, bool FEATURE_MAJOR>
 __device__ __forceinline__ void gemm_mainloop(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W, int K, int m0, int n0,
                                               uint16_t* lds, f32x16_t (&acc)[TM][TN]) {
   using G = GemmTile<TM, TN, NSTAGE>;
@@ -105,18 +105,18 @@ __device__ __forceinline__ void gemm_mainloop(const uint16_t* __restrict__ A, co
     const uint16_t* featp = tokp + G::TOK_PIECES * 512;
     // fetch the fragments of both k-steps first, so that the second set's LDS latency hides under
     // the first set's MFMAs
-    bf16x8_t tf[2][TM], ff[2][TN];
+    uint4 tf[2][TM], ff[2][TN];
 #pragma unroll
     for (int ksl = 0; ksl < 2; ++ksl) {
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         int rbAll = wm * TM + i;   // 32-row block inside the workgroup tile
-        tf[ksl][i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(tokp + (((rbAll >> 2) * 2 + ksl) * 4 + (rbAll & 3)) * 512));
+        tf[ksl][i] = *reinterpret_cast<const uint4*>(tokp + (((rbAll >> 2) * 2 + ksl) * 4 + (rbAll & 3)) * 512);
       }
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         int nbAll = wn * TN + j;
-        ff[ksl][j] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(featp + (((nbAll >> 2) * 2 + ksl) * 4 + (nbAll & 3)) * 512));
+        ff[ksl][j] = *reinterpret_cast<const uint4*>(featp + (((nbAll >> 2) * 2 + ksl) * 4 + (nbAll & 3)) * 512);
       }
     }
     __builtin_amdgcn_sched_barrier(0);   // keep all twelve reads ahead of the MFMAs
@@ -126,8 +126,7 @@ __device__ __forceinline__ void gemm_mainloop(const uint16_t* __restrict__ A, co
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = FEATURE_MAJOR ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(ff[ksl][j], tf[ksl][i], acc[i][j], 0, 0, 0)
-                                    : __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf[ksl][i], ff[ksl][j], acc[i][j], 0, 0, 0);
+          acc[i][j] = FEATURE_MAJOR ? H::mfma(ff[ksl][j], tf[ksl][i], acc[i][j]) : H::mfma(tf[ksl][i], ff[ksl][j], acc[i][j]);
     slot = (slot == NSTAGE - 1) ? 0 : slot + 1;
   }
   __syncthreads();   // every wavefront is done reading LDS: the epilogue may reuse it
@@ -146,14 +145,11 @@ struct F1Params {
   float q_mul;
 };
 
-__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
-  f32x2_t v = {a, b};
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
-}
 
 constexpr int kF1TM = 4, kF1TN = 2, kF1Stages = 3;   // 256 tokens x 128 features per workgroup
 constexpr int kStageLd = 64 * kF1TN + 8;          // epilogue staging row stride (elements)
 
+template <typename H>
 __global__ __launch_bounds__(256, 2) void f1_gemm_bf16_kernel(F1Params p) {
   constexpr int TM = kF1TM, TN = kF1TN;
   using G = GemmTile<TM, TN, kF1Stages>;
@@ -183,7 +179,7 @@ __global__ __launch_bounds__(256, 2) void f1_gemm_bf16_kernel(F1Params p) {
   if (blk == 1 && prefix_tile) {
     // ---- V of prefix rows: token-major product; the accumulator of a 32-token x 32-feature block
     // is, lane for lane, two V-tile fragments (m = 0, 1), stored as 1 KiB contiguous runs.
-    gemm_mainloop<TM, TN, kF1Stages, false>(p.A, p.W, d, m0, n0, lds, acc);
+    gemm_mainloop<H, TM, TN, kF1Stages, false>(p.A, p.W, d, m0, n0, lds, acc);
     const int user = p.rt.user[m0];
     const UserDesc ud = p.users[user];
     const int pos0 = p.rt.idx[m0];
@@ -193,7 +189,7 @@ __global__ __launch_bounds__(256, 2) void f1_gemm_bf16_kernel(F1Params p) {
     for (int j = 0; j < TN; ++j) {
       const int c = c0 + wn * 64 + j * 32;                  // first feature of this 32-feature block
       const int head = c / dh, db = (c - head * dh) >> 5;
-      const float bias = bf16_bits_to_float(p.bias[n0 + wn * 64 + j * 32 + l32]);
+      const float bias = H::to_f32(p.bias[n0 + wn * 64 + j * 32 + l32]);
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         const int tok0 = pos0 + wm * 128 + i * 32;          // first token of this 32-token block
@@ -213,8 +209,8 @@ __global__ __launch_bounds__(256, 2) void f1_gemm_bf16_kernel(F1Params p) {
               float val = silu_fast(acc[i][j][4 * e4 + r] + bias);
               v[r] = tok < L ? val : 0.f;                    // the ragged tail of the last tile holds zeros
             }
-            w[2 * h] = pack_bf16x2(v[0], v[1]);
-            w[2 * h + 1] = pack_bf16x2(v[2], v[3]);
+            w[2 * h] = H::pack2(v[0], v[1]);
+            w[2 * h + 1] = H::pack2(v[2], v[3]);
           }
           *reinterpret_cast<uint4*>(frag + (((db * 2 + kb) * 2 + m) * 64 + lane) * 8) = make_uint4(w[0], w[1], w[2], w[3]);
         }
@@ -236,7 +232,7 @@ __global__ __launch_bounds__(256, 2) void f1_gemm_bf16_kernel(F1Params p) {
   // a prefix tile belongs to one user and holds consecutive prefix positions from pos0 on
   const int tile_user = prefix_tile ? p.rt.user[m0] : 0;
   const int pos0 = prefix_tile ? p.rt.idx[m0] : 0;
-  gemm_mainloop<TM, TN, kF1Stages, true>(p.A, p.W, d, m0, n0, lds, acc);
+  gemm_mainloop<H, TM, TN, kF1Stages, true>(p.A, p.W, d, m0, n0, lds, acc);
   const float mul = (blk == 2) ? p.q_mul : 1.0f;
 #pragma unroll
   for (int j = 0; j < TN; ++j)
@@ -244,14 +240,14 @@ __global__ __launch_bounds__(256, 2) void f1_gemm_bf16_kernel(F1Params p) {
     for (int e4 = 0; e4 < 4; ++e4) {
       const int f = wn * 64 + j * 32 + 8 * e4 + 4 * g;  // 4 consecutive features held by this lane
       const uint2 bb = *reinterpret_cast<const uint2*>(p.bias + n0 + f);
-      const float b0 = bf16_bits_to_float(bb.x & 0xFFFF), b1 = bf16_bits_to_float(bb.x >> 16);
-      const float b2 = bf16_bits_to_float(bb.y & 0xFFFF), b3 = bf16_bits_to_float(bb.y >> 16);
+      const float b0 = H::to_f32(bb.x & 0xFFFF), b1 = H::to_f32(bb.x >> 16);
+      const float b2 = H::to_f32(bb.y & 0xFFFF), b3 = H::to_f32(bb.y >> 16);
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         const int t = wm * 128 + i * 32 + l32;
         uint2 w;
-        w.x = pack_bf16x2(silu_fast(acc[i][j][4 * e4] + b0) * mul, silu_fast(acc[i][j][4 * e4 + 1] + b1) * mul);
-        w.y = pack_bf16x2(silu_fast(acc[i][j][4 * e4 + 2] + b2) * mul, silu_fast(acc[i][j][4 * e4 + 3] + b3) * mul);
+        w.x = H::pack2(silu_fast(acc[i][j][4 * e4] + b0) * mul, silu_fast(acc[i][j][4 * e4 + 1] + b1) * mul);
+        w.y = H::pack2(silu_fast(acc[i][j][4 * e4 + 2] + b2) * mul, silu_fast(acc[i][j][4 * e4 + 3] + b3) * mul);
         *reinterpret_cast<uint2*>(&lds[t * kStageLd + f]) = w;
       }
     }
@@ -289,11 +285,11 @@ __global__ __launch_bounds__(256, 2) void f1_gemm_bf16_kernel(F1Params p) {
     }
     const int rr = idx & 63;
     if (blk == 3) {
-      *reinterpret_cast<uint4*>(base + KvLayout<__hip_bfloat16>::k_off(rr, f, dh)) = val;
+      *reinterpret_cast<uint4*>(base + KvLayout16::k_off(rr, f, dh)) = val;
     } else {   // V of a suffix row: its 8 features go to 8 different fragments
       const uint16_t* e = reinterpret_cast<const uint16_t*>(&val);
 #pragma unroll
-      for (int x = 0; x < 8; ++x) base[KvLayout<__hip_bfloat16>::v_off(rr, f + x, dh)] = e[x];
+      for (int x = 0; x < 8; ++x) base[KvLayout16::v_off(rr, f + x, dh)] = e[x];
     }
   }
 }
@@ -310,6 +306,7 @@ struct F2Params {
 
 constexpr int kF2TM = 2, kF2TN = 2, kF2Stages = 4;   // 128 tokens x 128 features per workgroup
 
+template <typename H>
 __global__ __launch_bounds__(256, 2) void f2_gemm_bf16_kernel(F2Params p) {
   constexpr int TM = kF2TM, TN = kF2TN;
   using G = GemmTile<TM, TN, kF2Stages>;
@@ -325,7 +322,7 @@ __global__ __launch_bounds__(256, 2) void f2_gemm_bf16_kernel(F2Params p) {
   f32x16_t acc[TM][TN];
   // feature-major: a lane holds one token and runs of 4 consecutive features, i.e. one 16-byte
   // read-modify-write of the fp32 residual row per accumulator quad
-  gemm_mainloop<TM, TN, kF2Stages, true>(p.A, p.W, p.d, m0, n0, lds, acc);
+  gemm_mainloop<H, TM, TN, kF2Stages, true>(p.A, p.W, p.d, m0, n0, lds, acc);
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     const int row = m0 + wm * 64 + i * 32 + l32;
@@ -338,10 +335,10 @@ __global__ __launch_bounds__(256, 2) void f2_gemm_bf16_kernel(F2Params p) {
         const int c = n0 + wn * 64 + j * 32 + 8 * e4 + 4 * g;
         const uint2 bb = *reinterpret_cast<const uint2*>(p.bias + c);
         float4 v = *reinterpret_cast<const float4*>(xrow + c);
-        v.x += acc[i][j][4 * e4] + bf16_bits_to_float(bb.x & 0xFFFF);
-        v.y += acc[i][j][4 * e4 + 1] + bf16_bits_to_float(bb.x >> 16);
-        v.z += acc[i][j][4 * e4 + 2] + bf16_bits_to_float(bb.y & 0xFFFF);
-        v.w += acc[i][j][4 * e4 + 3] + bf16_bits_to_float(bb.y >> 16);
+        v.x += acc[i][j][4 * e4] + H::to_f32(bb.x & 0xFFFF);
+        v.y += acc[i][j][4 * e4 + 1] + H::to_f32(bb.x >> 16);
+        v.z += acc[i][j][4 * e4 + 2] + H::to_f32(bb.y & 0xFFFF);
+        v.w += acc[i][j][4 * e4 + 3] + H::to_f32(bb.y >> 16);
         *reinterpret_cast<float4*>(xrow + c) = v;
       }
   }
@@ -407,7 +404,6 @@ __device__ __forceinline__ void ld_bf16_run(const uint16_t* src, uint32_t (&w)[E
     }
   }
 }
-__device__ __forceinline__ float bf16_of_word(uint32_t w, int i) { return __uint_as_float((i & 1) ? (w & 0xFFFF0000u) : (w << 16)); }
 
 // One row of the attention combine + gate, by one wavefront, lane owning features [lane*E, lane*E+E):
 // loads are issued by load_gate_row for several rows before any of them is reduced.
@@ -454,7 +450,7 @@ __device__ __forceinline__ void load_gate_row(const F2LnParams& p, int row, bool
 
 // Finishes G rows at once (their reductions interleave) and writes y (bf16) into the token
 // fragments: local row lr0 + i of the workgroup goes to row block (lr0+i)/32, row (lr0+i)%32.
-template <int D, int G>
+template <typename H, int D, int G>
 __device__ __forceinline__ void finish_gate_rows(const F2LnParams& p, GateRow<D / 64> (&gr)[G], int lane, uint16_t* tok, int lr0,
                                                  const uint32_t (&gw)[D / 128], const uint32_t (&ow)[D / 128]) {
   constexpr int E = D / 64, KS = D / 16;
@@ -465,7 +461,7 @@ __device__ __forceinline__ void finish_gate_rows(const F2LnParams& p, GateRow<D 
     if (gr[r].kind == kRowCand) {      // the candidate's own key: SiLU(alpha <q_c, k_c>) v_c per head
       float dot = 0.f;
 #pragma unroll
-      for (int i = 0; i < E; ++i) dot += bf16_of_word(gr[r].qb[i >> 1], i) * bf16_of_word(gr[r].kb[i >> 1], i);
+      for (int i = 0; i < E; ++i) dot += H::of_word(gr[r].qb[i >> 1], i) * H::of_word(gr[r].kb[i >> 1], i);
       // the lanes of one head are dh/E consecutive lanes
       const int hl = p.dh / E;
       if (hl == 2) dot = lanes2_sum(dot);
@@ -476,7 +472,7 @@ __device__ __forceinline__ void finish_gate_rows(const F2LnParams& p, GateRow<D 
       else if (hl == 64) dot = wave_sum_dpp(dot);
       const float pself = silu_f32(dot * p.qk_mul);
 #pragma unroll
-      for (int i = 0; i < E; ++i) gr[r].o[i] += pself * bf16_of_word(gr[r].vb[i >> 1], i);
+      for (int i = 0; i < E; ++i) gr[r].o[i] += pself * H::of_word(gr[r].vb[i >> 1], i);
       n += 1;
     }
     inv_n[r] = 1.0f / (float)(n > 0 ? n : 1);
@@ -499,11 +495,11 @@ __device__ __forceinline__ void finish_gate_rows(const F2LnParams& p, GateRow<D 
     uint32_t yw[E / 2];
 #pragma unroll
     for (int i = 0; i < E / 2; ++i) {
-      float z0 = (gr[r].o[2 * i] - mean[r]) * rstd * bf16_of_word(gw[i], 0) + bf16_of_word(ow[i], 0);
-      float z1 = (gr[r].o[2 * i + 1] - mean[r]) * rstd * bf16_of_word(gw[i], 1) + bf16_of_word(ow[i], 1);
-      f32x2_t two = {z0 * bf16_of_word(gr[r].ub[i], 0), z1 * bf16_of_word(gr[r].ub[i], 1)};
+      float z0 = (gr[r].o[2 * i] - mean[r]) * rstd * H::of_word(gw[i], 0) + H::of_word(ow[i], 0);
+      float z1 = (gr[r].o[2 * i + 1] - mean[r]) * rstd * H::of_word(gw[i], 1) + H::of_word(ow[i], 1);
+      f32x2_t two = {z0 * H::of_word(gr[r].ub[i], 0), z1 * H::of_word(gr[r].ub[i], 1)};
       if (gr[r].kind == kRowPad) { two[0] = 0.f; two[1] = 0.f; }
-      yw[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2_t));
+      yw[i] = H::pack2(two[0], two[1]);
     }
     // feature f of a row block's local row rr sits at fragment f/16, lane (f/8 % 2)*32 + rr, element f%8
     const int lr = lr0 + r;
@@ -521,7 +517,7 @@ __device__ __forceinline__ void finish_gate_rows(const F2LnParams& p, GateRow<D 
   }
 }
 
-template <int D, int NW, int RB>
+template <typename H, int D, int NW, int RB>
 __global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
   constexpr int KS = D / 16;            // k-steps
   constexpr int FB = D / 32 / NW;       // 32-feature blocks per wavefront
@@ -557,11 +553,11 @@ __global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
     const int fb = wave * FB + j;
     wbase[j] = p.W + (size_t)(fb >> 2) * KS * 2048 + (fb & 3) * 512 + lane * 8;
   }
-  bf16x8_t wf[PF][FB];
+  uint4 wf[PF][FB];
 #pragma unroll
   for (int i = 0; i < PF; ++i)
 #pragma unroll
-    for (int j = 0; j < FB; ++j) wf[i][j] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(wbase[j] + (size_t)i * 2048));
+    for (int j = 0; j < FB; ++j) wf[i][j] = *reinterpret_cast<const uint4*>(wbase[j] + (size_t)i * 2048);
   // The accumulators start from the residual row plus the bias, fetched now so that the gate and
   // the product hide the latency (the row's kind is only needed when results are stored): element
   // e of acc[b][j] is feature (wave*FB + j)*32 + 8*(e/4) + 4*g + e%4 of token row0 + 32*b + l32.
@@ -582,16 +578,16 @@ __global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
         const int c = (wave * FB + j) * 32 + 8 * e4 + 4 * g;
         const uint2 bb = *reinterpret_cast<const uint2*>(p.bias + c);
         const float4 v = *reinterpret_cast<const float4*>(xrow[b] + c);
-        acc[b][j][4 * e4] = v.x + bf16_bits_to_float(bb.x & 0xFFFF);
-        acc[b][j][4 * e4 + 1] = v.y + bf16_bits_to_float(bb.x >> 16);
-        acc[b][j][4 * e4 + 2] = v.z + bf16_bits_to_float(bb.y & 0xFFFF);
-        acc[b][j][4 * e4 + 3] = v.w + bf16_bits_to_float(bb.y >> 16);
+        acc[b][j][4 * e4] = v.x + H::to_f32(bb.x & 0xFFFF);
+        acc[b][j][4 * e4 + 1] = v.y + H::to_f32(bb.x >> 16);
+        acc[b][j][4 * e4 + 2] = v.z + H::to_f32(bb.y & 0xFFFF);
+        acc[b][j][4 * e4 + 3] = v.w + H::to_f32(bb.y >> 16);
       }
   }
 
   // now that everything else is in flight behind them, the first rows are reduced and written as
   // token fragments; further groups of rows follow
-  finish_gate_rows<D, GROUP>(p, gr, lane, tok, wave * RPW, gw, ow);
+  finish_gate_rows<H, D, GROUP>(p, gr, lane, tok, wave * RPW, gw, ow);
 #pragma unroll
   for (int r0 = GROUP; r0 < RPW; r0 += GROUP) {
 #pragma unroll
@@ -599,7 +595,7 @@ __global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
       const int lr = wave * RPW + r0 + i;
       load_gate_row<D>(p, row0 + lr, row0 + lr < p.row_end, lane, gr[i]);
     }
-    finish_gate_rows<D, GROUP>(p, gr, lane, tok, wave * RPW + r0, gw, ow);
+    finish_gate_rows<H, D, GROUP>(p, gr, lane, tok, wave * RPW + r0, gw, ow);
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
@@ -608,16 +604,16 @@ __global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
 #pragma unroll
     for (int i = 0; i < PF; ++i) {
       const int ks = ks0 + i;
-      bf16x8_t tf[RB];
+      uint4 tf[RB];
 #pragma unroll
-      for (int b = 0; b < RB; ++b) tf[b] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(&tok[(b * KS + ks) * 512 + lane * 8]));
+      for (int b = 0; b < RB; ++b) tf[b] = *reinterpret_cast<const uint4*>(&tok[(b * KS + ks) * 512 + lane * 8]);
 #pragma unroll
       for (int j = 0; j < FB; ++j)
 #pragma unroll
-        for (int b = 0; b < RB; ++b) acc[b][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i][j], tf[b], acc[b][j], 0, 0, 0);
+        for (int b = 0; b < RB; ++b) acc[b][j] = H::mfma(wf[i][j], tf[b], acc[b][j]);
       if (ks + PF < KS) {
 #pragma unroll
-        for (int j = 0; j < FB; ++j) wf[i][j] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(wbase[j] + (size_t)(ks + PF) * 2048));
+        for (int j = 0; j < FB; ++j) wf[i][j] = *reinterpret_cast<const uint4*>(wbase[j] + (size_t)(ks + PF) * 2048);
       }
     }
   }
@@ -681,10 +677,10 @@ __global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
           const int c = (wave * FB + j) * 32 + 8 * e4 + 4 * g;
           const uint2 gg = *reinterpret_cast<const uint2*>(p.gain + c), oo = *reinterpret_cast<const uint2*>(p.offs + c);
           const uint2 ww = *reinterpret_cast<const uint2*>(p.w_score + c);
-          sc += ((acc[b][j][4 * e4] - mean[b]) * rstd * bf16_bits_to_float(gg.x & 0xFFFF) + bf16_bits_to_float(oo.x & 0xFFFF)) * bf16_bits_to_float(ww.x & 0xFFFF);
-          sc += ((acc[b][j][4 * e4 + 1] - mean[b]) * rstd * bf16_bits_to_float(gg.x >> 16) + bf16_bits_to_float(oo.x >> 16)) * bf16_bits_to_float(ww.x >> 16);
-          sc += ((acc[b][j][4 * e4 + 2] - mean[b]) * rstd * bf16_bits_to_float(gg.y & 0xFFFF) + bf16_bits_to_float(oo.y & 0xFFFF)) * bf16_bits_to_float(ww.y & 0xFFFF);
-          sc += ((acc[b][j][4 * e4 + 3] - mean[b]) * rstd * bf16_bits_to_float(gg.y >> 16) + bf16_bits_to_float(oo.y >> 16)) * bf16_bits_to_float(ww.y >> 16);
+          sc += ((acc[b][j][4 * e4] - mean[b]) * rstd * H::to_f32(gg.x & 0xFFFF) + H::to_f32(oo.x & 0xFFFF)) * H::to_f32(ww.x & 0xFFFF);
+          sc += ((acc[b][j][4 * e4 + 1] - mean[b]) * rstd * H::to_f32(gg.x >> 16) + H::to_f32(oo.x >> 16)) * H::to_f32(ww.x >> 16);
+          sc += ((acc[b][j][4 * e4 + 2] - mean[b]) * rstd * H::to_f32(gg.y & 0xFFFF) + H::to_f32(oo.y & 0xFFFF)) * H::to_f32(ww.y & 0xFFFF);
+          sc += ((acc[b][j][4 * e4 + 3] - mean[b]) * rstd * H::to_f32(gg.y >> 16) + H::to_f32(oo.y >> 16)) * H::to_f32(ww.y >> 16);
         }
       score_part[b] = sc + __shfl_xor(sc, 32, 64);
       continue;
@@ -697,15 +693,15 @@ __global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
       for (int e4 = 0; e4 < 4; ++e4) {
         const int c = (wave * FB + j) * 32 + 8 * e4 + 4 * g;
         const uint2 gg = *reinterpret_cast<const uint2*>(p.gain + c), oo = *reinterpret_cast<const uint2*>(p.offs + c);
-        float z0 = (acc[b][j][4 * e4] - mean[b]) * rstd * bf16_bits_to_float(gg.x & 0xFFFF) + bf16_bits_to_float(oo.x & 0xFFFF);
-        float z1 = (acc[b][j][4 * e4 + 1] - mean[b]) * rstd * bf16_bits_to_float(gg.x >> 16) + bf16_bits_to_float(oo.x >> 16);
-        float z2 = (acc[b][j][4 * e4 + 2] - mean[b]) * rstd * bf16_bits_to_float(gg.y & 0xFFFF) + bf16_bits_to_float(oo.y & 0xFFFF);
-        float z3 = (acc[b][j][4 * e4 + 3] - mean[b]) * rstd * bf16_bits_to_float(gg.y >> 16) + bf16_bits_to_float(oo.y >> 16);
+        float z0 = (acc[b][j][4 * e4] - mean[b]) * rstd * H::to_f32(gg.x & 0xFFFF) + H::to_f32(oo.x & 0xFFFF);
+        float z1 = (acc[b][j][4 * e4 + 1] - mean[b]) * rstd * H::to_f32(gg.x >> 16) + H::to_f32(oo.x >> 16);
+        float z2 = (acc[b][j][4 * e4 + 2] - mean[b]) * rstd * H::to_f32(gg.y & 0xFFFF) + H::to_f32(oo.y & 0xFFFF);
+        float z3 = (acc[b][j][4 * e4 + 3] - mean[b]) * rstd * H::to_f32(gg.y >> 16) + H::to_f32(oo.y >> 16);
         if (!live[b]) z0 = z1 = z2 = z3 = 0.f;     // filler rows stay finite
         f32x2_t lo = {z0, z1}, hi = {z2, z3};
         uint2 out;
-        out.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2_t));
-        out.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2_t));
+        out.x = H::pack2(lo[0], lo[1]);
+        out.y = H::pack2(hi[0], hi[1]);
         *reinterpret_cast<uint2*>(p.xh + panel_off(row, c, D)) = out;
       }
   }

@@ -97,6 +97,8 @@ def round_to_bf16(x: np.ndarray) -> np.ndarray:
 def _store(x: np.ndarray, dtype: str) -> np.ndarray:
     if dtype == "bf16":
         return round_to_bf16(x)
+    if dtype == "fp16":
+        return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).astype(np.float32)   # round to nearest even
     if dtype == "fp32":
         return np.ascontiguousarray(x, dtype=np.float32)
     raise ValueError(f"unknown storage dtype {dtype!r}")
@@ -111,7 +113,7 @@ class ModelConfig:
     n_layers: int
     d_model: int
     n_heads: int
-    dtype: str  # "fp32" or "bf16": storage type of weights, embeddings and cached K/V
+    dtype: str  # "fp32", "bf16" or "fp16": storage type of weights, embeddings and cached K/V
     ln_eps: float = 1e-5
 
     @property
@@ -159,6 +161,9 @@ WORKLOADS: Dict[str, Workload] = {
     "X1": Workload("X1", ModelConfig(8, 1024, 8, "bf16"), seed=6, n_users=16,
                    prefix_len=4096, n_cands=512, n_suffix=0),
     "X2": Workload("X2", ModelConfig(16, 512, 8, "bf16"), seed=7, n_users=16,
+                   prefix_len=4096, n_cands=512, n_suffix=0),
+    # the half precision the paper mentions as lowering the rank stage (Section 5.2): C3 in IEEE fp16
+    "X3": Workload("X3", ModelConfig(8, 512, 8, "fp16"), seed=8, n_users=16,
                    prefix_len=4096, n_cands=512, n_suffix=0),
 }
 

@@ -12,7 +12,9 @@ import paper_2601_01712_amd as rg
 import synth
 from synth.generator import user_slices
 
-TOL = {"fp32": 1e-4, "bf16": 2e-2}   # max-abs error relative to max(1, max|reference|)
+# max-abs error relative to max(1, max|reference|).  fp32 and bf16: the stated targets.  fp16 has three more
+# mantissa bits than bf16 (unit roundoff 2^-11 against 2^-8), so its bound is the bf16 one divided by 8.
+TOL = {"fp32": 1e-4, "bf16": 2e-2, "fp16": 2.5e-3}
 
 
 def make_workload(name, cfg: synth.ModelConfig, seed: int, n_users: int) -> synth.Workload:
@@ -53,7 +55,7 @@ class Harness:
         page_bytes = rg.relaygr_kv_pool_bytes_for(ccfg, page_tokens, page_tokens)
         self.pool = rg.KvPool(ccfg, cfg.dtype, max(1, pages) * page_bytes, page_tokens)
         # poison the slab so that a kernel reading a slot nobody wrote is noticed
-        self.pool.slab.view(torch.int16).fill_(0x7FC1 if cfg.dtype == "bf16" else -1)
+        self.pool.slab.view(torch.int16).fill_(0x7FC1 if cfg.dtype != "fp32" else -1)   # a NaN in bf16 and in fp16
         self.dbatch = rg.Batch(batch, cfg.dtype)
         self.handles = np.zeros(n, dtype=np.uint64)
 

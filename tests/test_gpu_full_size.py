@@ -70,6 +70,11 @@ def test_x2_depth_16_layers():
     run_full("X2", sample_users=[7])
 
 
+def test_x3_fp16():
+    """The half precision the paper mentions (Section 5.2): C3's shape in IEEE fp16."""
+    run_full("X3", sample_users=[9])
+
+
 def test_c5_jagged_batch_with_uncached_users():
     wl = synth.WORKLOADS["C5"]
     L, S, M, cached = synth.make_lengths(wl, 0)

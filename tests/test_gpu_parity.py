@@ -70,6 +70,25 @@ def test_bf16_head_sizes(d, H):
     run_three_routes(synth.ModelConfig(2, d, H, "bf16"), 70 + H, [300, 129], [5, 0], [140, 66])
 
 
+# ------------------------------------------------------------------------------------ fp16
+@pytest.mark.parametrize("L,S,M", [
+    ([1], [0], [1]), ([65, 300], [0, 70], [3, 129]), ([513, 0, 128], [64, 2, 0], [257, 9, 1]), ([1000], [17], [400]),
+])
+def test_fp16_small_shapes(L, S, M):
+    run_three_routes(synth.ModelConfig(3, 128, 2, "fp16"), 160 + len(L), L, S, M)
+
+
+@pytest.mark.parametrize("d,H", [(128, 4), (256, 2), (512, 8), (1024, 8)])
+def test_fp16_head_sizes(d, H):
+    run_three_routes(synth.ModelConfig(2, d, H, "fp16"), 170 + H, [300, 129], [5, 0], [140, 66])
+
+
+def test_fp16_mixed_hits_and_misses_in_one_batch():
+    cfg = synth.ModelConfig(3, 256, 4, "fp16")
+    run_three_routes(cfg, 181, [400, 130, 64, 700, 257], [0, 30, 64, 3, 0], [200, 50, 129, 7, 300],
+                     page_tokens=128, miss=(1, 3))
+
+
 def test_bf16_mixed_hits_and_misses_in_one_batch():
     cfg = synth.ModelConfig(3, 256, 4, "bf16")
     run_three_routes(cfg, 81, [400, 130, 64, 700, 257], [0, 30, 64, 3, 0], [200, 50, 129, 7, 300],
@@ -83,7 +102,7 @@ def test_c2_bf16_full():
 
 
 # ------------------------------------------------------------------- psi, independence, determinism
-@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("dtype", ["fp32", "bf16", "fp16"])
 def test_pool_contents_equal_oracle_psi(dtype):
     """The cached object itself (Section 3.1): every layer's K and V of the prefix."""
     cfg = synth.ModelConfig(3, 128, 2, dtype)
@@ -101,7 +120,7 @@ def test_pool_contents_equal_oracle_psi(dtype):
                     idx = [rg.relaygr_kv_pool_locate(h.pool, int(h.handles[u]), l, t, f) for f in range(cfg.d_model)]
                     gk = el[[i[0] for i in idx]]
                     gv = el[[i[1] for i in idx]]
-                    tol = 1e-5 if dtype == "fp32" else 1e-2
+                    tol = {"fp32": 1e-5, "bf16": 1e-2, "fp16": 1.5e-3}[dtype]
                     np.testing.assert_allclose(gk, k[t].numpy(), rtol=tol, atol=tol * 0.3)
                     np.testing.assert_allclose(gv, v[t].numpy(), rtol=tol, atol=tol * 0.3)
     finally:
