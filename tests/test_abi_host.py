@@ -33,11 +33,15 @@ def test_kv_footprint_matches_papers_table():
     assert rg.relaygr_kv_footprint_bytes(cfg, 8192) == 134217728
     assert rg.relaygr_kv_pool_bytes_for(cfg, 8192, 256) == 134217728
     assert rg.relaygr_kv_pool_bytes_for(cfg, 8193, 256) == 134217728 + 256 * 16384
+    # the two 16-bit storage types take the same space and scratch
+    half = rg.make_config(8, 512, 8, "fp16")
+    assert rg.relaygr_kv_footprint_bytes(half, 8192) == 134217728
+    assert rg.relaygr_scratch_bytes(half, 16, 65536, 8192) == rg.relaygr_scratch_bytes(cfg, 16, 65536, 8192) > 0
 
 
 @pytest.mark.parametrize("bad", [
     dict(n_layers=0), dict(d_model=96), dict(n_heads=3), dict(d_model=512, n_heads=2),
-    dict(dtype="bf16", d_model=64, n_heads=2), dict(ln_eps=0.0),
+    dict(dtype="bf16", d_model=64, n_heads=2), dict(dtype="fp16", d_model=64, n_heads=2), dict(ln_eps=0.0),
 ])
 def test_unsupported_configs_are_rejected(bad):
     kw = dict(n_layers=2, d_model=256, n_heads=4, dtype="bf16", ln_eps=1e-5)
