@@ -226,7 +226,7 @@ __device__ __forceinline__ void attn_step(const uint16_t* __restrict__ khalf, co
 }
 
 template <typename H, int DH, int NQ, int NW>
-__global__ __launch_bounds__(NW * 64, 512 / (NW * 64)) void attn_bf16_kernel(AttnParams p) {
+__global__ __launch_bounds__(NW * 64, (DH * NQ >= 256) ? 1 : 512 / (NW * 64)) void attn_bf16_kernel(AttnParams p) {
   constexpr int KS = DH / 16;              // k-steps of the first product
   constexpr int DB = DH / 32;              // 32-feature blocks of the output
   constexpr int TILE = 2 * kTile * DH;     // elements of one K tile + one V tile

@@ -474,7 +474,10 @@ static int launch_attention16(const relaygr_model_config& cfg, const AttnParams&
       if (nq == 2) hipLaunchKernelGGL((attn_bf16_kernel<H, 64, 2, 4>), grid, dim3(256), 0, st, ap);
       else hipLaunchKernelGGL((attn_bf16_kernel<H, 64, 1, 4>), grid, dim3(256), 0, st, ap);
       break;
-    case 128: hipLaunchKernelGGL((attn_bf16_kernel<H, 128, 1, 4>), grid, dim3(256), 0, st, ap); break;
+    case 128:
+      if (nq == 2) hipLaunchKernelGGL((attn_bf16_kernel<H, 128, 2, 4>), grid, dim3(256), 0, st, ap);
+      else hipLaunchKernelGGL((attn_bf16_kernel<H, 128, 1, 4>), grid, dim3(256), 0, st, ap);
+      break;
     default: return fail(RELAYGR_EINVAL, "attention: unsupported d_head");
   }
   LAUNCH_CHECK("attn (16-bit)");
@@ -573,7 +576,7 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
   // with 256-row items (two row blocks per wavefront); use them when that still yields at least
   // one workgroup per compute unit.
   int nq = 1;
-  if (bf16 && dh == 64) {
+  if (bf16 && (dh == 64 || dh == 128)) {
     int64_t items256 = 0;
     for (int u = 0; u < n; ++u) {
       if (users[u].nrow0 >= 0) items256 += (users[u].S + users[u].M + 255) / 256;
