@@ -35,8 +35,10 @@
  *     memory; it owns host-side metadata and a small pinned staging area.
  *   - Compute calls enqueue work on the given HIP stream and return without
  *     synchronising.  Buffers passed to a call must stay valid and unmodified
- *     until that stream has passed the call's work.  A context must not be used
- *     from two streams at once (its scratch buffer is shared by its calls).
+ *     until that stream has passed the call's work.  A context is one model slot:
+ *     it must not be used from two streams or two threads at once (its scratch
+ *     buffer and staging area are shared by its calls); several contexts may share
+ *     one pool, whose calls (and the expander's and trigger's) are thread-safe.
  *   - Every function returning int returns RELAYGR_OK or a negative code; the
  *     text of the last failure on the calling thread is relaygr_last_error().
  *   - dtype selects storage AND arithmetic: RELAYGR_DTYPE_FP32 keeps everything
