@@ -8,7 +8,10 @@ array version shows up as a mismatch on tiny inputs.  Only practical for a few
 dozen tokens.
 
 Sequence: [prefix | suffix | candidates] (Section 2.3).  Token i may use key j
-when j <= i and j is not another candidate.
+when j <= i and j is not another candidate.  With cfg.attention == "softmax"
+(the reading of the backbone variant of Section 5.4) the weight of key j is
+exp(alpha q.k_j) over the sum of the same over the visible keys, instead of
+SiLU(alpha q.k_j) / n_i.
 """
 from __future__ import annotations
 
@@ -39,6 +42,7 @@ def brute_force_scores(cfg, weights: dict, prefix, suffix, cands) -> List[float]
     dh = d // H
     alpha = 1.0 / math.sqrt(dh)
     eps = cfg.ln_eps
+    softmax = getattr(cfg, "attention", "silu") == "softmax"
     rows = [[float(t) for t in r] for seg in (prefix, suffix, cands) for r in seg]
     L, S, M = len(prefix), len(suffix), len(cands)
     N = L + S + M
@@ -68,11 +72,18 @@ def brute_force_scores(cfg, weights: dict, prefix, suffix, cands) -> List[float]
             o = [0.0] * d
             for h in range(H):
                 lo = h * dh
+                dots = []
                 for j in keys:
                     dot = 0.0
                     for f in range(lo, lo + dh):
                         dot += q[i][f] * k[j][f]
-                    a = _silu(alpha * dot) / n_i
+                    dots.append(alpha * dot)
+                if softmax:
+                    total = sum(math.exp(t) for t in dots)
+                    wts = [math.exp(t) / total for t in dots]
+                else:
+                    wts = [_silu(t) / n_i for t in dots]
+                for j, a in zip(keys, wts):
                     for f in range(lo, lo + dh):
                         o[f] += a * v[j][f]
             y = _layer_norm(o, lw["ln_at_g"], lw["ln_at_b"], eps)

@@ -36,6 +36,17 @@ Under this mask row i < L of every layer depends on p_0..p_i only, so the
 prefix K/V are candidate-independent and the identity holds with zero deviation
 in exact arithmetic.
 
+Second attention form.  Section 5.4 evaluates a variant of the backbone that
+differs from the first only in how attention is computed and gives no formula
+for it.  The reading used here (cfg.attention == "softmax") replaces the
+pointwise activation and the 1/n_i by a softmax over the visible keys,
+
+              a_ij^h          = m_ij exp(alpha <q_i^h, k_j^h>) / sum_j' m_ij' exp(alpha <q_i^h, k_j'^h>)
+
+with everything else (projections, mask, gate, residual, head, and therefore
+the cached K/V) unchanged.  The mask alone makes psi candidate-independent, so
+the relay-race identity holds for this form too.
+
 All arithmetic is float64 with no intermediate rounding; inputs arrive already
 rounded to their storage type by the input generator.
 """
@@ -103,17 +114,43 @@ def _attend(q, k_all, v_all, mask, n_heads: int, alpha: float) -> torch.Tensor:
     return o
 
 
+def _attend_softmax(q, k_all, v_all, mask, n_heads: int, alpha: float) -> torch.Tensor:
+    """Step 3 in the second form: o_i^h = sum_j softmax_j(alpha <q_i^h, k_j^h> over visible j) v_j^h.
+
+    Same arguments as _attend.  Every row must see at least one key (each token
+    sees itself under the visibility rule).
+    """
+    R, d = q.shape
+    dh = d // n_heads
+    o = torch.empty((R, d), dtype=_F64)
+    for h in range(n_heads):
+        c = slice(h * dh, (h + 1) * dh)
+        s = alpha * (q[:, c] @ k_all[:, c].T)
+        s = torch.where(mask, s, torch.full_like(s, -math.inf))
+        e = torch.exp(s - s.max(dim=1, keepdim=True).values)     # invisible keys: exp(-inf) = 0
+        o[:, c] = (e / e.sum(dim=1, keepdim=True)) @ v_all[:, c]
+    return o
+
+
+def _attention_of(cfg):
+    form = getattr(cfg, "attention", "silu")
+    if form not in ("silu", "softmax"):
+        raise ValueError(f"unknown attention form {form!r}")
+    return form
+
+
 def _finish_layer(x, o, u, lw: dict, eps: float) -> torch.Tensor:
     """Step 4: gated, normalised attention output through W2, plus the residual."""
     y = layer_norm(o, _t(lw["ln_at_g"]), _t(lw["ln_at_b"]), eps) * u
     return x + y @ _t(lw["w2"]).T + _t(lw["b2"])
 
 
-def backbone_layer(x: torch.Tensor, lw: dict, mask: torch.Tensor, n_heads: int, alpha: float, eps: float):
+def backbone_layer(x: torch.Tensor, lw: dict, mask: torch.Tensor, n_heads: int, alpha: float, eps: float,
+                   form: str = "silu"):
     """One layer over a whole sequence; returns (new x, k, v)."""
     d = x.shape[1]
     u, v, q, k = _project(x, lw, eps, d)
-    o = _attend(q, k, v, mask, n_heads, alpha)
+    o = (_attend_softmax if form == "softmax" else _attend)(q, k, v, mask, n_heads, alpha)
     return _finish_layer(x, o, u, lw, eps), k, v
 
 
@@ -135,8 +172,9 @@ def full_recompute(cfg, weights: dict, prefix, suffix, cands) -> np.ndarray:
     x = torch.cat([prefix, suffix, cands], dim=0)
     mask = visibility_mask(L, S, M)
     alpha = 1.0 / math.sqrt(d // cfg.n_heads)
+    form = _attention_of(cfg)
     for lw in weights["layers"]:
-        x, _, _ = backbone_layer(x, lw, mask, cfg.n_heads, alpha, cfg.ln_eps)
+        x, _, _ = backbone_layer(x, lw, mask, cfg.n_heads, alpha, cfg.ln_eps, form)
     return score_head(x[L + S:], weights, cfg.ln_eps).numpy()
 
 
@@ -148,8 +186,9 @@ def prefix_kv(cfg, weights: dict, prefix) -> List[Tuple[torch.Tensor, torch.Tens
     mask = visibility_mask(L, 0, 0)
     alpha = 1.0 / math.sqrt(d // cfg.n_heads)
     psi = []
+    form = _attention_of(cfg)
     for lw in weights["layers"]:
-        x, k, v = backbone_layer(x, lw, mask, cfg.n_heads, alpha, cfg.ln_eps)
+        x, k, v = backbone_layer(x, lw, mask, cfg.n_heads, alpha, cfg.ln_eps, form)
         psi.append((k, v))
     return psi
 
@@ -168,9 +207,11 @@ def rank_with_kv(cfg, weights: dict, psi: Sequence[Tuple[torch.Tensor, torch.Ten
     x = torch.cat([suffix, cands], dim=0)
     mask = visibility_mask(L, S, M)[L:, :]
     alpha = 1.0 / math.sqrt(d // cfg.n_heads)
+    form = _attention_of(cfg)
     for lw, (kp, vp) in zip(weights["layers"], psi):
         u, v, q, k = _project(x, lw, cfg.ln_eps, d)
-        o = _attend(q, torch.cat([kp, k], dim=0), torch.cat([vp, v], dim=0), mask, cfg.n_heads, alpha)
+        o = (_attend_softmax if form == "softmax" else _attend)(
+            q, torch.cat([kp, k], dim=0), torch.cat([vp, v], dim=0), mask, cfg.n_heads, alpha)
         x = _finish_layer(x, o, u, lw, cfg.ln_eps)
     return score_head(x[S:], weights, cfg.ln_eps).numpy()
 

@@ -115,6 +115,7 @@ class ModelConfig:
     n_heads: int
     dtype: str  # "fp32", "bf16" or "fp16": storage type of weights, embeddings and cached K/V
     ln_eps: float = 1e-5
+    attention: str = "silu"  # "silu": pointwise SiLU attention; "softmax": the second attention form
 
     @property
     def d_head(self) -> int:
@@ -164,6 +165,10 @@ WORKLOADS: Dict[str, Workload] = {
                    prefix_len=4096, n_cands=512, n_suffix=0),
     # the half precision the paper mentions as lowering the rank stage (Section 5.2): C3 in IEEE fp16
     "X3": Workload("X3", ModelConfig(8, 512, 8, "fp16"), seed=8, n_users=16,
+                   prefix_len=4096, n_cands=512, n_suffix=0),
+    # the backbone variant that differs only in its attention computation (Section 5.4): C3 with
+    # softmax attention over the visible keys
+    "X4": Workload("X4", ModelConfig(8, 512, 8, "bf16", attention="softmax"), seed=9, n_users=16,
                    prefix_len=4096, n_cands=512, n_suffix=0),
 }
 
