@@ -42,6 +42,7 @@ WORKLOAD_TEXT = {
     "X1": "X1 (width axis): bf16, 8 layers, d=1024, 8 heads; 16 users x (prefix 4096, 512 candidates)",
     "X2": "X2 (depth axis): bf16, 16 layers, d=512, 8 heads; 16 users x (prefix 4096, 512 candidates)",
     "X3": "X3 (half precision): fp16, 8 layers, d=512, 8 heads; 16 users x (prefix 4096, 512 candidates)",
+    "X4": "X4 (second attention form: softmax over the visible keys): bf16, 8 layers, d=512, 8 heads; 16 users x (prefix 4096, 512 candidates)",
 }
 
 
@@ -178,7 +179,7 @@ def main() -> int:
     if args.batches is None:
         args.batches = 8 if args.config == "C5" else 1
     if args.full_steps is None:
-        args.full_steps = 100 if args.config in ("C1", "C2", "C3", "X3") else 20
+        args.full_steps = 100 if args.config in ("C1", "C2", "C3", "X3", "X4") else 20
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (users shard by hash across GPUs with no "
               "collective; see DESIGN.md); run with --gpus 1", file=sys.stderr)

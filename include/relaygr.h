@@ -145,6 +145,20 @@ int  relaygr_ctx_create(const relaygr_model_config* cfg, const relaygr_weights* 
                         void* scratch_dev, size_t scratch_bytes, relaygr_ctx** out);
 void relaygr_ctx_destroy(relaygr_ctx* ctx);
 
+/* Attention form of a context's backbone.  The paper evaluates a second backbone that differs
+ * from the first only in its attention computation (Section 5.4) and gives no formula for it;
+ * this library's reading of it is a softmax over the visible keys,
+ *   o_i^h = sum_j m_ij exp(alpha <q_i^h, k_j^h>) v_j^h / sum_j m_ij exp(alpha <q_i^h, k_j^h>),
+ * in place of sum_j m_ij SiLU(alpha <q_i^h, k_j^h>) v_j^h / n_i; projections, visibility, gate,
+ * residual, score head and therefore the cached K/V layout are the same.  A new context uses
+ * RELAYGR_ATTN_SILU.  The form holds for every later call on the context; psi written under
+ * one form is not meaningful under the other (layers above the first see different inputs).
+ * Rows attend in fp32 with a running maximum, so large scores do not overflow.
+ * Returns RELAYGR_EINVAL for a null context or an unknown form. */
+#define RELAYGR_ATTN_SILU    0
+#define RELAYGR_ATTN_SOFTMAX 1
+int  relaygr_ctx_set_attention(relaygr_ctx* ctx, int32_t form);
+
 /* ---- HBM pool of psi objects (Section 3.3, "HBM as a lifecycle window") -------------- */
 
 /* Creates an allocator over slab_dev (device, 256-byte aligned, slab_bytes long) for models of

@@ -24,7 +24,7 @@ RELAYGR_TILE_TOKENS = 64
 
 EXPORTS = [
     "relaygr_kv_footprint_bytes", "relaygr_kv_pool_bytes_for", "relaygr_scratch_bytes",
-    "relaygr_ctx_create", "relaygr_ctx_destroy",
+    "relaygr_ctx_create", "relaygr_ctx_destroy", "relaygr_ctx_set_attention",
     "relaygr_kv_pool_create", "relaygr_kv_pool_destroy", "relaygr_kv_pool_alloc", "relaygr_kv_pool_free",
     "relaygr_kv_pool_lookup", "relaygr_kv_pool_entry_len", "relaygr_kv_pool_stats", "relaygr_kv_pool_locate",
     "relaygr_prefill_prefix", "relaygr_rank_with_cache", "relaygr_rank_full_recompute",
@@ -116,6 +116,7 @@ def load_library() -> C.CDLL:
         "relaygr_rank_full_recompute": (C.c_int, [vp, P(BatchC), vp, vp]),
         "relaygr_ctx_profile_enable": (C.c_int, [vp, C.c_uint32]),
         "relaygr_ctx_profile_sample": (C.c_int, [vp, i32]),
+        "relaygr_ctx_set_attention": (C.c_int, [vp, i32]),
         "relaygr_ctx_profile_read": (C.c_int, [vp, i32, P(C.c_double), P(i64)]),
         "relaygr_kv_pool_entry_bytes": (sz, [vp, u64]),
         "relaygr_kv_pool_spill": (C.c_int, [vp, u64, vp, sz, vp]),
@@ -216,6 +217,9 @@ class Context:
         h = C.c_void_p()
         _check(lib.relaygr_ctx_create(C.byref(self.cfg), C.byref(wc), self.scratch.data_ptr(), nbytes, C.byref(h)))
         self.handle = h
+        form = getattr(model_cfg, "attention", "silu")
+        if form != "silu":
+            relaygr_ctx_set_attention(self, form)
 
     def close(self):
         if getattr(self, "handle", None):
@@ -228,6 +232,16 @@ class Context:
             self.close()
         except Exception:
             pass
+
+
+ATTENTION_FORMS = {"silu": 0, "softmax": 1}
+
+
+def relaygr_ctx_set_attention(ctx: Context, form: str) -> None:
+    """Selects the context's attention form: "silu" (pointwise SiLU, the default) or "softmax"."""
+    if form not in ATTENTION_FORMS:
+        raise RelayGRError(RELAYGR_EINVAL, f"unknown attention form {form!r}")
+    _check(load_library().relaygr_ctx_set_attention(ctx.handle, ATTENTION_FORMS[form]))
 
 
 def relaygr_ctx_profile_enable(ctx: Context, classes: Sequence[str]) -> None:

@@ -5,6 +5,12 @@
 // workgroups needs no renormalisation -- partial sums are added later in fixed split order, the
 // candidate's self term and the 1/n_i are applied there too.
 //
+// Second form (SOFTMAX template flag; the backbone variant of Section 5.4 read as a softmax over
+// the visible keys): the kernels produce, per row, head and key split, a reference score m, the
+// sum l of exp(s_j - m) over the split's visible keys and the sum of exp(s_j - m) v_j; m is a
+// running maximum, so nothing overflows, and the splits and the candidate's own key are merged
+// afterwards by softmax_combine_kernel (rowwise.h).
+//
 // Keys come in tiles of 64 tokens (layout in common.h): a K tile [64][dh] followed by a V tile
 // stored transposed [dh][64].  Prefix tiles come from the user's K/V space (pool or scratch),
 // suffix tiles from the suffix scratch space.  Only three kinds of tile need a per-element
@@ -25,6 +31,8 @@ struct AttnParams {
   const void* sfx;    // suffix K/V space (single layer)
   float* part;        // [nsplit][rows][d]
   size_t split_stride;
+  float* ml;          // softmax form: [nsplit][rows][n_heads][2] = (m, l) of each row, head and split
+  size_t ml_stride;   // floats between the (m, l) tables of consecutive splits
   int nsplit;
   int n_tiles;        // work items in this launch
   int d, n_heads, layer;
@@ -58,7 +66,7 @@ __device__ __forceinline__ TileRange tile_range(const AttnTile& at, const UserDe
 }
 
 // ---- fp32 kernel: one thread per row, keys broadcast from LDS -----------------------------------
-template <int DH>
+template <int DH, bool SOFTMAX>
 __global__ __launch_bounds__(64) void attn_f32_kernel(AttnParams p) {
   __shared__ float Ks[kTile * DH];
   __shared__ float Vs[DH * kTile];
@@ -75,6 +83,7 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(AttnParams p) {
   const float* qrow = reinterpret_cast<const float*>(p.q) + (size_t)row * p.d + head * DH;
 #pragma unroll
   for (int f = 0; f < DH; ++f) { qv[f] = qrow[f] * p.score_mul; o[f] = 0.f; }
+  float m = -INFINITY, l = 0.f;   // softmax form: running maximum and sum of exp(s - m)
 
   for (int tt = tr.t0; tt < tr.t1; ++tt) {
     const bool is_sfx = tt >= tr.nkp;
@@ -98,7 +107,20 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(AttnParams p) {
       float s = 0.f;
 #pragma unroll
       for (int f = 0; f < DH; ++f) s = fmaf(qv[f], Ks[j * DH + f], s);
-      float pj = (j < vis) ? silu_f32(s) : 0.f;
+      float pj;
+      if constexpr (SOFTMAX) {
+        if (j < vis && s > m) {        // new maximum: bring what was summed so far to the new reference
+          const float c = __expf(m - s);
+          l *= c;
+#pragma unroll
+          for (int f = 0; f < DH; ++f) o[f] *= c;
+          m = s;
+        }
+        pj = (j < vis) ? __expf(s - m) : 0.f;
+        l += pj;
+      } else {
+        pj = (j < vis) ? silu_f32(s) : 0.f;
+      }
 #pragma unroll
       for (int f = 0; f < DH; ++f) o[f] = fmaf(pj, Vs[f * kTile + j], o[f]);
     }
@@ -107,6 +129,10 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(AttnParams p) {
     float* dst = p.part + split * p.split_stride + (size_t)row * p.d + head * DH;
 #pragma unroll
     for (int f = 0; f < DH; ++f) dst[f] = o[f];
+    if constexpr (SOFTMAX) {
+      float* mlp = p.ml + split * p.ml_stride + ((size_t)row * p.n_heads + head) * 2;
+      mlp[0] = m; mlp[1] = l;
+    }
   }
 }
 
@@ -170,11 +196,12 @@ __device__ __forceinline__ void attn_pv_half(const uint16_t* __restrict__ vhalf,
 // previous one, so MFMAs placed back to back would leave the vector ALU idle behind them.  The
 // step is therefore cut into slots -- the SiLU of 128/DH score elements per row block, then NQ
 // MFMAs that take about as long -- and the scheduler is fenced between slots.
-template <typename H, int DH, int NQ, bool MASKED>
+template <typename H, int DH, int NQ, bool MASKED, bool SOFTMAX>
 __device__ __forceinline__ void attn_step(const uint16_t* __restrict__ khalf, const uint16_t* __restrict__ vhalf,
                                           const uint4 (&qf)[NQ][DH / 16], const f32x16_t (&s_in)[NQ], f32x16_t (&s_out)[NQ],
                                           const uint32_t (&pk_in)[NQ][8], uint32_t (&pk_out)[NQ][8],
-                                          f32x16_t (&oacc)[DH / 32][NQ], const int (&vis)[NQ]) {
+                                          f32x16_t (&oacc)[DH / 32][NQ], const int (&vis)[NQ],
+                                          const float (&mref)[NQ], float (&lsum)[NQ]) {
   constexpr int KS = DH / 16, DB = DH / 32;
   constexpr int SLOTS = KS + 2 * DB;      // = DH / 8
   constexpr int EPS = 16 / SLOTS > 0 ? 16 / SLOTS : 1;   // score elements per row block and slot
@@ -197,8 +224,11 @@ __device__ __forceinline__ void attn_step(const uint16_t* __restrict__ khalf, co
 #pragma unroll
       for (int e = slot * EPS; e < (slot + 1) * EPS; ++e) {
         const float t = s_in[qb][e];
-        float pe = t * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-t));
+        float pe;
+        if constexpr (SOFTMAX) pe = __builtin_amdgcn_exp2f(t - mref[qb]);
+        else pe = t * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-t));
         if (MASKED) pe = (8 * (e >> 2) + (e & 3) < vis[qb]) ? pe : 0.f;
+        if constexpr (SOFTMAX) lsum[qb] += pe;
         pv[qb][e] = pe;
         if (e & 1) {
           f32x2_t two = {pv[qb][e - 1], pv[qb][e]};
@@ -225,7 +255,52 @@ __device__ __forceinline__ void attn_step(const uint16_t* __restrict__ khalf, co
   }
 }
 
-template <typename H, int DH, int NQ, int NW>
+// Softmax form: keeps each row's reference score m (in log2 units, like the stored q) within
+// kSoftmaxSlack of the largest visible score seen so far, so that exp2(t - m) <= 2^kSoftmaxSlack fits
+// either 16-bit type.  Called before the step that exponentiates the half tile s: when no lane
+// holds a score above m + slack (the common case after the first half tile) nothing happens.
+// Otherwise, for the whole wavefront: the second product still owed from the preceding half
+// (computed against the old references) is issued now and its P cleared, then m rises to the
+// running maximum -- the two lanes of a row (l32, g = 0 and 1) exchange theirs, a row has one m --
+// and the sums gathered so far are scaled by 2^(m_old - m_new).
+constexpr float kSoftmaxSlack = 8.0f;
+
+template <typename H, int DH, int NQ, bool MASKED>
+__device__ __forceinline__ void softmax_track(const f32x16_t (&s)[NQ], const int (&vis)[NQ], float (&mref)[NQ], float (&lsum)[NQ],
+                                              f32x16_t (&oacc)[DH / 32][NQ], uint32_t (&pk_owed)[NQ][8],
+                                              const uint16_t* __restrict__ v_owed) {
+  float mx[NQ];
+  bool need = false;
+#pragma unroll
+  for (int qb = 0; qb < NQ; ++qb) {
+    mx[qb] = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      float t = s[qb][e];
+      if (MASKED) t = (8 * (e >> 2) + (e & 3) < vis[qb]) ? t : -INFINITY;
+      mx[qb] = fmaxf(mx[qb], t);
+    }
+    need |= mx[qb] > mref[qb] + kSoftmaxSlack;
+  }
+  if (__builtin_amdgcn_ballot_w64(need) == 0) return;
+  attn_pv_half<H, DH, NQ>(v_owed, pk_owed, oacc);
+#pragma unroll
+  for (int qb = 0; qb < NQ; ++qb) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) pk_owed[qb][e] = 0u;
+    const float both = fmaxf(mx[qb], __shfl_xor(mx[qb], 32, 64));
+    const float mn = fmaxf(mref[qb], both);
+    const float c = (mn == mref[qb]) ? 1.0f : __builtin_amdgcn_exp2f(mref[qb] - mn);   // from -inf: 0
+    mref[qb] = mn;
+    lsum[qb] *= c;
+#pragma unroll
+    for (int db = 0; db < DH / 32; ++db)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) oacc[db][qb][e] *= c;
+  }
+}
+
+template <typename H, int DH, int NQ, int NW, bool SOFTMAX>
 __global__ __launch_bounds__(NW * 64, (DH * NQ >= 256) ? 1 : 512 / (NW * 64)) void attn_bf16_kernel(AttnParams p) {
   constexpr int KS = DH / 16;              // k-steps of the first product
   constexpr int DB = DH / 32;              // 32-feature blocks of the output
@@ -271,6 +346,9 @@ __global__ __launch_bounds__(NW * 64, (DH * NQ >= 256) ? 1 : 512 / (NW * 64)) vo
     for (int qb = 0; qb < NQ; ++qb)
 #pragma unroll
       for (int e = 0; e < 16; ++e) oacc[db][qb][e] = 0.f;
+  float mref[NQ], lsum[NQ];   // softmax form: reference score of the row, this lane's sum of exp2(t - m)
+#pragma unroll
+  for (int qb = 0; qb < NQ; ++qb) { mref[qb] = -INFINITY; lsum[qb] = 0.f; }
 
   const uint16_t* kv_base = reinterpret_cast<const uint16_t*>(ud.kv) + ud.kv_tile0 + (int64_t)p.layer * ud.kv_layer_stride +
                             (int64_t)head * TILE;
@@ -328,7 +406,10 @@ __global__ __launch_bounds__(NW * 64, (DH * NQ >= 256) ? 1 : 512 / (NW * 64)) vo
       const uint16_t* kt = &bufs[b][lane * 8];
       const uint16_t* vt = kt + kTile * DH;
       // step 1: SiLU of the first half | first product of the second half, second product owed from before
-      if (wave_active) attn_step<H, DH, NQ, MASKED>(kt + KS * 512, vprev, qf, s_cur, s_nxt, pk_b, pk_a, oacc, vis);
+      if (wave_active) {
+        if constexpr (SOFTMAX) softmax_track<H, DH, NQ, MASKED>(s_cur, vis, mref, lsum, oacc, pk_b, vprev);
+        attn_step<H, DH, NQ, MASKED, SOFTMAX>(kt + KS * 512, vprev, qf, s_cur, s_nxt, pk_b, pk_a, oacc, vis, mref, lsum);
+      }
       // the next tile must have landed before its first product; every wavefront is now past tile i-1
       const int bn = (b == 2) ? 0 : b + 1;
       const bool more = i + 1 < nt;
@@ -343,7 +424,10 @@ __global__ __launch_bounds__(NW * 64, (DH * NQ >= 256) ? 1 : 512 / (NW * 64)) vo
 #pragma unroll
         for (int qb = 0; qb < NQ; ++qb) vis[qb] -= 32;
       }
-      if (wave_active) attn_step<H, DH, NQ, MASKED>(more ? &bufs[bn][lane * 8] : kt, vt, qf, s_nxt, s_cur, pk_a, pk_b, oacc, vis);
+      if (wave_active) {
+        if constexpr (SOFTMAX) softmax_track<H, DH, NQ, MASKED>(s_nxt, vis, mref, lsum, oacc, pk_a, vt);
+        attn_step<H, DH, NQ, MASKED, SOFTMAX>(more ? &bufs[bn][lane * 8] : kt, vt, qf, s_nxt, s_cur, pk_a, pk_b, oacc, vis, mref, lsum);
+      }
       vprev = vt + 2 * 512;
       b = bn;
     };
@@ -357,11 +441,21 @@ __global__ __launch_bounds__(NW * 64, (DH * NQ >= 256) ? 1 : 512 / (NW * 64)) vo
   }
 
   // element e of oacc[db][qb]: feature db*32 + 8*(e/4) + 4*g + e%4, row l32 of block qb
-  const float kLn2 = 0.69314718055994531f;
+  const float kLn2 = SOFTMAX ? 1.0f : 0.69314718055994531f;
+  if constexpr (SOFTMAX) {   // a row's sum is spread over its two lanes
+#pragma unroll
+    for (int qb = 0; qb < NQ; ++qb) lsum[qb] += __shfl_xor(lsum[qb], 32, 64);
+  }
 #pragma unroll
   for (int qb = 0; qb < NQ; ++qb) {
     int lr = wave * 32 * NQ + qb * 32 + l32;
     if (lr >= at.nrows) continue;
+    if constexpr (SOFTMAX) {
+      if (g == 0) {
+        float* mlp = p.ml + split * p.ml_stride + ((size_t)(at.row0 + lr) * p.n_heads + head) * 2;
+        *reinterpret_cast<float2*>(mlp) = make_float2(mref[qb], lsum[qb]);
+      }
+    }
     float* dst = p.part + split * p.split_stride + (size_t)(at.row0 + lr) * p.d + head * DH;
 #pragma unroll
     for (int db = 0; db < DB; ++db)

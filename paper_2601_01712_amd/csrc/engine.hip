@@ -87,7 +87,7 @@ struct Plan {
   int n_tiles_new = 0, n_tiles_prefix = 0;
   int nsplit = 1;
   // byte offsets into scratch
-  size_t off_x, off_xh, off_u, off_q, off_knew, off_vnew, off_sfx, off_kvs, off_part, off_rows, off_blob;
+  size_t off_x, off_xh, off_u, off_q, off_knew, off_vnew, off_sfx, off_kvs, off_part, off_ml, off_rows, off_blob;
   size_t blob_bytes = 0;
   size_t total = 0;
 };
@@ -121,6 +121,7 @@ static void carve(const relaygr_model_config& c, Plan& p) {
   p.off_sfx = take((size_t)p.sfx_tiles * 2 * kTile * d * e);
   p.off_kvs = take((size_t)p.kvs_tiles * 2 * kTile * d * e);
   p.off_part = take((size_t)p.nsplit * R * d * 4);
+  p.off_ml = take((size_t)p.nsplit * R * c.n_heads * 2 * 4);   // softmax form: (m, l) per row, head and split
   p.off_rows = take(5 * align_up(R * 4));
   size_t n_tiles = (size_t)p.n_tiles_new + p.n_tiles_prefix;
   p.blob_bytes = align_up((size_t)p.n_users * sizeof(UserDesc)) + 2 * align_up((size_t)(p.n_users + 1) * 4) +
@@ -161,7 +162,7 @@ extern "C" size_t relaygr_scratch_bytes(const relaygr_model_config* cfg, int32_t
   size_t base = p.total;
   // head-room so that small calls may split their key range 8 ways
   size_t small_rows = std::min<size_t>((size_t)p.n_rows, 8192);
-  return base + align_up(small_rows * 7 * (size_t)cfg->d_model * 4);
+  return base + align_up(small_rows * 7 * ((size_t)cfg->d_model * 4 + (size_t)cfg->n_heads * 8));
 }
 
 // ---- context ----------------------------------------------------------------------------------
@@ -184,6 +185,7 @@ struct relaygr_ctx {
   double prof_ms[RELAYGR_K_COUNT] = {};
   int64_t prof_n[RELAYGR_K_COUNT] = {};
   relaygr_model_config cfg;
+  int attn_form = RELAYGR_ATTN_SILU;
   std::vector<relaygr_layer_weights> layers;
   const void *ln_out_g, *ln_out_b, *w_score;
   float b_score;
@@ -233,6 +235,13 @@ extern "C" int relaygr_ctx_create(const relaygr_model_config* cfg, const relaygr
     if (e != hipSuccess) { delete c; return fail(RELAYGR_EHIP, "ctx_create: packing weights: %s", hipGetErrorString(e)); }
   }
   *out = c;
+  return RELAYGR_OK;
+}
+
+extern "C" int relaygr_ctx_set_attention(relaygr_ctx* c, int32_t form) {
+  if (!c) return fail(RELAYGR_EINVAL, "ctx_set_attention: null context");
+  if (form != RELAYGR_ATTN_SILU && form != RELAYGR_ATTN_SOFTMAX) return fail(RELAYGR_EINVAL, "ctx_set_attention: unknown form %d", form);
+  c->attn_form = form;
   return RELAYGR_OK;
 }
 
@@ -449,34 +458,38 @@ template <> struct GemmLaunch<__half> {
 };
 
 template <typename T>
-static int launch_attention(const relaygr_model_config& cfg, const AttnParams& ap, int n_tiles, int nq, hipStream_t st);
+static int launch_attention(const relaygr_model_config& cfg, const AttnParams& ap, int n_tiles, int nq, bool softmax, hipStream_t st);
 
-template <>
-int launch_attention<float>(const relaygr_model_config& cfg, const AttnParams& ap, int n_tiles, int, hipStream_t st) {
+template <bool SM>
+static int launch_attention_f32(const relaygr_model_config& cfg, const AttnParams& ap, int n_tiles, hipStream_t st) {
   dim3 grid(n_tiles, cfg.n_heads, ap.nsplit);
   switch (cfg.d_model / cfg.n_heads) {
-    case 32: hipLaunchKernelGGL((attn_f32_kernel<32>), grid, dim3(64), 0, st, ap); break;
-    case 64: hipLaunchKernelGGL((attn_f32_kernel<64>), grid, dim3(64), 0, st, ap); break;
-    case 128: hipLaunchKernelGGL((attn_f32_kernel<128>), grid, dim3(64), 0, st, ap); break;
+    case 32: hipLaunchKernelGGL((attn_f32_kernel<32, SM>), grid, dim3(64), 0, st, ap); break;
+    case 64: hipLaunchKernelGGL((attn_f32_kernel<64, SM>), grid, dim3(64), 0, st, ap); break;
+    case 128: hipLaunchKernelGGL((attn_f32_kernel<128, SM>), grid, dim3(64), 0, st, ap); break;
     default: return fail(RELAYGR_EINVAL, "attention: unsupported d_head");
   }
   LAUNCH_CHECK("attn_f32");
   return RELAYGR_OK;
 }
+template <>
+int launch_attention<float>(const relaygr_model_config& cfg, const AttnParams& ap, int n_tiles, int, bool softmax, hipStream_t st) {
+  return softmax ? launch_attention_f32<true>(cfg, ap, n_tiles, st) : launch_attention_f32<false>(cfg, ap, n_tiles, st);
+}
 
-template <typename H>
+template <typename H, bool SM>
 static int launch_attention16(const relaygr_model_config& cfg, const AttnParams& ap, int n_tiles, int nq, hipStream_t st) {
   int total = n_tiles * cfg.n_heads * ap.nsplit;
   dim3 grid((total + 7) / 8 * 8);
   switch (cfg.d_model / cfg.n_heads) {
-    case 32: hipLaunchKernelGGL((attn_bf16_kernel<H, 32, 1, 4>), grid, dim3(256), 0, st, ap); break;
+    case 32: hipLaunchKernelGGL((attn_bf16_kernel<H, 32, 1, 4, SM>), grid, dim3(256), 0, st, ap); break;
     case 64:
-      if (nq == 2) hipLaunchKernelGGL((attn_bf16_kernel<H, 64, 2, 4>), grid, dim3(256), 0, st, ap);
-      else hipLaunchKernelGGL((attn_bf16_kernel<H, 64, 1, 4>), grid, dim3(256), 0, st, ap);
+      if (nq == 2) hipLaunchKernelGGL((attn_bf16_kernel<H, 64, 2, 4, SM>), grid, dim3(256), 0, st, ap);
+      else hipLaunchKernelGGL((attn_bf16_kernel<H, 64, 1, 4, SM>), grid, dim3(256), 0, st, ap);
       break;
     case 128:
-      if (nq == 2) hipLaunchKernelGGL((attn_bf16_kernel<H, 128, 2, 4>), grid, dim3(256), 0, st, ap);
-      else hipLaunchKernelGGL((attn_bf16_kernel<H, 128, 1, 4>), grid, dim3(256), 0, st, ap);
+      if (nq == 2) hipLaunchKernelGGL((attn_bf16_kernel<H, 128, 2, 4, SM>), grid, dim3(256), 0, st, ap);
+      else hipLaunchKernelGGL((attn_bf16_kernel<H, 128, 1, 4, SM>), grid, dim3(256), 0, st, ap);
       break;
     default: return fail(RELAYGR_EINVAL, "attention: unsupported d_head");
   }
@@ -484,12 +497,12 @@ static int launch_attention16(const relaygr_model_config& cfg, const AttnParams&
   return RELAYGR_OK;
 }
 template <>
-int launch_attention<__hip_bfloat16>(const relaygr_model_config& cfg, const AttnParams& ap, int n_tiles, int nq, hipStream_t st) {
-  return launch_attention16<Bf16>(cfg, ap, n_tiles, nq, st);
+int launch_attention<__hip_bfloat16>(const relaygr_model_config& cfg, const AttnParams& ap, int n_tiles, int nq, bool softmax, hipStream_t st) {
+  return softmax ? launch_attention16<Bf16, true>(cfg, ap, n_tiles, nq, st) : launch_attention16<Bf16, false>(cfg, ap, n_tiles, nq, st);
 }
 template <>
-int launch_attention<__half>(const relaygr_model_config& cfg, const AttnParams& ap, int n_tiles, int nq, hipStream_t st) {
-  return launch_attention16<F16>(cfg, ap, n_tiles, nq, st);
+int launch_attention<__half>(const relaygr_model_config& cfg, const AttnParams& ap, int n_tiles, int nq, bool softmax, hipStream_t st) {
+  return softmax ? launch_attention16<F16, true>(cfg, ap, n_tiles, nq, st) : launch_attention16<F16, false>(cfg, ap, n_tiles, nq, st);
 }
 
 static int check_offsets(const int32_t* off, int n, const char* what) {
@@ -634,6 +647,8 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
   T* sfx = (T*)(S0 + p.off_sfx);
   T* kvs = (T*)(S0 + p.off_kvs);
   float* part = (float*)(S0 + p.off_part);
+  float* ml = (float*)(S0 + p.off_ml);
+  const bool softmax = c->attn_form == RELAYGR_ATTN_SOFTMAX;
   RowTables rt;
   {
     size_t rb = align_up((size_t)p.n_rows * 4);
@@ -750,12 +765,25 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
     AttnParams ap;
     ap.tiles = d_tiles; ap.users = d_users; ap.rt = rt; ap.q = qbuf; ap.sfx = sfx; ap.part = part;
     ap.split_stride = (size_t)R * d; ap.nsplit = p.nsplit; ap.d = d; ap.n_heads = H; ap.layer = l; ap.score_mul = score_mul;
+    ap.ml = ml; ap.ml_stride = (size_t)R * H * 2;
     int nt = last ? p.n_tiles_new : n_tiles_all;
     ap.n_tiles = nt;
     if (nt > 0) {
       ProfScope ps(c, RELAYGR_K_ATTN, st);
-      rc = launch_attention<T>(cfg, ap, nt, nq, st);
+      rc = launch_attention<T>(cfg, ap, nt, nq, softmax, st);
       if (rc != RELAYGR_OK) return rc;
+    }
+    // softmax form: merge the key splits and the candidate's own key into the finished o (in part[0]);
+    // the fused 16-bit tail kernel does this merge itself
+    if (softmax && !fuse_ln) {
+      ProfScope ps(c, RELAYGR_K_GATE, st);
+      dim3 grid((R - a0 + kRowsPerBlock - 1) / kRowsPerBlock);
+      dispatch_e(d, [&](auto e) {
+        constexpr int E = decltype(e)::value;
+        hipLaunchKernelGGL((softmax_combine_kernel<T, E>), grid, dim3(256), 0, st, part, ml, p.nsplit, (size_t)R * d, (size_t)R * H * 2,
+                           qbuf, knew, vnew, rt, p.n_prows, a0, R, dh, H, bf16 ? 1.0f : alpha, bf16 ? 1.0f : kLog2e);
+      });
+      LAUNCH_CHECK("softmax_combine");
     }
     // steps 3-4: combine splits, self term, 1/n, LayerNorm, gate by u (part of the fused kernel below otherwise)
     if (!fuse_ln) {
@@ -764,7 +792,7 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
       dispatch_e(d, [&](auto e) {
         constexpr int E = decltype(e)::value;
         hipLaunchKernelGGL((attn_gate_kernel<T, E, kPanel>), grid, dim3(256), 0, st, part, p.nsplit, (size_t)R * d, ubuf, qbuf, knew, vnew, xh,
-                           (const T*)lw.ln_at_g, (const T*)lw.ln_at_b, rt, p.n_prows, a0, R, dh, gate_mul, cfg.ln_eps);
+                           (const T*)lw.ln_at_g, (const T*)lw.ln_at_b, rt, p.n_prows, a0, R, dh, gate_mul, cfg.ln_eps, softmax ? 1 : 0);
       });
       LAUNCH_CHECK("attn_gate");
     }
@@ -791,26 +819,32 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
           fp.u = (const uint16_t*)ubuf; fp.q = (const uint16_t*)qbuf; fp.knew = (const uint16_t*)knew; fp.vnew = (const uint16_t*)vnew;
           fp.gate_gain = (const uint16_t*)lw.ln_at_g; fp.gate_offs = (const uint16_t*)lw.ln_at_b;
           fp.n_prows = p.n_prows; fp.dh = dh; fp.qk_mul = gate_mul;
+          fp.ml = softmax ? ml : nullptr; fp.ml_stride = (size_t)R * H * 2; fp.n_heads = H;
           // two row blocks per workgroup halve the passes over W2 once that still leaves every
           // compute unit two workgroups
           const int rows = R - a0;
           const bool rb2 = d <= 512 && rows >= 64 * 512;
           dim3 grid((rows + (rb2 ? 63 : 31)) / (rb2 ? 64 : 32));
-          switch (d) {
-            case 128:
-              if (rb2) hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 128, 4, 2>), grid, dim3(256), 0, st, fp);
-              else hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 128, 4, 1>), grid, dim3(256), 0, st, fp);
-              break;
-            case 256:
-              if (rb2) hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 256, 8, 2>), grid, dim3(512), 0, st, fp);
-              else hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 256, 8, 1>), grid, dim3(512), 0, st, fp);
-              break;
-            case 512:
-              if (rb2) hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 512, 8, 2>), grid, dim3(512), 0, st, fp);
-              else hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 512, 8, 1>), grid, dim3(512), 0, st, fp);
-              break;
-            default: hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 1024, 8, 1>), grid, dim3(512), 0, st, fp); break;
-          }
+          auto launch_tail = [&](auto sm) {
+            constexpr bool SM = decltype(sm)::value;
+            switch (d) {
+              case 128:
+                if (rb2) hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 128, 4, 2, SM>), grid, dim3(256), 0, st, fp);
+                else hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 128, 4, 1, SM>), grid, dim3(256), 0, st, fp);
+                break;
+              case 256:
+                if (rb2) hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 256, 8, 2, SM>), grid, dim3(512), 0, st, fp);
+                else hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 256, 8, 1, SM>), grid, dim3(512), 0, st, fp);
+                break;
+              case 512:
+                if (rb2) hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 512, 8, 2, SM>), grid, dim3(512), 0, st, fp);
+                else hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 512, 8, 1, SM>), grid, dim3(512), 0, st, fp);
+                break;
+              default: hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 1024, 8, 1, SM>), grid, dim3(512), 0, st, fp); break;
+            }
+          };
+          if (softmax) launch_tail(std::true_type());
+          else launch_tail(std::false_type());
         } else {
           F2Params fp;
           fp.A = (const uint16_t*)xh; fp.W = c->w2_packed[l]; fp.bias = (const uint16_t*)lw.b2; fp.x = x; fp.rt = rt; fp.d = d;

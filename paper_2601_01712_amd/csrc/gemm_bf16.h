@@ -371,6 +371,11 @@ struct F2LnParams {
   const uint16_t* gate_offs;
   int n_prows, dh;
   float qk_mul;             // stored q . k -> alpha <q, k>
+  // softmax form (kernels instantiated with SM): part holds sums of exp2(t - m) v, ml the (m, l) of every row, head and
+  // split as [split][row][head][2]; the splits and the candidate's own key are merged here
+  const float* ml;
+  size_t ml_stride;
+  int n_heads;
   const uint16_t* W;        // packed W2 [D, D]
   const uint16_t* bias;     // b2 [D]
   float* x;                 // residual stream [rows, D], updated in place
@@ -412,9 +417,10 @@ struct GateRow {
   float o[E];
   uint32_t ub[E / 2], qb[E / 2], kb[E / 2], vb[E / 2];
   int n, kind;
+  float mpart, lpart;   // softmax form: reference score of o and the matching sum of weights
 };
 
-template <int D>
+template <int D, bool SM>
 __device__ __forceinline__ void load_gate_row(const F2LnParams& p, int row, bool ok, int lane, GateRow<D / 64>& gr) {
   constexpr int E = D / 64;
   // nothing here waits for the row's kind: every load of the row is issued at once
@@ -424,18 +430,35 @@ __device__ __forceinline__ void load_gate_row(const F2LnParams& p, int row, bool
   for (int i = 0; i < E; ++i) gr.o[i] = 0.f;
 #pragma unroll
   for (int i = 0; i < E / 2; ++i) gr.ub[i] = gr.qb[i] = gr.kb[i] = gr.vb[i] = 0u;
+  gr.mpart = 0.f; gr.lpart = 1.f;
   if (!ok) return;
   const size_t base = (size_t)row * D + lane * E;
+  // softmax form: split s counts with weight 2^(m_s - M), M the largest m_s of this lane's head
+  const float* mlr = nullptr;
+  float M = 0.f;
+  gr.lpart = 0.f;
+  if constexpr (SM) {
+    mlr = p.ml + ((size_t)row * p.n_heads + lane * E / p.dh) * 2;
+    M = -INFINITY;
+    for (int s = 0; s < p.nsplit; ++s) M = fmaxf(M, mlr[s * p.ml_stride]);
+  }
+  gr.mpart = M;
   for (int s = 0; s < p.nsplit; ++s) {
     const float* src = p.part + s * p.split_stride + base;
+    float w = 1.0f;
+    if constexpr (SM) {
+      const float2 v = *reinterpret_cast<const float2*>(mlr + s * p.ml_stride);
+      w = (v.x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(v.x - M);
+      gr.lpart += w * v.y;
+    }
     if constexpr (E == 2) {
       const float2 v = *reinterpret_cast<const float2*>(src);
-      gr.o[0] += v.x; gr.o[1] += v.y;
+      gr.o[0] += w * v.x; gr.o[1] += w * v.y;
     } else {
 #pragma unroll
       for (int c = 0; c < E / 4; ++c) {
         const float4 v = *reinterpret_cast<const float4*>(src + 4 * c);
-        gr.o[4 * c] += v.x; gr.o[4 * c + 1] += v.y; gr.o[4 * c + 2] += v.z; gr.o[4 * c + 3] += v.w;
+        gr.o[4 * c] += w * v.x; gr.o[4 * c + 1] += w * v.y; gr.o[4 * c + 2] += w * v.z; gr.o[4 * c + 3] += w * v.w;
       }
     }
   }
@@ -450,7 +473,7 @@ __device__ __forceinline__ void load_gate_row(const F2LnParams& p, int row, bool
 
 // Finishes G rows at once (their reductions interleave) and writes y (bf16) into the token
 // fragments: local row lr0 + i of the workgroup goes to row block (lr0+i)/32, row (lr0+i)%32.
-template <typename H, int D, int G>
+template <typename H, int D, int G, bool SM>
 __device__ __forceinline__ void finish_gate_rows(const F2LnParams& p, GateRow<D / 64> (&gr)[G], int lane, uint16_t* tok, int lr0,
                                                  const uint32_t (&gw)[D / 128], const uint32_t (&ow)[D / 128]) {
   constexpr int E = D / 64, KS = D / 16;
@@ -458,6 +481,7 @@ __device__ __forceinline__ void finish_gate_rows(const F2LnParams& p, GateRow<D 
 #pragma unroll
   for (int r = 0; r < G; ++r) {
     int n = gr[r].n;
+    float lsum = gr[r].lpart;
     if (gr[r].kind == kRowCand) {      // the candidate's own key: SiLU(alpha <q_c, k_c>) v_c per head
       float dot = 0.f;
 #pragma unroll
@@ -470,12 +494,23 @@ __device__ __forceinline__ void finish_gate_rows(const F2LnParams& p, GateRow<D 
       else if (hl == 16) dot = lanes16_sum(dot);
       else if (hl == 32) dot = lanes32_sum(dot);
       else if (hl == 64) dot = wave_sum_dpp(dot);
-      const float pself = silu_f32(dot * p.qk_mul);
+      if constexpr (SM) {
+        // softmax form: the stored q carries alpha * log2(e), so dot is the own key's score in the units
+        // of m; bring the merged splits and the own key to their common maximum
+        const float Mn = fmaxf(gr[r].mpart, dot);
+        const float c = (gr[r].mpart == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(gr[r].mpart - Mn);
+        const float ws = __builtin_amdgcn_exp2f(dot - Mn);
 #pragma unroll
-      for (int i = 0; i < E; ++i) gr[r].o[i] += pself * H::of_word(gr[r].vb[i >> 1], i);
-      n += 1;
+        for (int i = 0; i < E; ++i) gr[r].o[i] = gr[r].o[i] * c + ws * H::of_word(gr[r].vb[i >> 1], i);
+        lsum = lsum * c + ws;
+      } else {
+        const float pself = silu_f32(dot * p.qk_mul);
+#pragma unroll
+        for (int i = 0; i < E; ++i) gr[r].o[i] += pself * H::of_word(gr[r].vb[i >> 1], i);
+        n += 1;
+      }
     }
-    inv_n[r] = 1.0f / (float)(n > 0 ? n : 1);
+    inv_n[r] = SM ? 1.0f / (lsum > 0.f ? lsum : 1.0f) : 1.0f / (float)(n > 0 ? n : 1);
     s[r] = 0.f;
 #pragma unroll
     for (int i = 0; i < E; ++i) { gr[r].o[i] *= inv_n[r]; s[r] += gr[r].o[i]; }
@@ -517,7 +552,7 @@ __device__ __forceinline__ void finish_gate_rows(const F2LnParams& p, GateRow<D 
   }
 }
 
-template <typename H, int D, int NW, int RB>
+template <typename H, int D, int NW, int RB, bool SM>
 __global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
   constexpr int KS = D / 16;            // k-steps
   constexpr int FB = D / 32 / NW;       // 32-feature blocks per wavefront
@@ -541,7 +576,7 @@ __global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
 #pragma unroll
   for (int i = 0; i < GROUP; ++i) {
     const int lr = wave * RPW + i;
-    load_gate_row<D>(p, row0 + lr, row0 + lr < p.row_end, lane, gr[i]);
+    load_gate_row<D, SM>(p, row0 + lr, row0 + lr < p.row_end, lane, gr[i]);
   }
   ld_bf16_run<D / 64>(p.gate_gain + lane * (D / 64), gw);
   ld_bf16_run<D / 64>(p.gate_offs + lane * (D / 64), ow);
@@ -587,15 +622,15 @@ __global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
 
   // now that everything else is in flight behind them, the first rows are reduced and written as
   // token fragments; further groups of rows follow
-  finish_gate_rows<H, D, GROUP>(p, gr, lane, tok, wave * RPW, gw, ow);
+  finish_gate_rows<H, D, GROUP, SM>(p, gr, lane, tok, wave * RPW, gw, ow);
 #pragma unroll
   for (int r0 = GROUP; r0 < RPW; r0 += GROUP) {
 #pragma unroll
     for (int i = 0; i < GROUP; ++i) {
       const int lr = wave * RPW + r0 + i;
-      load_gate_row<D>(p, row0 + lr, row0 + lr < p.row_end, lane, gr[i]);
+      load_gate_row<D, SM>(p, row0 + lr, row0 + lr < p.row_end, lane, gr[i]);
     }
-    finish_gate_rows<H, D, GROUP>(p, gr, lane, tok, wave * RPW + r0, gw, ow);
+    finish_gate_rows<H, D, GROUP, SM>(p, gr, lane, tok, wave * RPW + r0, gw, ow);
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();

@@ -114,19 +114,23 @@ __global__ __launch_bounds__(256) void ln_in_kernel(float* __restrict__ x, T* __
 // sequence, added here in split order (fixed order => reproducible bits).  A candidate's self
 // term SiLU(alpha <q_c^h, k_c^h>) v_c^h is evaluated here from the row's own q, k, v.
 // qk_mul turns the stored q into alpha*q (q may be stored pre-scaled).
+// With plain_o set, part[0] already holds the finished o_i (softmax form, after
+// softmax_combine_kernel): no split sum, no self term, no 1/n.
 template <typename T, int E, bool PANEL>
 __global__ __launch_bounds__(256) void attn_gate_kernel(const float* __restrict__ part, int nsplit, size_t split_stride,
                                                         const T* __restrict__ u, const T* __restrict__ q,
                                                         const T* __restrict__ knew, const T* __restrict__ vnew,
                                                         T* __restrict__ y, const T* __restrict__ gain,
                                                         const T* __restrict__ offs, RowTables rt, int n_prows,
-                                                        int row_begin, int row_end, int dh, float qk_mul, float eps) {
+                                                        int row_begin, int row_end, int dh, float qk_mul, float eps,
+                                                        int plain_o) {
   const int d = 64 * E;
   int r = row_begin + blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
   if (r >= row_end) return;
   int lane = threadIdx.x & 63;
   size_t base = (size_t)r * d + lane * E;
   float o[E];
+  if (plain_o) nsplit = 1;
   if (rt.kind[r] == kRowPad) {
 #pragma unroll
     for (int i = 0; i < E; ++i) o[i] = 0.f;
@@ -139,8 +143,8 @@ __global__ __launch_bounds__(256) void attn_gate_kernel(const float* __restrict_
 #pragma unroll
     for (int i = 0; i < E; ++i) o[i] += part[s * split_stride + base + i];
   }
-  int n = rt.lim[r];
-  if (rt.kind[r] == kRowCand) {
+  int n = plain_o ? 1 : rt.lim[r];
+  if (rt.kind[r] == kRowCand && !plain_o) {
     size_t nb = (size_t)(r - n_prows) * d + lane * E;
     float dot = 0.f;
 #pragma unroll
@@ -164,6 +168,65 @@ __global__ __launch_bounds__(256) void attn_gate_kernel(const float* __restrict_
     o[i] = z * Elem<T>::ld(u + base + i);
   }
   store_row_run<T, E, PANEL>(y, r, lane, d, o);
+}
+
+// Second attention form (softmax over the visible keys): merges a row's key splits and, for a
+// candidate, its own key into the finished attention output
+//   o_i^h = ( sum_s w_s part_s  +  w_self v_c^h ) / ( sum_s w_s l_s + w_self ),
+//   w_s = exp(m_s - M),  w_self = exp(t_self - M),  M = max(m_s, t_self),
+// where split s delivered part_s = sum_j exp(t_j - m_s) v_j, l_s = sum_j exp(t_j - m_s) and m_s
+// (ml holds m and l as [split][row][head][2]; m_s = -inf and l_s = 0 for a split in which the row
+// sees no key).  Scores are stored scaled by 1/to_log2 relative to base-2 exponents: the fp32 path
+// keeps natural-log scores (to_log2 = log2 e), the 16-bit path stores q pre-multiplied by
+// alpha * log2(e) (to_log2 = 1, qk_mul = 1).  Splits are merged in fixed order.  The result
+// overwrites split 0's partial sums, which the gate then reads with its plain_o flag set.
+template <typename T, int E>
+__global__ __launch_bounds__(256) void softmax_combine_kernel(float* __restrict__ part, const float* __restrict__ ml, int nsplit,
+                                                              size_t split_stride, size_t ml_stride, const T* __restrict__ q,
+                                                              const T* __restrict__ knew, const T* __restrict__ vnew, RowTables rt,
+                                                              int n_prows, int row_begin, int row_end, int dh, int n_heads,
+                                                              float qk_mul, float to_log2) {
+  const int d = 64 * E;
+  int r = row_begin + blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
+  if (r >= row_end) return;
+  const int kind = rt.kind[r];
+  if (kind == kRowPad) return;
+  int lane = threadIdx.x & 63;
+  const int head = lane * E / dh;
+  size_t base = (size_t)r * d + lane * E;
+  const float* mlr = ml + ((size_t)r * n_heads + head) * 2;
+  float M = -INFINITY;
+  for (int s = 0; s < nsplit; ++s) M = fmaxf(M, mlr[s * ml_stride]);
+  float tself = 0.f;
+  size_t nb = 0;
+  if (kind == kRowCand) {
+    nb = (size_t)(r - n_prows) * d + lane * E;
+    float dot = 0.f;
+#pragma unroll
+    for (int i = 0; i < E; ++i) dot += Elem<T>::ld(q + base + i) * Elem<T>::ld(knew + nb + i);
+    for (int m = (dh / E) >> 1; m > 0; m >>= 1) dot += __shfl_xor(dot, m, 64);
+    tself = dot * qk_mul;
+    M = fmaxf(M, tself);
+  }
+  float o[E], L = 0.f;
+#pragma unroll
+  for (int i = 0; i < E; ++i) o[i] = 0.f;
+  for (int s = 0; s < nsplit; ++s) {
+    const float ms = mlr[s * ml_stride], ls = mlr[s * ml_stride + 1];
+    const float w = (ms == -INFINITY) ? 0.f : exp2f((ms - M) * to_log2);
+    L += w * ls;
+#pragma unroll
+    for (int i = 0; i < E; ++i) o[i] += w * part[s * split_stride + base + i];
+  }
+  if (kind == kRowCand) {
+    const float w = exp2f((tself - M) * to_log2);
+    L += w;
+#pragma unroll
+    for (int i = 0; i < E; ++i) o[i] += w * Elem<T>::ld(vnew + nb + i);
+  }
+  const float inv = 1.0f / L;
+#pragma unroll
+  for (int i = 0; i < E; ++i) part[base + i] = o[i] * inv;
 }
 
 // Score head: score_c = <w_s, LN(x_c; g_out, b_out)> + b_s for candidate rows, written at the

@@ -161,3 +161,12 @@ def test_pool_create_validates_arguments():
     assert lib.relaygr_kv_pool_create(C.byref(cfg), C.c_void_p(0x1001), 1 << 30, 128, C.byref(out)) == rg.RELAYGR_EINVAL
     assert lib.relaygr_kv_pool_create(C.byref(cfg), C.c_void_p(0x1000), 1000, 128, C.byref(out)) == rg.RELAYGR_ENOSPC
     assert "smaller than one page" in rg.relaygr_last_error()
+
+
+def test_attention_form_setter_rejects_a_null_context():
+    lib = rg.load_library()
+    assert lib.relaygr_ctx_set_attention(None, B.ATTENTION_FORMS["softmax"]) == rg.RELAYGR_EINVAL
+    assert "null context" in rg.relaygr_last_error()
+    assert B.ATTENTION_FORMS == {"silu": 0, "softmax": 1}       # RELAYGR_ATTN_SILU, RELAYGR_ATTN_SOFTMAX
+    header = open(os.path.join(ROOT, "include", "relaygr.h")).read()
+    assert re.search(r"#define\s+RELAYGR_ATTN_SILU\s+0", header) and re.search(r"#define\s+RELAYGR_ATTN_SOFTMAX\s+1", header)

@@ -75,6 +75,12 @@ def test_x3_fp16():
     run_full("X3", sample_users=[9])
 
 
+def test_x4_softmax_attention():
+    """The backbone variant that differs only in its attention computation (Section 5.4), read as a
+    softmax over the visible keys: C3's shape."""
+    run_full("X4", sample_users=[4])
+
+
 def test_c5_jagged_batch_with_uncached_users():
     wl = synth.WORKLOADS["C5"]
     L, S, M, cached = synth.make_lengths(wl, 0)

@@ -1,7 +1,8 @@
 """GPU parity on seeded random jagged batches: random model shape and storage type, 1-5 users with random
 prefix / suffix / candidate counts (including empty prefixes, empty suffixes and users without candidates),
 a random subset of users uncached, random pool page size.  Every case checks ranking on the cached prefix
-and full recompute against the CPU oracle, user by user."""
+and full recompute against the CPU oracle, user by user.  The last eight cases use the second attention form
+(softmax over the visible keys)."""
 import numpy as np
 import pytest
 
@@ -14,7 +15,7 @@ SHAPES = [(64, 2, "fp32"), (128, 2, "fp32"), (128, 2, "bf16"), (128, 4, "bf16"),
           (512, 8, "bf16"), (128, 2, "fp16"), (256, 4, "fp16"), (512, 4, "fp16")]
 
 
-@pytest.mark.parametrize("case", range(16))
+@pytest.mark.parametrize("case", range(24))
 def test_random_jagged_batch(case):
     rng = np.random.default_rng(1000 + case)
     d, H, dtype = SHAPES[case % len(SHAPES)]
@@ -25,5 +26,5 @@ def test_random_jagged_batch(case):
     if sum(M) == 0:
         M[0] = 7
     miss = tuple(int(u) for u in range(n) if rng.random() < 0.3)
-    cfg = synth.ModelConfig(int(rng.integers(1, 4)), d, H, dtype)
+    cfg = synth.ModelConfig(int(rng.integers(1, 4)), d, H, dtype, attention="softmax" if case >= 16 else "silu")
     run_three_routes(cfg, 2000 + case, L, S, M, page_tokens=int(rng.choice([64, 128, 256])), miss=miss)
