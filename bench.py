@@ -181,8 +181,8 @@ def main() -> int:
     if args.full_steps is None:
         args.full_steps = 100 if args.config in ("C1", "C2", "C3", "X3", "X4") else 20
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (users shard by hash across GPUs with no "
-              "collective; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (users would shard by hash across GPUs with "
+              "no collective, one pool and context per GPU); run with --gpus 1", file=sys.stderr)
         return 2
 
     import torch

@@ -114,9 +114,41 @@ class Harness:
         self.pool.close()
 
 
-def build_case(cfg: synth.ModelConfig, seed: int, L, S, M, emb_std: float = 0.02):
+def store(x: np.ndarray, dtype: str) -> np.ndarray:
+    """x rounded once to the storage type, returned as float32."""
+    if dtype == "bf16":
+        return synth.round_to_bf16(x.astype(np.float32))
+    if dtype == "fp16":
+        return x.astype(np.float16).astype(np.float32)
+    return x.astype(np.float32)
+
+
+# With the benchmark's N(0, 0.02^2) weights the attention output reaches the scores only through two small
+# matrices: measured on the oracle, an attention that loses a whole key tile out of ten moves the scores by
+# 5e-5, far inside every tolerance.  Boosting q/k rows 4x and u/v rows, W2 and the score head 5x makes the same
+# mistake move them by 0.56 (ten times the bf16 bound) while plain bf16 rounding of the projections stays
+# at 7e-3; the boosted cases are the ones that hold the attention kernels to the tolerance.
+BOOST = (4.0, 5.0, 5.0, 5.0)
+
+
+def boost_weights(weights: dict, cfg: synth.ModelConfig, factors=BOOST) -> dict:
+    bqk, buv, b2, bs = factors
+    d = cfg.d_model
+    for lw in weights["layers"]:
+        w1 = lw["w1"].copy()
+        w1[2 * d:4 * d] *= bqk
+        w1[:2 * d] *= buv
+        lw["w1"] = store(w1, cfg.dtype)
+        lw["w2"] = store(lw["w2"] * b2, cfg.dtype)
+    weights["w_score"] = store(weights["w_score"] * bs, cfg.dtype)
+    return weights
+
+
+def build_case(cfg: synth.ModelConfig, seed: int, L, S, M, emb_std: float = 0.02, boost=None):
     wl = make_workload("case", cfg, seed, len(L))
     cached = np.ones(len(L), dtype=bool)
     batch = synth.make_batch(wl, 0, lengths=(L, S, M, cached), emb_std=emb_std)
     weights = synth.make_weights(cfg, seed)
+    if boost is not None:
+        boost_weights(weights, cfg, boost)
     return weights, batch
