@@ -47,6 +47,18 @@ def test_boosted_weights(dtype, attention, L, S, M):
     run_three_routes(synth.ModelConfig(2, d, H, dtype, attention=attention), 500 + len(L), L, S, M, boost=BOOST)
 
 
+@pytest.mark.parametrize("attention", ["silu", "softmax"])
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+def test_ragged_batch_on_256_row_work_items(dtype, attention):
+    """Enough candidate rows (37 work items x 8 heads) that the MFMA attention kernel takes two row blocks per
+    wavefront, the launch shape of the benchmark, here with ragged prefixes, suffixes and candidate counts
+    and one uncached user.  At d = 512 the benchmark's own weight scale already lets a lost key tile move
+    the scores by twenty times the tolerance (measured on the oracle)."""
+    run_three_routes(synth.ModelConfig(2, 512, 8, dtype, attention=attention), 520,
+                     [130, 300, 0, 64, 513, 77], [0, 70, 3, 0, 5, 64], [2000, 1500, 900, 1025, 1300, 1600],
+                     page_tokens=128, miss=(4,))
+
+
 # ------------------------------------------------------------------------------------ fp32
 def test_c1_fp32_full():
     wl = synth.WORKLOADS["C1"]
