@@ -618,11 +618,15 @@ __global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
     const int fb = wave * FB + j;
     wbase[j] = p.W + (size_t)(fb >> 2) * KS * 2048 + (fb & 3) * 512 + lane * 8;
   }
+  // the workgroups of an XCD walk the k-steps from different starting points, so that at any moment
+  // they ask the XCD's L2 for different slices of W2 instead of all for the same one
+  static_assert((KS & (KS - 1)) == 0, "k-steps: a power of two");
+  const int rot = (((int)blockIdx.x >> 3) * PF) & (KS - 1);
   uint4 wf[PF][FB];
 #pragma unroll
   for (int i = 0; i < PF; ++i)
 #pragma unroll
-    for (int j = 0; j < FB; ++j) wf[i][j] = *reinterpret_cast<const uint4*>(wbase[j] + (size_t)i * 2048);
+    for (int j = 0; j < FB; ++j) wf[i][j] = *reinterpret_cast<const uint4*>(wbase[j] + (size_t)((i + rot) & (KS - 1)) * 2048);
   // The accumulators start from the residual row plus the bias, fetched now so that the gate and
   // the product hide the latency (the row's kind is only needed when results are stored): element
   // e of acc[b][j] is feature (wave*FB + j)*32 + 8*(e/4) + 4*g + e%4 of token row0 + 32*b + l32.
@@ -669,7 +673,7 @@ __global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
   for (int ks0 = 0; ks0 < KS; ks0 += PF) {
 #pragma unroll
     for (int i = 0; i < PF; ++i) {
-      const int ks = ks0 + i;
+      const int ks = (ks0 + i + rot) & (KS - 1);
       uint4 tf[RB];
 #pragma unroll
       for (int b = 0; b < RB; ++b) tf[b] = *reinterpret_cast<const uint4*>(&tok[(b * KS + ks) * 512 + lane * 8]);
@@ -677,9 +681,9 @@ __global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
       for (int j = 0; j < FB; ++j)
 #pragma unroll
         for (int b = 0; b < RB; ++b) acc[b][j] = H::mfma(wf[i][j], tf[b], acc[b][j]);
-      if (ks + PF < KS) {
+      if (ks0 + i + PF < KS) {
 #pragma unroll
-        for (int j = 0; j < FB; ++j) wf[i][j] = *reinterpret_cast<const uint4*>(wbase[j] + (size_t)(ks + PF) * 2048);
+        for (int j = 0; j < FB; ++j) wf[i][j] = *reinterpret_cast<const uint4*>(wbase[j] + (size_t)((ks + PF) & (KS - 1)) * 2048);
       }
     }
   }
