@@ -823,7 +823,7 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
           // two row blocks per workgroup halve the passes over W2 once that still leaves every
           // compute unit two workgroups
           const int rows = R - a0;
-          const bool rb2 = d <= 512 && rows >= 64 * 512;
+          const bool rb2 = d <= 512 && rows >= 64 * 384;
           dim3 grid((rows + (rb2 ? 63 : 31)) / (rb2 ? 64 : 32));
           auto launch_tail = [&](auto sm) {
             constexpr bool SM = decltype(sm)::value;
