@@ -170,3 +170,35 @@ def test_attention_form_setter_rejects_a_null_context():
     assert B.ATTENTION_FORMS == {"silu": 0, "softmax": 1}       # RELAYGR_ATTN_SILU, RELAYGR_ATTN_SOFTMAX
     header = open(os.path.join(ROOT, "include", "relaygr.h")).read()
     assert re.search(r"#define\s+RELAYGR_ATTN_SILU\s+0", header) and re.search(r"#define\s+RELAYGR_ATTN_SOFTMAX\s+1", header)
+
+
+def test_header_is_valid_c99_and_links_against_the_library(tmp_path):
+    """The boundary is a C ABI: a C99 translation unit that includes the header, takes the address of
+    every declared function and calls the host-only ones must compile without warnings and link."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    header = open(os.path.join(ROOT, "include", "relaygr.h")).read()
+    names = sorted(set(re.findall(r"\b(relaygr_[a-z_0-9]+)\s*\(", header)))
+    src = tmp_path / "abi.c"
+    src.write_text(
+        '#include "relaygr.h"\n#include <stdio.h>\n'
+        "typedef void (*fn)(void);\n"
+        "int main(void) {\n"
+        "  fn table[] = {" + ", ".join(f"(fn){n}" for n in names) + "};\n"
+        "  relaygr_model_config cfg = {8, 256, 8, RELAYGR_DTYPE_FP32, 1e-5f};\n"
+        "  size_t kv = relaygr_kv_footprint_bytes(&cfg, 2048);\n"
+        "  int rc = relaygr_ctx_set_attention(NULL, RELAYGR_ATTN_SOFTMAX);\n"
+        '  printf("%zu %d %zu\\n", kv, rc, sizeof(table) / sizeof(table[0]));\n'
+        "  return 0;\n}\n")
+    rg.load_library()
+    from paper_2601_01712_amd import build as _build
+    lib_dir = os.path.dirname(_build.LIB)
+    exe = tmp_path / "abi"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe), "-L", lib_dir, "-lrelaygr", f"-Wl,-rpath,{lib_dir}"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert int(out[0]) == 32 * 1024 * 1024          # the paper's example: 2K tokens, 8 layers, d 256, fp32 (Section 5.1)
+    assert int(out[1]) == rg.RELAYGR_EINVAL
+    assert int(out[2]) == len(names) == len(rg.EXPORTS)
