@@ -172,12 +172,12 @@ def main() -> int:
     ap.add_argument("--no-concurrent", action="store_true", help="skip the rank-beside-prefill measurement on two streams")
     ap.add_argument("--no-dram", action="store_true", help="skip the spill / reload (DRAM tier) measurement")
     ap.add_argument("--batches", type=int, default=None,
-                    help="distinct seeded batches the timed rank calls cycle through (default 8 for the jagged C5, else 1)")
+                    help="distinct seeded batches the timed rank calls cycle through (default 32 for the jagged C5, else 1)")
     ap.add_argument("--no-single", action="store_true", help="skip the one-user-per-call latency breakdown (pre / load / rank)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the small-M sweep of the attention kernel (its HBM-bound regime)")
     args = ap.parse_args()
     if args.batches is None:
-        args.batches = 8 if args.config == "C5" else 1
+        args.batches = 32 if args.config == "C5" else 1
     if args.full_steps is None:
         args.full_steps = 100 if args.config in ("C1", "C2", "C3", "X3", "X4") else 20
     if args.gpus != 1:
