@@ -837,7 +837,7 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
                 else hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 256, 8, 1, SM>), grid, dim3(512), 0, st, fp);
                 break;
               case 512:
-                if (rb2) hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 512, 8, 2, SM>), grid, dim3(512), 0, st, fp);
+                if (rb2) hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 512, 8, 2, SM, 2>), grid, dim3(512), 0, st, fp);
                 else hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 512, 8, 1, SM>), grid, dim3(512), 0, st, fp);
                 break;
               default: hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 1024, 8, 1, SM>), grid, dim3(512), 0, st, fp); break;

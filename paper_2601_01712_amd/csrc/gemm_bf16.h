@@ -576,11 +576,15 @@ __device__ __forceinline__ int l2_touch(const void* base, int lines, int share, 
   return acc;
 }
 
-template <typename H, int D, int NW, int RB, bool SM>
-__global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
+// OCC = 2: built to fit two workgroups on a compute unit (128 registers per lane), so that one's gate
+// phase (memory) overlaps the other's product phase (L2 and matrix cores) when a launch has several
+// workgroups per unit: fewer k-steps and gate rows in flight, and the weight fragments and the
+// residual rows are requested after the gate instead of before it.
+template <typename H, int D, int NW, int RB, bool SM, int OCC = 1>
+__global__ __launch_bounds__(NW * 64, OCC) void f2_ln_bf16_kernel(F2LnParams p) {
   constexpr int KS = D / 16;            // k-steps
   constexpr int FB = D / 32 / NW;       // 32-feature blocks per wavefront
-  constexpr int PF = FB >= 4 ? 2 : 8;   // k-steps of weight fragments in flight per wavefront
+  constexpr int PF = FB >= 4 ? 2 : (OCC == 2 ? 4 : 8);   // k-steps of weight fragments in flight per wavefront
   constexpr int ROWS = 32 * RB;         // rows per workgroup: RB blocks of 32 share one pass over W2
   static_assert(FB >= 1 && FB * NW * 32 == D && KS % PF == 0, "shape");
   static_assert(RB * KS * 1024 <= 65536, "token fragments fit static LDS");
@@ -593,7 +597,7 @@ __global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
   // The gate makes the tokens: each wavefront takes ROWS/NW rows, a few at a time
   // so that their loads are in flight together.  The first group's loads go out before anything
   // else, since they are what the workgroup needs first.
-  constexpr int RPW = ROWS / NW, GMAX = RB * FB >= 4 ? (D >= 1024 ? 1 : 2) : 4, GROUP = RPW < GMAX ? RPW : GMAX;
+  constexpr int RPW = ROWS / NW, GMAX = OCC == 2 ? 2 : (RB * FB >= 4 ? (D >= 1024 ? 1 : 2) : 4), GROUP = RPW < GMAX ? RPW : GMAX;
   static_assert(RPW >= 1 && RPW % GROUP == 0, "rows per wavefront");
   GateRow<D / 64> gr[GROUP];
   uint32_t gw[D / 128], ow[D / 128];
@@ -623,10 +627,13 @@ __global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
   static_assert((KS & (KS - 1)) == 0, "k-steps: a power of two");
   const int rot = (((int)blockIdx.x >> 3) * PF) & (KS - 1);
   uint4 wf[PF][FB];
+  auto prefetch_w = [&]() {
 #pragma unroll
-  for (int i = 0; i < PF; ++i)
+    for (int i = 0; i < PF; ++i)
 #pragma unroll
-    for (int j = 0; j < FB; ++j) wf[i][j] = *reinterpret_cast<const uint4*>(wbase[j] + (size_t)((i + rot) & (KS - 1)) * 2048);
+      for (int j = 0; j < FB; ++j) wf[i][j] = *reinterpret_cast<const uint4*>(wbase[j] + (size_t)((i + rot) & (KS - 1)) * 2048);
+  };
+  if constexpr (OCC == 1) prefetch_w();
   // The accumulators start from the residual row plus the bias, fetched now so that the gate and
   // the product hide the latency (the row's kind is only needed when results are stored): element
   // e of acc[b][j] is feature (wave*FB + j)*32 + 8*(e/4) + 4*g + e%4 of token row0 + 32*b + l32.
@@ -634,25 +641,28 @@ __global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
   float* xrow[RB];
   int kind_ep[RB];
   f32x16_t acc[RB][FB];
+  auto init_acc = [&]() {
 #pragma unroll
-  for (int b = 0; b < RB; ++b) {
-    const int row = row0 + 32 * b + l32;
-    in_range[b] = row < p.row_end;
-    kind_ep[b] = p.rt.kind[in_range[b] ? row : row0];
-    xrow[b] = p.x + (size_t)(in_range[b] ? row : row0) * D;
+    for (int b = 0; b < RB; ++b) {
+      const int row = row0 + 32 * b + l32;
+      in_range[b] = row < p.row_end;
+      kind_ep[b] = p.rt.kind[in_range[b] ? row : row0];
+      xrow[b] = p.x + (size_t)(in_range[b] ? row : row0) * D;
 #pragma unroll
-    for (int j = 0; j < FB; ++j)
+      for (int j = 0; j < FB; ++j)
 #pragma unroll
-      for (int e4 = 0; e4 < 4; ++e4) {
-        const int c = (wave * FB + j) * 32 + 8 * e4 + 4 * g;
-        const uint2 bb = *reinterpret_cast<const uint2*>(p.bias + c);
-        const float4 v = *reinterpret_cast<const float4*>(xrow[b] + c);
-        acc[b][j][4 * e4] = v.x + H::to_f32(bb.x & 0xFFFF);
-        acc[b][j][4 * e4 + 1] = v.y + H::to_f32(bb.x >> 16);
-        acc[b][j][4 * e4 + 2] = v.z + H::to_f32(bb.y & 0xFFFF);
-        acc[b][j][4 * e4 + 3] = v.w + H::to_f32(bb.y >> 16);
-      }
-  }
+        for (int e4 = 0; e4 < 4; ++e4) {
+          const int c = (wave * FB + j) * 32 + 8 * e4 + 4 * g;
+          const uint2 bb = *reinterpret_cast<const uint2*>(p.bias + c);
+          const float4 v = *reinterpret_cast<const float4*>(xrow[b] + c);
+          acc[b][j][4 * e4] = v.x + H::to_f32(bb.x & 0xFFFF);
+          acc[b][j][4 * e4 + 1] = v.y + H::to_f32(bb.x >> 16);
+          acc[b][j][4 * e4 + 2] = v.z + H::to_f32(bb.y & 0xFFFF);
+          acc[b][j][4 * e4 + 3] = v.w + H::to_f32(bb.y >> 16);
+        }
+    }
+  };
+  if constexpr (OCC == 1) init_acc();
 
   // now that everything else is in flight behind them, the first rows are reduced and written as
   // token fragments; further groups of rows follow
@@ -669,6 +679,7 @@ __global__ __launch_bounds__(NW * 64) void f2_ln_bf16_kernel(F2LnParams p) {
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   if (touched == 0x5a17c0de && p.eps < 0.f) red[0] = 0.f;   // never taken: keeps the warm-up loads
+  if constexpr (OCC == 2) { prefetch_w(); init_acc(); }
 
   for (int ks0 = 0; ks0 < KS; ks0 += PF) {
 #pragma unroll
