@@ -66,10 +66,10 @@ extern "C" int relaygr_probe_mfma(void* work_dev, size_t work_bytes, int32_t ran
   float* out = (float*)work_dev;
   const int blocks = 512;    // two workgroups of four wavefronts per compute unit
   hipLaunchKernelGGL(mfma_probe_kernel, dim3(blocks), dim3(256), 0, st, out, 16, random_data);   // warm-up
-  hipEventRecord(a, st);
+  hipError_t e = hipEventRecord(a, st);
   hipLaunchKernelGGL(mfma_probe_kernel, dim3(blocks), dim3(256), 0, st, out, iters, random_data);
-  hipEventRecord(b, st);
-  hipError_t e = hipEventSynchronize(b);
+  if (e == hipSuccess) e = hipEventRecord(b, st);
+  if (e == hipSuccess) e = hipEventSynchronize(b);
   float ms = 0.f, t[2] = {0.f, 0.f};
   if (e == hipSuccess) e = hipEventElapsedTime(&ms, a, b);
   if (e == hipSuccess) e = hipMemcpy(t, out, sizeof(t), hipMemcpyDeviceToHost);
