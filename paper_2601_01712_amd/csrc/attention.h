@@ -301,7 +301,7 @@ __device__ __forceinline__ void softmax_track(const f32x16_t (&s)[NQ], const int
 }
 
 template <typename H, int DH, int NQ, int NW, bool SOFTMAX>
-__global__ __launch_bounds__(NW * 64, (DH * NQ >= 256) ? 1 : 512 / (NW * 64)) void attn_bf16_kernel(AttnParams p) {
+__global__ __launch_bounds__(NW * 64, (DH >= 128) ? 1 : 512 / (NW * 64)) void attn_bf16_kernel(AttnParams p) {   // DH = 128: the 96 KiB tile ring admits one workgroup per compute unit
   constexpr int KS = DH / 16;              // k-steps of the first product
   constexpr int DB = DH / 32;              // 32-feature blocks of the output
   constexpr int TILE = 2 * kTile * DH;     // elements of one K tile + one V tile
