@@ -624,8 +624,12 @@ __global__ __launch_bounds__(NW * 64, OCC) void f2_ln_bf16_kernel(F2LnParams p) 
   }
   // the workgroups of an XCD walk the k-steps from different starting points, so that at any moment
   // they ask the XCD's L2 for different slices of W2 instead of all for the same one
+  // (the sum over k then runs in a different order per block; for prefix rows the starting point is
+  // taken from the block's position inside its user's prefix, not from the block index, so that the
+  // K/V a pre-inference leaves in the pool do not depend on which other users shared its batch)
   static_assert((KS & (KS - 1)) == 0, "k-steps: a power of two");
-  const int rot = (((int)blockIdx.x >> 3) * PF) & (KS - 1);
+  const int blk_id = row0 < p.n_prows ? p.rt.idx[row0] / ROWS : (int)blockIdx.x;
+  const int rot = ((blk_id >> 3) * PF) & (KS - 1);
   uint4 wf[PF][FB];
   auto prefetch_w = [&]() {
 #pragma unroll
