@@ -283,7 +283,8 @@ int  relaygr_expander_alloc(relaygr_expander* ex, uint64_t user_id, int32_t pref
 /* Releases reclaimable entries, oldest retirement first, until at most `keep` remain in HBM. */
 int  relaygr_expander_trim(relaygr_expander* ex, int32_t keep);
 /* The idempotent probe issued before every rank (pseudo-pre-infer): *source = 0 and the live handle if
- * psi is in HBM (a pending retire of it is cancelled); *source = 1 if it was found in DRAM, in which
+ * psi is in HBM (a pending retire of it is cancelled; hip_stream is made to wait only if a reload of
+ * this very entry is still in flight, never for other users' copies); *source = 1 if it was found in DRAM, in which
  * case an entry is allocated (as by relaygr_expander_alloc), the reload is enqueued on the copy stream and hip_stream is made to wait
  * for it (no host wait); RELAYGR_ENOENT if neither tier has it (the caller ranks by full recompute
  * or pre-infers); RELAYGR_EBUSY if the reload limit is reached (the caller falls back, nothing queued). */

@@ -84,6 +84,10 @@ struct PendingFree {
   hipEvent_t spilled;
   bool cancelled;
 };
+struct Reload {
+  relaygr_kv_handle handle;   // the HBM entry being filled
+  hipEvent_t done;
+};
 }  // namespace
 
 struct relaygr_expander {
@@ -95,7 +99,7 @@ struct relaygr_expander {
   std::unordered_map<uint64_t, uint64_t> last_use;   // DRAM-resident user -> LRU stamp
   std::vector<PendingFree> pending_free;        // retired, spill not yet known to be complete
   std::deque<relaygr_kv_handle> reclaimable;    // retired and spilled: still in HBM, oldest first
-  std::vector<hipEvent_t> reloads;      // reloads that may still be in flight
+  std::vector<Reload> reloads;          // reloads that may still be in flight
   std::vector<hipEvent_t> spare_events;
   uint64_t clock = 0;
   int64_t stats[6] = {};
@@ -124,8 +128,8 @@ static void poll(relaygr_expander* ex) {
     }
   }
   for (size_t i = 0; i < ex->reloads.size();) {
-    if (hipEventQuery(ex->reloads[i]) == hipSuccess) {
-      ex->spare_events.push_back(ex->reloads[i]);
+    if (hipEventQuery(ex->reloads[i].done) == hipSuccess) {
+      ex->spare_events.push_back(ex->reloads[i].done);
       ex->reloads[i] = ex->reloads.back();
       ex->reloads.pop_back();
     } else {
@@ -223,7 +227,7 @@ extern "C" void relaygr_expander_destroy(relaygr_expander* ex) {
   (void)hipStreamSynchronize(ex->copy_stream);
   poll(ex);
   for (auto& pf : ex->pending_free) (void)hipEventDestroy(pf.spilled);
-  for (auto e : ex->reloads) (void)hipEventDestroy(e);
+  for (auto& r : ex->reloads) (void)hipEventDestroy(r.done);
   for (auto e : ex->spare_events) (void)hipEventDestroy(e);
   (void)hipStreamDestroy(ex->copy_stream);
   if (ex->arena) (void)hipHostFree(ex->arena);
@@ -243,7 +247,11 @@ extern "C" int relaygr_expander_retire(relaygr_expander* ex, relaygr_kv_handle h
   forget_reclaimable(ex, h);
   const size_t bytes = (size_t)e.npages * page_bytes(ex->hbm);
   hipEvent_t consumed = get_event(ex), spilled = get_event(ex);
-  if (!consumed || !spilled) return fail(RELAYGR_EHIP, "expander_retire: cannot create events");
+  if (!consumed || !spilled) {
+    if (consumed) ex->spare_events.push_back(consumed);
+    if (spilled) ex->spare_events.push_back(spilled);
+    return fail(RELAYGR_EHIP, "expander_retire: cannot create events");
+  }
   HIP_TRY(hipEventRecord(consumed, (hipStream_t)stream));
   HIP_TRY(hipStreamWaitEvent(ex->copy_stream, consumed, 0));
   ex->spare_events.push_back(consumed);   // the wait is enqueued; the event may be recorded again later
@@ -272,12 +280,10 @@ extern "C" int relaygr_expander_lookup(relaygr_expander* ex, uint64_t user_id, v
     for (auto& pf : ex->pending_free)
       if (pf.handle == h) pf.cancelled = true;              // keep it live; its DRAM copy still completes
     forget_reclaimable(ex, h);                              // live again until it is retired again
-    // a reload of this entry may still be in flight on the copy stream: order the caller behind it
-    hipEvent_t ev = get_event(ex);
-    if (!ev) return fail(RELAYGR_EHIP, "expander_lookup: cannot create an event");
-    HIP_TRY(hipEventRecord(ev, ex->copy_stream));
-    HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, ev, 0));
-    ex->spare_events.push_back(ev);
+    // a reload of this very entry may still be in flight on the copy stream: order the caller behind
+    // it, and behind nothing else (a hit does not wait for other users' spills and reloads)
+    for (auto& r : ex->reloads)
+      if (r.handle == h) HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, r.done, 0));
     auto it = ex->last_use.find(user_id);
     if (it != ex->last_use.end()) it->second = ++ex->clock;
     ex->stats[0] += 1;
@@ -304,7 +310,7 @@ extern "C" int relaygr_expander_lookup(relaygr_expander* ex, uint64_t user_id, v
   if (he != hipSuccess) { ex->hbm->release(h); ex->spare_events.push_back(done); return fail(RELAYGR_EHIP, "expander_lookup: %s", hipGetErrorString(he)); }
   HIP_TRY(hipEventRecord(done, ex->copy_stream));
   HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, done, 0));
-  ex->reloads.push_back(done);
+  ex->reloads.push_back({h, done});
   ex->last_use[user_id] = ++ex->clock;
   ex->stats[1] += 1;
   *out = h;

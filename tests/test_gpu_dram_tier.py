@@ -345,3 +345,39 @@ def test_expander_bounds_reloads_in_flight():
     finally:
         ex.close()
         h.close()
+
+
+def test_hbm_hit_does_not_wait_for_another_users_copy():
+    """A level-1 hit is ordered behind a reload of its own entry only: while another user's 256 MiB
+    image is still on its way to DRAM, the stream handed to the lookup stays free."""
+    cfg = synth.ModelConfig(8, 512, 8, "bf16")
+    weights, batch = build_case(cfg, 141, [16384, 64], [0, 0], [4, 4])
+    h = Harness(cfg, weights, batch, page_tokens=256, pool_extra_pages=2)
+    page = rg.relaygr_kv_pool_bytes_for(h.ctx.cfg, 256, 256)
+    ex = rg.Expander(h.pool, 70 * page, max_inflight_reloads=2)
+    try:
+        h.prefill()
+        torch.cuda.synchronize()
+        assert rg.relaygr_kv_pool_entry_bytes(h.pool, int(h.handles[0])) == 256 << 20
+        s2 = torch.cuda.Stream()                                     # default priority
+        rg.relaygr_expander_retire(ex, int(h.handles[0]))             # several milliseconds of copy
+        hb, src = rg.relaygr_expander_lookup(ex, _uid(batch, 1), stream=s2)
+        idle = s2.query()                                            # nothing is enqueued on s2 but what the lookup put there
+        still_copying = rg.relaygr_expander_stats(ex)["hbm_reclaimable"] == 0
+        assert (hb, src) == (int(h.handles[1]), 0)
+        if not still_copying:
+            pytest.skip("the spill had finished before the lookup returned: inconclusive")
+        assert idle, "the hit was made to wait for another user's spill"
+        # the hit's own reload, on the other hand, is waited for: displace user 1, reload it, hit it again
+        rg.relaygr_expander_retire(ex, hb)
+        _settle(ex)
+        rg.relaygr_expander_trim(ex, 0)
+        h1, src = rg.relaygr_expander_lookup(ex, _uid(batch, 1), stream=s2)
+        assert src == 1
+        h1b, src = rg.relaygr_expander_lookup(ex, _uid(batch, 1), stream=s2)
+        assert (h1b, src) == (h1, 0)
+        torch.cuda.synchronize()
+        assert np.array_equal(_rank_user(h, 1, h1b), _rank_user(h, 1, h1))
+    finally:
+        ex.close()
+        h.close()
