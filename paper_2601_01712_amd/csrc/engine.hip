@@ -705,8 +705,9 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
   const int R = p.n_rows;
   constexpr bool kPanel = !std::is_same<T, float>::value;   // bf16: xh / y are written as MFMA panels
 
-  // bf16: the output projection also applies the next layer's input LayerNorm (one pass over x less)
-  const bool fuse_ln = bf16 && (d == 128 || d == 256 || d == 512 || d == 1024);
+  // 16-bit types: one row-local kernel per layer takes everything between the attention and the next
+  // layer's projections (combine, gate, output projection, residual, next input LayerNorm, score head)
+  constexpr bool fuse_ln = kPanel;
   for (int l = 0; l < NL; ++l) {
     const relaygr_layer_weights& lw = c->layers[l];
     const bool last = (l == NL - 1);
@@ -724,7 +725,7 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
         if (l == 0)
           hipLaunchKernelGGL((ln_in_kernel<T, E, true, kPanel>), grid, dim3(256), 0, st, x, xh, (const T*)lw.ln_in_g, (const T*)lw.ln_in_b,
                              emb_p, emb_s, emb_c, rt, 0, R, cfg.ln_eps);
-        else
+        else if constexpr (!fuse_ln)
           hipLaunchKernelGGL((ln_in_kernel<T, E, false, kPanel>), grid, dim3(256), 0, st, x, xh, (const T*)lw.ln_in_g, (const T*)lw.ln_in_b,
                              emb_p, emb_s, emb_c, rt, 0, R, cfg.ln_eps);
       });
@@ -775,7 +776,7 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
     }
     // softmax form: merge the key splits and the candidate's own key into the finished o (in part[0]);
     // the fused 16-bit tail kernel does this merge itself
-    if (softmax && !fuse_ln) {
+    if constexpr (!fuse_ln) if (softmax) {
       ProfScope ps(c, RELAYGR_K_GATE, st);
       dim3 grid((R - a0 + kRowsPerBlock - 1) / kRowsPerBlock);
       dispatch_e(d, [&](auto e) {
@@ -786,7 +787,7 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
       LAUNCH_CHECK("softmax_combine");
     }
     // steps 3-4: combine splits, self term, 1/n, LayerNorm, gate by u (part of the fused kernel below otherwise)
-    if (!fuse_ln) {
+    if constexpr (!fuse_ln) {
       ProfScope ps(c, RELAYGR_K_GATE, st);
       dim3 grid((R - a0 + kRowsPerBlock - 1) / kRowsPerBlock);
       dispatch_e(d, [&](auto e) {
@@ -805,7 +806,7 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
         ColMap one = {1, {0, 0, 0, 0}, d};
         GemmLaunch<T>::run(xh, (const T*)lw.w2, d, a0, R, one, e2, st);
       } else {
-        if (fuse_ln) {
+        {
           F2LnParams fp;
           fp.W = c->w2_packed[l]; fp.bias = (const uint16_t*)lw.b2; fp.x = x; fp.rt = rt;
           // the last layer of a ranking call ends in the score head instead of the next layer's LayerNorm
@@ -845,19 +846,13 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
           };
           if (softmax) launch_tail(std::true_type());
           else launch_tail(std::false_type());
-        } else {
-          F2Params fp;
-          fp.A = (const uint16_t*)xh; fp.W = c->w2_packed[l]; fp.bias = (const uint16_t*)lw.b2; fp.x = x; fp.rt = rt; fp.d = d;
-          fp.row_begin = a0; fp.row_end = R; fp.n_mtiles = (R - a0 + 64 * kF2TM - 1) / (64 * kF2TM);
-          int total = fp.n_mtiles * (d / (64 * kF2TN));
-          hipLaunchKernelGGL(f2_gemm_bf16_kernel<HT>, dim3((total + 7) / 8 * 8), dim3(256), 0, st, fp);
         }
       }
     }
     LAUNCH_CHECK("f2");
   }
 
-  if (mode != kPrefill && p.n_nrows && !fuse_ln) {   // the fused bf16 tail kernel has written the scores already
+  if constexpr (!fuse_ln) if (mode != kPrefill && p.n_nrows) {   // the fused 16-bit tail kernel has written the scores already
     ProfScope ps(c, RELAYGR_K_SCORE, st);
     dim3 grid((p.n_nrows + kRowsPerBlock - 1) / kRowsPerBlock);
     dispatch_e(d, [&](auto e) {

@@ -294,56 +294,6 @@ __global__ __launch_bounds__(256, 2) void f1_gemm_bf16_kernel(F1Params p) {
   }
 }
 
-// ---- f2 -------------------------------------------------------------------------------------------
-struct F2Params {
-  const uint16_t* A;        // y panels
-  const uint16_t* W;        // packed W2 [d, d]
-  const uint16_t* bias;     // [d]
-  float* x;                 // residual stream [rows, d], updated in place
-  RowTables rt;
-  int d, row_begin, row_end, n_mtiles;
-};
-
-constexpr int kF2TM = 2, kF2TN = 2, kF2Stages = 4;   // 128 tokens x 128 features per workgroup
-
-template <typename H>
-__global__ __launch_bounds__(256, 2) void f2_gemm_bf16_kernel(F2Params p) {
-  constexpr int TM = kF2TM, TN = kF2TN;
-  using G = GemmTile<TM, TN, kF2Stages>;
-  __shared__ __attribute__((aligned(16))) uint16_t lds[G::LDS_ELEMS];
-  const int n_ntiles = p.d / G::BNf;
-  const int total = p.n_mtiles * n_ntiles;
-  const int logical = xcd_remap(blockIdx.x, total);
-  if (logical >= total) return;
-  const int mt = logical / n_ntiles, nt = logical - mt * n_ntiles;
-  const int m0 = p.row_begin + mt * G::BMt, n0 = nt * G::BNf;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave >> 1, wn = wave & 1, l32 = lane & 31, g = lane >> 5;
-  f32x16_t acc[TM][TN];
-  // feature-major: a lane holds one token and runs of 4 consecutive features, i.e. one 16-byte
-  // read-modify-write of the fp32 residual row per accumulator quad
-  gemm_mainloop<H, TM, TN, kF2Stages, true>(p.A, p.W, p.d, m0, n0, lds, acc);
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int row = m0 + wm * 64 + i * 32 + l32;
-    if (row >= p.row_end) continue;
-    float* xrow = p.x + (size_t)row * p.d;
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int e4 = 0; e4 < 4; ++e4) {
-        const int c = n0 + wn * 64 + j * 32 + 8 * e4 + 4 * g;
-        const uint2 bb = *reinterpret_cast<const uint2*>(p.bias + c);
-        float4 v = *reinterpret_cast<const float4*>(xrow + c);
-        v.x += acc[i][j][4 * e4] + H::to_f32(bb.x & 0xFFFF);
-        v.y += acc[i][j][4 * e4 + 1] + H::to_f32(bb.x >> 16);
-        v.z += acc[i][j][4 * e4 + 2] + H::to_f32(bb.y & 0xFFFF);
-        v.w += acc[i][j][4 * e4 + 3] + H::to_f32(bb.y >> 16);
-        *reinterpret_cast<float4*>(xrow + c) = v;
-      }
-  }
-}
-
 // ---- gate + f2 + next layer's input LayerNorm in one kernel ------------------------------------
 // Everything between the attention of one layer and the projections of the next is local to a row:
 //   y  = LN((sum of key-split partial sums + a candidate's self term) / n; g_at, b_at) * u
