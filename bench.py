@@ -103,10 +103,13 @@ def small_m_sweep(torch, rg, synth, n_users=128, L=8192, Ms=(16, 32, 64, 128), s
             "points": out}
 
 
-def single_request_breakdown(torch, rg, synth, cfg, weights, shapes=((4096, 512), (8192, 512), (8192, 2048), (15360, 512)), reps=15):
+def single_request_breakdown(torch, rg, synth, cfg, weights, shapes=((1024, 512), (2048, 512), (4096, 128), (4096, 512), (4096, 1024), (4096, 2048), (8192, 512),
+                                    (8192, 2048), (15360, 512)), reps=15):
     """The paper's per-request latency components (Section 5.2, pre / load / rank) for ONE user per call on the
     benchmark model: prefix pre-inference, reload of psi from pinned host memory, ranking on the cached prefix,
-    and the baseline's full inference inline.  Median of `reps` calls each, HIP events on the call's stream."""
+    and the baseline's full inference inline, over the paper's two sweeps: prefix length at about 512 candidates
+    (Section 5.3) and candidate count at a fixed prefix (Section 5.4).  Median of `reps` calls each, HIP events on
+    the call's stream."""
     Lmax = max(L for L, _ in shapes)
     Mmax = max(M for _, M in shapes)
     ctx = rg.Context(cfg, weights, 1, Lmax, Mmax)
