@@ -206,7 +206,8 @@ int  relaygr_prefill_prefix(relaygr_ctx* ctx, relaygr_kv_pool* pool, const relay
  * read, but prefix_off must still give the prefix length, which must equal the entry's).  A user
  * whose handle is RELAYGR_NO_CACHE is recomputed in the same call from prefix_emb (the paper's
  * miss fallback); pool may be null if every handle is RELAYGR_NO_CACHE.  A stale handle is
- * RELAYGR_ENOENT and nothing is enqueued: the caller retries with RELAYGR_NO_CACHE for that user. */
+ * RELAYGR_ENOENT and nothing is enqueued: the caller retries with RELAYGR_NO_CACHE for that user.
+ * A batch of zero users, or one without candidates, is not an error (scores_dev may then be null). */
 int  relaygr_rank_with_cache(relaygr_ctx* ctx, relaygr_kv_pool* pool, const relaygr_batch* batch,
                              float* scores_dev, void* hip_stream);
 

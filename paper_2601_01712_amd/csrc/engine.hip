@@ -582,7 +582,7 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
   if (mode != kPrefill && nrow > 0) {
     if ((sfx_tiles > 0 && !b->suffix_emb)) return fail(RELAYGR_EINVAL, "suffix tokens present but suffix_emb is null");
     if (!b->cand_emb && b->cand_off && b->cand_off[n] > 0) return fail(RELAYGR_EINVAL, "candidates present but cand_emb is null");
-    if (!scores) return fail(RELAYGR_EINVAL, "scores_dev is null");
+    if (!scores && b->cand_off && b->cand_off[n] > 0) return fail(RELAYGR_EINVAL, "scores_dev is null");
   }
 
   // Rows per attention work item.  The MFMA kernel reads half as much LDS and L2 per score element
