@@ -423,7 +423,7 @@ __device__ __forceinline__ void load_gate_row(const F2LnParams& p, int row, bool
 
 // Finishes G rows at once (their reductions interleave) and writes y (bf16) into the token
 // fragments: local row lr0 + i of the workgroup goes to row block (lr0+i)/32, row (lr0+i)%32.
-template <typename H, int D, int G, bool SM>
+template <typename H, int D, int G, bool SM, int FRAG>
 __device__ __forceinline__ void finish_gate_rows(const F2LnParams& p, GateRow<D / 64> (&gr)[G], int lane, uint16_t* tok, int lr0,
                                                  const uint32_t (&gw)[D / 128], const uint32_t (&ow)[D / 128]) {
   constexpr int E = D / 64, KS = D / 16;
@@ -488,13 +488,13 @@ __device__ __forceinline__ void finish_gate_rows(const F2LnParams& p, GateRow<D 
     }
     // feature f of a row block's local row rr sits at fragment f/16, lane (f/8 % 2)*32 + rr, element f%8
     const int lr = lr0 + r;
-    uint16_t* tokb = tok + (lr >> 5) * KS * 512;
+    uint16_t* tokb = tok + (lr >> 5) * KS * FRAG;
     const int rr = lr & 31;
     constexpr int RUN = E < 8 ? E : 8;
 #pragma unroll
     for (int c = 0; c < E; c += RUN) {
       const int f = lane * E + c;
-      uint16_t* dst = tokb + (f >> 4) * 512 + (((f >> 3) & 1) * 32 + rr) * 8 + (f & 7);
+      uint16_t* dst = tokb + (f >> 4) * FRAG + (((f >> 3) & 1) * 32 + rr) * 8 + (f & 7);
       if constexpr (RUN == 2) *reinterpret_cast<uint32_t*>(dst) = yw[c / 2];
       else if constexpr (RUN == 4) *reinterpret_cast<uint2*>(dst) = make_uint2(yw[c / 2], yw[c / 2 + 1]);
       else *reinterpret_cast<uint4*>(dst) = make_uint4(yw[c / 2], yw[c / 2 + 1], yw[c / 2 + 2], yw[c / 2 + 3]);
@@ -538,7 +538,10 @@ __global__ __launch_bounds__(NW * 64, OCC) void f2_ln_bf16_kernel(F2LnParams p) 
   constexpr int ROWS = 32 * RB;         // rows per workgroup: RB blocks of 32 share one pass over W2
   static_assert(FB >= 1 && FB * NW * 32 == D && KS % PF == 0, "shape");
   static_assert(RB * KS * 1024 <= 65536, "token fragments fit static LDS");
-  __shared__ __attribute__((aligned(16))) uint16_t tok[RB * KS * 512];   // ROWS tokens x D, fragment order
+  // A row's 16-byte chunks go to the same place of consecutive fragments: with fragments exactly 1 KiB apart all
+  // 64 lanes of such a write would hit one bank, so fragments sit 16 bytes further apart where static LDS allows it
+  constexpr int FRAG = 512 + (RB == 1 ? 8 : 0);   // elements between token fragments
+  __shared__ __attribute__((aligned(16))) uint16_t tok[RB * KS * FRAG];   // ROWS tokens x D, fragment order
   float* red = reinterpret_cast<float*>(tok);                             // reused after the product: [2][NW][ROWS]
   const int row0 = p.row_begin + blockIdx.x * ROWS;
   if (row0 >= p.row_end) return;
@@ -620,7 +623,7 @@ __global__ __launch_bounds__(NW * 64, OCC) void f2_ln_bf16_kernel(F2LnParams p) 
 
   // now that everything else is in flight behind them, the first rows are reduced and written as
   // token fragments; further groups of rows follow
-  finish_gate_rows<H, D, GROUP, SM>(p, gr, lane, tok, wave * RPW, gw, ow);
+  finish_gate_rows<H, D, GROUP, SM, FRAG>(p, gr, lane, tok, wave * RPW, gw, ow);
 #pragma unroll
   for (int r0 = GROUP; r0 < RPW; r0 += GROUP) {
 #pragma unroll
@@ -628,7 +631,7 @@ __global__ __launch_bounds__(NW * 64, OCC) void f2_ln_bf16_kernel(F2LnParams p) 
       const int lr = wave * RPW + r0 + i;
       load_gate_row<D, SM>(p, row0 + lr, row0 + lr < p.row_end, lane, gr[i]);
     }
-    finish_gate_rows<H, D, GROUP, SM>(p, gr, lane, tok, wave * RPW + r0, gw, ow);
+    finish_gate_rows<H, D, GROUP, SM, FRAG>(p, gr, lane, tok, wave * RPW + r0, gw, ow);
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
@@ -641,7 +644,7 @@ __global__ __launch_bounds__(NW * 64, OCC) void f2_ln_bf16_kernel(F2LnParams p) 
       const int ks = (ks0 + i + rot) & (KS - 1);
       uint4 tf[RB];
 #pragma unroll
-      for (int b = 0; b < RB; ++b) tf[b] = *reinterpret_cast<const uint4*>(&tok[(b * KS + ks) * 512 + lane * 8]);
+      for (int b = 0; b < RB; ++b) tf[b] = *reinterpret_cast<const uint4*>(&tok[(b * KS + ks) * FRAG + lane * 8]);
 #pragma unroll
       for (int j = 0; j < FB; ++j)
 #pragma unroll
