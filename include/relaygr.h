@@ -281,6 +281,13 @@ int  relaygr_expander_retire(relaygr_expander* ex, relaygr_kv_handle handle, voi
  * RELAYGR_ENOSPC when live entries alone leave no room (Section 3.1, invariant I2).  A reclaimable
  * entry of the same user is replaced; RELAYGR_EINVAL if the user has a live one. */
 int  relaygr_expander_alloc(relaygr_expander* ex, uint64_t user_id, int32_t prefix_len, relaygr_kv_handle* out);
+/* Rate limit of DRAM -> HBM reloads (Section 3.4: reloads are rate-limited and scheduled with bounded
+ * concurrency): a token bucket of burst_bytes refilled at bytes_per_second on the host's monotonic
+ * clock.  A lookup that would reload an image is refused with RELAYGR_EBUSY while the bucket holds
+ * less than the image (or less than burst_bytes, for an image larger than the bucket); an accepted
+ * reload takes its bytes out, so the long-run rate holds.  bytes_per_second = 0 lifts the limit (the
+ * state of a new expander).  RELAYGR_EINVAL for negative values or a rate without a burst size. */
+int  relaygr_expander_set_reload_rate(relaygr_expander* ex, double bytes_per_second, double burst_bytes);
 /* Releases reclaimable entries, oldest retirement first, until at most `keep` remain in HBM. */
 int  relaygr_expander_trim(relaygr_expander* ex, int32_t keep);
 /* The idempotent probe issued before every rank (pseudo-pre-infer): *source = 0 and the live handle if
@@ -288,7 +295,8 @@ int  relaygr_expander_trim(relaygr_expander* ex, int32_t keep);
  * this very entry is still in flight, never for other users' copies); *source = 1 if it was found in DRAM, in which
  * case an entry is allocated (as by relaygr_expander_alloc), the reload is enqueued on the copy stream and hip_stream is made to wait
  * for it (no host wait); RELAYGR_ENOENT if neither tier has it (the caller ranks by full recompute
- * or pre-infers); RELAYGR_EBUSY if the reload limit is reached (the caller falls back, nothing queued). */
+ * or pre-infers); RELAYGR_EBUSY if the limit of reloads in flight or the reload rate limit is reached
+ * (the caller falls back, nothing queued). */
 int  relaygr_expander_lookup(relaygr_expander* ex, uint64_t user_id, void* hip_stream, relaygr_kv_handle* out,
                              int32_t* source);
 /* Counters since creation: [0] HBM hits, [1] DRAM hits (reloads), [2] misses, [3] refusals (busy),

@@ -32,6 +32,7 @@ EXPORTS = [
     "relaygr_kv_pool_entry_bytes", "relaygr_kv_pool_spill", "relaygr_kv_pool_reload",
     "relaygr_expander_create", "relaygr_expander_destroy", "relaygr_expander_retire",
     "relaygr_expander_alloc", "relaygr_expander_trim", "relaygr_expander_lookup", "relaygr_expander_stats",
+    "relaygr_expander_set_reload_rate",
     "relaygr_admission_budget_compute", "relaygr_slot_throughput",
     "relaygr_trigger_create", "relaygr_trigger_destroy", "relaygr_trigger_admit", "relaygr_trigger_release",
     "relaygr_trigger_stats",
@@ -126,6 +127,7 @@ def load_library() -> C.CDLL:
         "relaygr_expander_retire": (C.c_int, [vp, u64, vp]),
         "relaygr_expander_alloc": (C.c_int, [vp, u64, i32, P(u64)]),
         "relaygr_expander_trim": (C.c_int, [vp, i32]),
+        "relaygr_expander_set_reload_rate": (C.c_int, [vp, C.c_double, C.c_double]),
         "relaygr_expander_lookup": (C.c_int, [vp, u64, vp, P(u64), P(i32)]),
         "relaygr_expander_stats": (C.c_int, [vp, P(i64)]),
         "relaygr_admission_budget_compute": (C.c_int, [P(AdmissionParamsC), P(AdmissionBudgetC)]),
@@ -379,6 +381,10 @@ def relaygr_expander_alloc(ex: Expander, user_id: int, prefix_len: int) -> int:
     out = C.c_uint64(0)
     _check(load_library().relaygr_expander_alloc(ex.handle, user_id, prefix_len, C.byref(out)))
     return out.value
+
+
+def relaygr_expander_set_reload_rate(ex: Expander, bytes_per_second: float, burst_bytes: float) -> None:
+    _check(load_library().relaygr_expander_set_reload_rate(ex.handle, C.c_double(bytes_per_second), C.c_double(burst_bytes)))
 
 
 def relaygr_expander_trim(ex: Expander, keep: int = 0) -> None:

@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <chrono>
 #include <deque>
 #include <mutex>
 #include <new>
@@ -102,6 +103,9 @@ struct relaygr_expander {
   std::vector<Reload> reloads;          // reloads that may still be in flight
   std::vector<hipEvent_t> spare_events;
   uint64_t clock = 0;
+  // reload rate limit: a token bucket in bytes (rate 0 = unlimited), refilled on the host's monotonic clock
+  double rate_bps = 0.0, burst_bytes = 0.0, tokens = 0.0;
+  std::chrono::steady_clock::time_point refilled;
   int64_t stats[6] = {};
   int64_t hbm_evictions = 0;
   std::mutex mu;
@@ -298,6 +302,17 @@ extern "C" int relaygr_expander_lookup(relaygr_expander* ex, uint64_t user_id, v
     return fail(RELAYGR_ENOENT, "expander_lookup: user %llu is in neither tier", (unsigned long long)user_id);
   }
   if ((int)ex->reloads.size() >= ex->max_inflight) { ex->stats[3] += 1; return fail(RELAYGR_EBUSY, "expander_lookup: %d reloads already in flight", ex->max_inflight); }
+  const double image_bytes = (double)slot.npages * (double)page_bytes(ex->hbm);
+  if (ex->rate_bps > 0.0) {
+    const auto now = std::chrono::steady_clock::now();
+    ex->tokens = std::min(ex->burst_bytes, ex->tokens + std::chrono::duration<double>(now - ex->refilled).count() * ex->rate_bps);
+    ex->refilled = now;
+    // an image larger than the bucket goes through when the bucket is full; the debt it leaves is paid off first
+    if (ex->tokens < std::min(image_bytes, ex->burst_bytes)) {
+      ex->stats[3] += 1;
+      return fail(RELAYGR_EBUSY, "expander_lookup: reload rate limit (%.0f bytes/s) reached", ex->rate_bps);
+    }
+  }
   int rc = alloc_in_window(ex, user_id, slot.prefix_len, &h);
   if (rc != RELAYGR_OK) return fail(rc, "expander_lookup: no free or reclaimable extent to reload %d tokens", slot.prefix_len);
   PoolEntry e;
@@ -311,6 +326,7 @@ extern "C" int relaygr_expander_lookup(relaygr_expander* ex, uint64_t user_id, v
   HIP_TRY(hipEventRecord(done, ex->copy_stream));
   HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, done, 0));
   ex->reloads.push_back({h, done});
+  if (ex->rate_bps > 0.0) ex->tokens -= image_bytes;
   ex->last_use[user_id] = ++ex->clock;
   ex->stats[1] += 1;
   *out = h;
@@ -335,6 +351,17 @@ extern "C" int relaygr_expander_alloc(relaygr_expander* ex, uint64_t user_id, in
   int rc = alloc_in_window(ex, user_id, prefix_len, out);
   if (rc == RELAYGR_ENOSPC) return fail(rc, "expander_alloc: live entries leave no extent for %d tokens", prefix_len);
   if (rc != RELAYGR_OK) return fail(rc, "expander_alloc: prefix_len < 1");
+  return RELAYGR_OK;
+}
+
+extern "C" int relaygr_expander_set_reload_rate(relaygr_expander* ex, double bytes_per_second, double burst_bytes) {
+  if (!ex || !(bytes_per_second >= 0.0) || !(burst_bytes >= 0.0) || (bytes_per_second > 0.0 && !(burst_bytes > 0.0)))
+    return fail(RELAYGR_EINVAL, "expander_set_reload_rate: null expander, negative rate, or a rate without a burst size");
+  std::lock_guard<std::mutex> lk(ex->mu);
+  ex->rate_bps = bytes_per_second;
+  ex->burst_bytes = burst_bytes;
+  ex->tokens = burst_bytes;
+  ex->refilled = std::chrono::steady_clock::now();
   return RELAYGR_OK;
 }
 

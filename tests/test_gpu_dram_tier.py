@@ -381,3 +381,51 @@ def test_hbm_hit_does_not_wait_for_another_users_copy():
     finally:
         ex.close()
         h.close()
+
+
+def test_expander_rate_limits_reloads():
+    """Section 3.4: reloads are rate-limited.  With a bucket of one image refilled at two images per second,
+    the second reload in a row is refused (nothing queued, the caller falls back) and goes through later."""
+    import time
+    h, weights, batch = _harness()
+    page = rg.relaygr_kv_pool_bytes_for(h.ctx.cfg, 64, 64)
+    ex = rg.Expander(h.pool, 64 * page, max_inflight_reloads=8)
+    try:
+        h.prefill()
+        base = {u: _rank_user(h, u, int(h.handles[u])) for u in (0, 2)}
+        for u in (0, 2):
+            rg.relaygr_expander_retire(ex, int(h.handles[u]))
+        _settle(ex)
+        rg.relaygr_expander_trim(ex, 0)                                    # both now live in DRAM only
+        image0 = 5 * page                                                  # user 0: 300 tokens = 5 pages; user 2: 200 tokens = 4 pages
+        with pytest.raises(rg.RelayGRError):
+            rg.relaygr_expander_set_reload_rate(ex, -1.0, 1.0)
+        with pytest.raises(rg.RelayGRError):
+            rg.relaygr_expander_set_reload_rate(ex, 10.0, 0.0)
+        rg.relaygr_expander_set_reload_rate(ex, 2.0 * image0, float(image0))
+        h0, src = rg.relaygr_expander_lookup(ex, _uid(batch, 0))
+        assert src == 1
+        with pytest.raises(rg.RelayGRError) as ei:
+            rg.relaygr_expander_lookup(ex, _uid(batch, 2))                  # the bucket is empty
+        assert ei.value.code == rg.RELAYGR_EBUSY and "rate limit" in str(ei.value)
+        assert rg.relaygr_kv_pool_lookup(h.pool, _uid(batch, 2)) == rg.RELAYGR_NO_CACHE   # nothing was allocated or queued
+        st = _settle(ex)
+        assert st["refusals"] == 1 and st["dram_hits"] == 1
+        time.sleep(0.6)                                                    # refills 1.2 images, capped at one
+        h2, src = rg.relaygr_expander_lookup(ex, _uid(batch, 2))
+        assert src == 1
+        assert np.array_equal(_rank_user(h, 0, h0), base[0]) and np.array_equal(_rank_user(h, 2, h2), base[2])
+        # a hit in HBM costs nothing, and lifting the limit lifts it
+        for _ in range(3):
+            assert rg.relaygr_expander_lookup(ex, _uid(batch, 0)) == (h0, 0)
+        rg.relaygr_expander_set_reload_rate(ex, 0.0, 0.0)
+        for hh in (h0, h2):
+            rg.relaygr_expander_retire(ex, hh)
+        _settle(ex)
+        rg.relaygr_expander_trim(ex, 0)
+        for u in (0, 2):
+            assert rg.relaygr_expander_lookup(ex, _uid(batch, u))[1] == 1
+        assert _settle(ex)["refusals"] == 1
+    finally:
+        ex.close()
+        h.close()
