@@ -346,18 +346,6 @@ int  relaygr_trigger_admit(relaygr_trigger* t, double now_s, int32_t prefix_len)
 int  relaygr_trigger_release(relaygr_trigger* t);
 int  relaygr_trigger_stats(relaygr_trigger* t, int64_t* live, int64_t* admitted, int64_t* refused, int64_t* not_at_risk);
 
-/* ---- diagnostics ----------------------------------------------------------------------------- */
-
-/* Device bytes relaygr_probe_mfma needs as its work buffer. */
-size_t relaygr_probe_bytes(void);
-/* Measures what the chip sustains on the hot path's MFMA (v_mfma_f32_32x32x16_bf16) in a pure
- * MFMA loop of 512 workgroups x 4 wavefronts x iters x 8 instructions, operands constant
- * (random_data = 0) or pseudo-random: dense TFLOP/s from HIP events on hip_stream, and the shader
- * clock (GHz) from the cycle counter against the 100 MHz wall counter.  Synchronises with the
- * stream.  work_dev: DEVICE scratch of at least relaygr_probe_bytes(), contents destroyed. */
-int  relaygr_probe_mfma(void* work_dev, size_t work_bytes, int32_t random_data, int32_t iters, void* hip_stream,
-                        double* tflops, double* shader_ghz);
-
 /* Text of the calling thread's last failure ("" if none).  Valid until the thread's next call. */
 const char* relaygr_last_error(void);
 

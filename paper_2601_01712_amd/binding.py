@@ -36,7 +36,6 @@ EXPORTS = [
     "relaygr_admission_budget_compute", "relaygr_slot_throughput",
     "relaygr_trigger_create", "relaygr_trigger_destroy", "relaygr_trigger_admit", "relaygr_trigger_release",
     "relaygr_trigger_stats",
-    "relaygr_probe_bytes", "relaygr_probe_mfma",
     "relaygr_last_error",
 ]
 EXPANDER_STATS = ["hbm_hits", "dram_hits", "misses", "refusals", "spills", "dram_evictions", "dram_bytes", "dram_entries",
@@ -137,8 +136,6 @@ def load_library() -> C.CDLL:
         "relaygr_trigger_admit": (C.c_int, [vp, C.c_double, i32]),
         "relaygr_trigger_release": (C.c_int, [vp]),
         "relaygr_trigger_stats": (C.c_int, [vp, P(i64), P(i64), P(i64), P(i64)]),
-        "relaygr_probe_bytes": (sz, []),
-        "relaygr_probe_mfma": (C.c_int, [vp, sz, i32, i32, vp, P(C.c_double), P(C.c_double)]),
         "relaygr_last_error": (C.c_char_p, []),
     }
     for name, (res, args) in sig.items():
@@ -410,9 +407,7 @@ def relaygr_admission_budget_compute(q_m: float, model_slots: int, kv_p99_bytes:
                                      n_instances: int, r2: float, t_life_s: float) -> dict:
     p = AdmissionParamsC(q_m, model_slots, kv_p99_bytes, hbm_bytes, r1, n_instances, r2, t_life_s)
     b = AdmissionBudgetC()
-    rc = load_library().relaygr_admission_budget_compute(C.byref(p), C.byref(b))
-    if rc != RELAYGR_OK:
-        raise RelayGRError(rc, "relaygr_admission_budget_compute: parameter out of range")
+    _check(load_library().relaygr_admission_budget_compute(C.byref(p), C.byref(b)))
     return {n: getattr(b, n) for n, _ in AdmissionBudgetC._fields_}
 
 
@@ -426,9 +421,7 @@ class Trigger:
     def __init__(self, budget: dict, len_threshold: int):
         b = AdmissionBudgetC(*[budget[n] for n, _ in AdmissionBudgetC._fields_])
         h = C.c_void_p()
-        rc = load_library().relaygr_trigger_create(C.byref(b), len_threshold, C.byref(h))
-        if rc != RELAYGR_OK:
-            raise RelayGRError(rc, "relaygr_trigger_create: bad budget or threshold")
+        _check(load_library().relaygr_trigger_create(C.byref(b), len_threshold, C.byref(h)))
         self.handle = h
 
     def close(self):
@@ -446,34 +439,18 @@ class Trigger:
 def relaygr_trigger_admit(t: Trigger, now_s: float, prefix_len: int) -> int:
     rc = load_library().relaygr_trigger_admit(t.handle, now_s, prefix_len)
     if rc < 0:
-        raise RelayGRError(rc, "relaygr_trigger_admit: bad argument")
+        _check(rc)
     return rc
 
 
 def relaygr_trigger_release(t: Trigger) -> None:
-    rc = load_library().relaygr_trigger_release(t.handle)
-    if rc != RELAYGR_OK:
-        raise RelayGRError(rc, "relaygr_trigger_release: no live cache to release")
+    _check(load_library().relaygr_trigger_release(t.handle))
 
 
 def relaygr_trigger_stats(t: Trigger) -> dict:
     a, b, c, d = C.c_int64(), C.c_int64(), C.c_int64(), C.c_int64()
     load_library().relaygr_trigger_stats(t.handle, C.byref(a), C.byref(b), C.byref(c), C.byref(d))
     return {"live": a.value, "admitted": b.value, "refused": c.value, "not_at_risk": d.value}
-
-
-# ---- diagnostics -------------------------------------------------------------------------------
-def relaygr_probe_bytes() -> int:
-    return load_library().relaygr_probe_bytes()
-
-
-def relaygr_probe_mfma(random_data: bool, iters: int = 20000, device: str = "cuda:0", stream=None) -> dict:
-    """Sustained dense TFLOP/s and shader clock (GHz) of a pure MFMA loop."""
-    work = torch.empty(relaygr_probe_bytes(), dtype=torch.uint8, device=device)
-    tf, ghz = C.c_double(), C.c_double()
-    _check(load_library().relaygr_probe_mfma(work.data_ptr(), work.numel(), int(bool(random_data)), iters, _stream_ptr(stream),
-                                             C.byref(tf), C.byref(ghz)))
-    return {"tflops": tf.value, "shader_ghz": ghz.value}
 
 
 class Batch:

@@ -8,7 +8,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librelaygr.so")
-SOURCES = ["engine.hip", "kv_pool.cpp", "expander.hip", "admission.cpp", "probe.hip"]
+SOURCES = ["engine.hip", "kv_pool.cpp", "expander.hip", "admission.cpp"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -5,13 +5,18 @@
 #include <new>
 
 #include "../../include/relaygr.h"
+#include "errors.h"
+
+using relaygr::fail;
 
 extern "C" int relaygr_admission_budget_compute(const relaygr_admission_params* p, relaygr_admission_budget* out) {
-  if (!p || !out) return RELAYGR_EINVAL;
+  if (!p || !out) return fail(RELAYGR_EINVAL, "admission_budget_compute: null argument");
   if (!(p->q_m > 0) || p->model_slots < 1 || !(p->kv_p99_bytes > 0) || !(p->hbm_bytes > 0) || !(p->r1 > 0 && p->r1 <= 1) ||
       p->n_instances < 1 || !(p->r2 > 0 && p->r2 <= 1) || !(p->t_life_s > 0))
-    return RELAYGR_EINVAL;
-  // Eq. 2: L * kv_p99 <= r1 * HBM
+    return fail(RELAYGR_EINVAL, "admission_budget_compute: parameter out of range (rates, sizes and the window must be positive, "
+                                "r1 and r2 in (0, 1], at least one slot and one instance)");
+  // Eq. 2: L * kv_p99 <= r1 * HBM.  The quotient of two doubles may land a rounding error below the integer the
+  // caller's decimal figures give exactly (0.5 * 32 GB / 0.1 GB), hence the slack of 1e-9 of a cache before the floor.
   out->max_live_caches = std::floor(p->r1 * p->hbm_bytes / p->kv_p99_bytes + 1e-9);
   // Eq. 1: L = Q_admit * T_life  =>  Q_admit <= L_max / T_life
   out->q_admit_hbm = out->max_live_caches / p->t_life_s;
@@ -39,9 +44,11 @@ struct relaygr_trigger {
 };
 
 extern "C" int relaygr_trigger_create(const relaygr_admission_budget* b, int32_t len_threshold, relaygr_trigger** out) {
-  if (!b || !out || len_threshold < 0 || !(b->q_admit > 0) || !(b->max_live_caches >= 1)) return RELAYGR_EINVAL;
+  if (!b || !out) return fail(RELAYGR_EINVAL, "trigger_create: null argument");
+  if (len_threshold < 0 || !(b->q_admit > 0) || !(b->max_live_caches >= 1))
+    return fail(RELAYGR_EINVAL, "trigger_create: needs len_threshold >= 0, q_admit > 0 and max_live_caches >= 1");
   relaygr_trigger* t = new (std::nothrow) relaygr_trigger();
-  if (!t) return RELAYGR_EINVAL;
+  if (!t) return fail(RELAYGR_EINVAL, "trigger_create: out of host memory");
   t->budget = *b;
   t->len_threshold = len_threshold;
   t->tokens = std::fmax(1.0, b->q_admit);
@@ -54,7 +61,7 @@ extern "C" int relaygr_trigger_create(const relaygr_admission_budget* b, int32_t
 extern "C" void relaygr_trigger_destroy(relaygr_trigger* t) { delete t; }
 
 extern "C" int relaygr_trigger_admit(relaygr_trigger* t, double now_s, int32_t prefix_len) {
-  if (!t) return RELAYGR_EINVAL;
+  if (!t) return fail(RELAYGR_EINVAL, "trigger_admit: null trigger");
   std::lock_guard<std::mutex> lk(t->mu);
   if (prefix_len < t->len_threshold) { t->not_at_risk += 1; return RELAYGR_TRIGGER_NOT_AT_RISK; }
   const double cap = std::fmax(1.0, t->budget.q_admit);
@@ -69,15 +76,15 @@ extern "C" int relaygr_trigger_admit(relaygr_trigger* t, double now_s, int32_t p
 }
 
 extern "C" int relaygr_trigger_release(relaygr_trigger* t) {
-  if (!t) return RELAYGR_EINVAL;
+  if (!t) return fail(RELAYGR_EINVAL, "trigger_release: null trigger");
   std::lock_guard<std::mutex> lk(t->mu);
-  if (t->live <= 0) return RELAYGR_ENOENT;
+  if (t->live <= 0) return fail(RELAYGR_ENOENT, "trigger_release: no live cache to release");
   t->live -= 1;
   return RELAYGR_OK;
 }
 
 extern "C" int relaygr_trigger_stats(relaygr_trigger* t, int64_t* live, int64_t* admitted, int64_t* refused, int64_t* not_at_risk) {
-  if (!t) return RELAYGR_EINVAL;
+  if (!t) return fail(RELAYGR_EINVAL, "trigger_stats: null trigger");
   std::lock_guard<std::mutex> lk(t->mu);
   if (live) *live = t->live;
   if (admitted) *admitted = t->admitted;

@@ -61,6 +61,39 @@ def test_library_budgets_equal_oracle_on_random_parameters():
         assert L * kv <= r1 * hbm * (1 + 1e-9) and (L + 1) * kv > r1 * hbm * (1 - 1e-9)
 
 
+def test_live_cache_bound_at_exact_quotients():
+    """Eq. 2 where r1 * HBM / kv_p99 is an integer: once exactly representable in binary (0.5 * 32 / 0.125 = 128),
+    once only in decimal (the paper's 0.5 * 32 / 0.1 = 160, whose double quotient need not be 160.0), in GB and in
+    bytes; one byte more per cache must cost one cache.  The oracle works in exact rationals of the decimal text,
+    the library in doubles with a slack: two different routes to the same integers."""
+    for kv_gb, hbm_gb, r1, want in ((0.125, 32.0, 0.5, 128), (0.1, 32.0, 0.5, 160), (0.3, 288.0, 0.25, 240), (0.7, 64.0, 0.7, 64)):
+        for unit in (1.0, 1e9):
+            kv, hbm = kv_gb * unit, hbm_gb * unit
+            assert oadm.live_cache_bound(kv, hbm, r1) == want, (kv_gb, unit)
+            got = rg.relaygr_admission_budget_compute(30.0, 5, kv, hbm, r1, 100, 0.1, 1.0)
+            assert got["max_live_caches"] == want, (kv_gb, unit)
+        assert oadm.live_cache_bound(kv_gb * 1e9 + 1, hbm_gb * 1e9, r1) == want - 1
+        assert rg.relaygr_admission_budget_compute(30.0, 5, kv_gb * 1e9 + 1, hbm_gb * 1e9, r1, 100, 0.1, 1.0)["max_live_caches"] == want - 1
+    # brute force over small integers: the bound is floor(a / b)
+    for a in range(1, 40):
+        for b in range(1, 12):
+            assert oadm.live_cache_bound(float(b), float(a), 1.0) == a // b
+
+
+def test_failures_leave_their_text_in_last_error():
+    with pytest.raises(rg.RelayGRError) as ei:
+        rg.relaygr_admission_budget_compute(30.0, 5, 1e8, 32e9, 1.5, 100, 0.1, 1.0)
+    assert "admission_budget_compute" in str(ei.value) and "r1" in str(ei.value)
+    t = _trigger(10.0, 3)
+    with pytest.raises(rg.RelayGRError) as ei:
+        rg.relaygr_trigger_release(t)
+    assert ei.value.code == rg.RELAYGR_ENOENT and "trigger_release" in str(ei.value)
+    t.close()
+    with pytest.raises(rg.RelayGRError) as ei:
+        _trigger(0.0, 10)
+    assert "trigger_create" in str(ei.value)
+
+
 @pytest.mark.parametrize("bad", [dict(q_m=0.0), dict(model_slots=0), dict(kv_p99_bytes=0.0), dict(hbm_bytes=-1.0),
                                  dict(r1=0.0), dict(r1=1.5), dict(n_instances=0), dict(r2=0.0), dict(t_life_s=0.0)])
 def test_budget_rejects_out_of_range_parameters(bad):

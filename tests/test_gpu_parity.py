@@ -240,11 +240,3 @@ def test_scratch_too_small_is_an_error_not_a_fault():
         assert e.value.code == rg.RELAYGR_ENOSPC
     finally:
         ctx.close()
-
-
-def test_mfma_probe_reports_a_plausible_rate():
-    """The diagnostic probe behind bench.py's sustained-rate figures: sane numbers, bad arguments refused."""
-    r = rg.relaygr_probe_mfma(True, iters=2000)
-    assert 100.0 < r["tflops"] < 2600.0 and 0.5 < r["shader_ghz"] < 3.0
-    with pytest.raises(rg.RelayGRError):
-        rg.relaygr_probe_mfma(True, iters=0)
