@@ -105,10 +105,10 @@ def small_m_sweep(torch, rg, synth, n_users=128, L=8192, Ms=(16, 32, 64, 128), s
 
 def single_request_breakdown(torch, rg, synth, cfg, weights, shapes=((1024, 512), (2048, 512), (4096, 128), (4096, 512), (4096, 1024), (4096, 2048), (8192, 512),
                                     (8192, 2048), (15360, 512)), reps=15):
-    """The paper's per-request latency components (Section 5.2, pre / load / rank) for ONE user per call on the
+    """The paper's per-request latency components (Section 4.2, pre / load / rank) for ONE user per call on the
     benchmark model: prefix pre-inference, reload of psi from pinned host memory, ranking on the cached prefix,
     and the baseline's full inference inline, over the paper's two sweeps: prefix length at about 512 candidates
-    (Section 5.3) and candidate count at a fixed prefix (Section 5.4).  Median of `reps` calls each, HIP events on
+    (Section 4.3) and candidate count at a fixed prefix (Section 4.4).  Median of `reps` calls each, HIP events on
     the call's stream."""
     Lmax = max(L for L, _ in shapes)
     Mmax = max(M for _, M in shapes)
@@ -387,7 +387,7 @@ def main() -> int:
         del ctx2, pool2, pre2
         torch.cuda.empty_cache()
 
-    # ---- the DRAM tier's `load` step (Section 3.4; the load column of the latency breakdown, Section 5.5): one user's psi
+    # ---- the DRAM tier's `load` step (Section 3.4; the load component of the latency breakdown, Section 4.2 "Where the savings come from"): one user's psi
     # spilled to pinned host memory, its extent freed, the image reloaded, and the same ranking repeated on it
     dram = None
     if not args.no_dram and hit:

@@ -32,10 +32,14 @@
  *     current device; "host" pointers are ordinary process memory.
  *   - The caller owns every device buffer (weights, embeddings, the pool slab,
  *     the scratch buffer, the score output).  The library allocates no device
- *     memory; it owns host-side metadata and a small pinned staging area.
+ *     memory; it owns host-side metadata and, per context, a small pinned staging
+ *     area allocated in relaygr_ctx_create (no compute call allocates or frees).
  *   - Compute calls enqueue work on the given HIP stream and return without
- *     synchronising.  Buffers passed to a call must stay valid and unmodified
- *     until that stream has passed the call's work.  A context is one model slot:
+ *     synchronising the device or the stream.  One bounded host wait exists: a
+ *     call's batch descriptors go through a ring of four pinned staging slots, so
+ *     the fifth call in a row waits until the upload of the first has completed
+ *     (microseconds once the stream has reached it).  Buffers passed to a call
+ *     must stay valid and unmodified until that stream has passed the call's work.  A context is one model slot:
  *     it must not be used from two streams or two threads at once (its scratch
  *     buffer and staging area are shared by its calls); several contexts may share
  *     one pool, whose calls (and the expander's and trigger's) are thread-safe.
@@ -45,7 +49,7 @@
  *     in fp32; RELAYGR_DTYPE_BF16 and RELAYGR_DTYPE_FP16 store weights, embeddings,
  *     activations and cached K/V as bfloat16 / IEEE half and accumulate, normalise and
  *     keep the residual stream in fp32 (fp16 is the half precision the paper mentions,
- *     Section 5.2; values beyond its range of 65504 are the caller's concern).  Scores
+ *     Section 4.2; values beyond its range of 65504 are the caller's concern).  Scores
  *     are always fp32.
  *   - Constraints checked at context creation: d_model in {64, 128, 256, 512, 1024}
  *     (bf16, fp16: at least 128); d_head = d_model / n_heads in {32, 64, 128} and at least
@@ -124,7 +128,7 @@ typedef struct {
 /* ---- sizes -------------------------------------------------------------------------- */
 
 /* Exact bytes of psi for one user: 2 (K and V) * n_layers * prefix_len * d_model * element size
- * (Section 5.1 "Cache semantics": 2K tokens, 8 layers, d 256, fp32 -> 32 MB).  0 on bad input. */
+ * (Section 4.1 "Cache semantics": 2K tokens, 8 layers, d 256, fp32 -> 32 MB).  0 on bad input. */
 size_t relaygr_kv_footprint_bytes(const relaygr_model_config* cfg, int32_t prefix_len);
 
 /* Bytes the same psi occupies in a pool whose pages hold page_tokens tokens (page-rounded). */
@@ -140,13 +144,15 @@ size_t relaygr_scratch_bytes(const relaygr_model_config* cfg, int32_t max_users,
 
 /* Binds a model (config + device weights) to a caller-owned device scratch buffer of
  * scratch_bytes (256-byte aligned).  Weight memory is referenced (biases, LayerNorm and
- * score-head parameters are read from it on every call), so it must outlive the context. */
+ * score-head parameters are read from it on every call), so it must outlive the context.
+ * The pinned staging for batch descriptors is sized here from scratch_bytes (what a call that fits
+ * the buffer can need); a call with more users or row tiles than that is RELAYGR_ENOSPC. */
 int  relaygr_ctx_create(const relaygr_model_config* cfg, const relaygr_weights* weights,
                         void* scratch_dev, size_t scratch_bytes, relaygr_ctx** out);
 void relaygr_ctx_destroy(relaygr_ctx* ctx);
 
 /* Attention form of a context's backbone.  The paper evaluates a second backbone that differs
- * from the first only in its attention computation (Section 5.4) and gives no formula for it;
+ * from the first only in its attention computation (Section 4.4) and gives no formula for it;
  * this library's reading of it is a softmax over the visible keys,
  *   o_i^h = sum_j m_ij exp(alpha <q_i^h, k_j^h>) v_j^h / sum_j m_ij exp(alpha <q_i^h, k_j^h>),
  * in place of sum_j m_ij SiLU(alpha <q_i^h, k_j^h>) v_j^h / n_i; projections, visibility, gate,
@@ -196,7 +202,8 @@ int  relaygr_kv_pool_locate(relaygr_kv_pool* pool, relaygr_kv_handle handle, int
 /* stage = pre-infer.  For every user of the batch: run the backbone over prefix_emb rows of that
  * user and write every layer's K and V into the pool entry handles[u], whose length must equal
  * the user's prefix length.  Suffix and candidate segments are ignored.  No output besides the
- * pool contents.  RELAYGR_ENOENT if a handle is stale, RELAYGR_ENOSPC if scratch is too small. */
+ * pool contents.  RELAYGR_ENOENT if a handle is stale, RELAYGR_ENOSPC if scratch is too small,
+ * RELAYGR_EINVAL if two users of the batch carry the same handle (nothing is enqueued). */
 int  relaygr_prefill_prefix(relaygr_ctx* ctx, relaygr_kv_pool* pool, const relaygr_batch* batch,
                             void* hip_stream);
 
@@ -211,7 +218,7 @@ int  relaygr_prefill_prefix(relaygr_ctx* ctx, relaygr_kv_pool* pool, const relay
 int  relaygr_rank_with_cache(relaygr_ctx* ctx, relaygr_kv_pool* pool, const relaygr_batch* batch,
                              float* scores_dev, void* hip_stream);
 
-/* Baseline: full inference inline for every user (Section 5.1 "Baselines"); handles are ignored
+/* Baseline: full inference inline for every user (Section 4.1 "Baselines"); handles are ignored
  * and no pool is touched.  Same output as relaygr_rank_with_cache. */
 int  relaygr_rank_full_recompute(relaygr_ctx* ctx, const relaygr_batch* batch,
                                  float* scores_dev, void* hip_stream);
@@ -259,15 +266,16 @@ int  relaygr_kv_pool_reload(relaygr_kv_pool* pool, uint64_t user_id, int32_t pre
  * dram_budget_bytes (rounded down to whole pool pages; 0 = no DRAM tier) allocated at creation and
  * freed at destruction; images are placed in it like entries in the pool, least recently used
  * dropped first when an image does not fit.  At most max_inflight_reloads reloads are in flight and
- * a user has at most one copy per tier.  Calls are thread-safe; copies run on a stream the expander
- * owns (default priority), ordered against the caller's streams with events, never host waits. */
+ * a user has at most one copy per tier.  Calls are thread-safe; copies run on two streams the expander
+ * owns (default priority; one for spills, one for reloads, so that a reload never queues behind other
+ * users' spills), ordered against each other and the caller's streams with events, never host waits. */
 typedef struct relaygr_expander relaygr_expander;
 int  relaygr_expander_create(relaygr_kv_pool* pool, size_t dram_budget_bytes, int32_t max_inflight_reloads,
                              relaygr_expander** out);
 /* Waits for the expander's outstanding copies, frees its DRAM.  Pool entries stay as they are. */
 void relaygr_expander_destroy(relaygr_expander* ex);
 /* After ranking has consumed an entry: once hip_stream has passed this point the entry is copied to
- * DRAM on the expander's own copy stream.  When that copy has completed (observed at a later
+ * DRAM on the expander's own spill stream.  When that copy has completed (observed at a later
  * expander call) the entry becomes RECLAIMABLE: it stays in HBM, still found by
  * relaygr_expander_lookup (which makes it live again), until relaygr_expander_alloc or a reload
  * needs its pages; reclaimable entries leave oldest retirement first.  The caller must not use the
@@ -293,7 +301,7 @@ int  relaygr_expander_trim(relaygr_expander* ex, int32_t keep);
 /* The idempotent probe issued before every rank (pseudo-pre-infer): *source = 0 and the live handle if
  * psi is in HBM (a pending retire of it is cancelled; hip_stream is made to wait only if a reload of
  * this very entry is still in flight, never for other users' copies); *source = 1 if it was found in DRAM, in which
- * case an entry is allocated (as by relaygr_expander_alloc), the reload is enqueued on the copy stream and hip_stream is made to wait
+ * case an entry is allocated (as by relaygr_expander_alloc), the reload is enqueued on the expander's reload stream and hip_stream is made to wait
  * for it (no host wait); RELAYGR_ENOENT if neither tier has it (the caller ranks by full recompute
  * or pre-infers); RELAYGR_EBUSY if the limit of reloads in flight or the reload rate limit is reached
  * (the caller falls back, nothing queued). */

@@ -9,7 +9,7 @@ dozen tokens.
 
 Sequence: [prefix | suffix | candidates] (Section 2.3).  Token i may use key j
 when j <= i and j is not another candidate.  With cfg.attention == "softmax"
-(the reading of the backbone variant of Section 5.4) the weight of key j is
+(the reading of the backbone variant of Section 4.4) the weight of key j is
 exp(alpha q.k_j) over the sum of the same over the visible keys, instead of
 SiLU(alpha q.k_j) / n_i.
 """

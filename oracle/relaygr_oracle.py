@@ -10,7 +10,7 @@ What the paper fixes (Section 2.3, the relay-race identity, and Section 3.1,
 per-layer K/V of the backbone over the long-term prefix, a deterministic
 function of the prefix tokens and the weights that does not depend on the
 candidates; and f evaluated on the incremental tokens with psi must equal f
-evaluated on the whole sequence up to a small deviation.  Section 5.1 ("Models
+evaluated on the whole sequence up to a small deviation.  Section 4.1 ("Models
 and workloads", "Cache semantics") names the backbone family (HSTU-style) and
 fixes the cache as one K and one V of width d per layer and token.
 
@@ -36,7 +36,7 @@ Under this mask row i < L of every layer depends on p_0..p_i only, so the
 prefix K/V are candidate-independent and the identity holds with zero deviation
 in exact arithmetic.
 
-Second attention form.  Section 5.4 evaluates a variant of the backbone that
+Second attention form.  Section 4.4 evaluates a variant of the backbone that
 differs from the first only in how attention is computed and gives no formula
 for it.  The reading used here (cfg.attention == "softmax") replaces the
 pointwise activation and the 1/n_i by a softmax over the visible keys,
@@ -217,5 +217,5 @@ def rank_with_kv(cfg, weights: dict, psi: Sequence[Tuple[torch.Tensor, torch.Ten
 
 
 def kv_footprint_bytes(n_layers: int, prefix_len: int, d_model: int, elem_bytes: int) -> int:
-    """Bytes of psi for one user: K and V, every layer, every prefix token (Section 5.1, Table 'KV caches')."""
+    """Bytes of psi for one user: K and V, every layer, every prefix token (Section 4.1, Table 'KV caches')."""
     return 2 * n_layers * prefix_len * d_model * elem_bytes

@@ -5,7 +5,7 @@
 // workgroups needs no renormalisation -- partial sums are added later in fixed split order, the
 // candidate's self term and the 1/n_i are applied there too.
 //
-// Second form (SOFTMAX template flag; the backbone variant of Section 5.4 read as a softmax over
+// Second form (SOFTMAX template flag; the backbone variant of Section 4.4 read as a softmax over
 // the visible keys): the kernels produce, per row, head and key split, a reference score m, the
 // sum l of exp(s_j - m) over the split's visible keys and the sum of exp(s_j - m) v_j; m is a
 // running maximum, so nothing overflows, and the splits and the candidate's own key are merged

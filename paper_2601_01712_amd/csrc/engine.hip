@@ -110,7 +110,7 @@ static int prefix_row_align(const relaygr_model_config& c) { return is_half16(c)
 static void carve(const relaygr_model_config& c, Plan& p) {
   const size_t d = c.d_model, e = elem_bytes(c), R = p.n_rows;
   const size_t Rp = (R + 255) / 256 * 256;     // the bf16 GEMMs read whole 256-row tiles of xh
-  size_t o = wpack_bytes(c);
+  size_t o = 0;   // offsets are relative to the call scratch, which follows the packed weights in a context's buffer
   auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
   p.off_x = take(R * d * 4);
   p.off_xh = take(Rp * d * e);
@@ -159,13 +159,14 @@ extern "C" size_t relaygr_scratch_bytes(const relaygr_model_config* cfg, int32_t
   p.n_tiles_prefix = (int)(padded / rpt) + max_users;
   p.nsplit = 1;
   carve(*cfg, p);
-  size_t base = p.total;
+  size_t base = wpack_bytes(*cfg) + p.total;
   // head-room so that small calls may split their key range 8 ways
   size_t small_rows = std::min<size_t>((size_t)p.n_rows, 8192);
   return base + align_up(small_rows * 7 * ((size_t)cfg->d_model * 4 + (size_t)cfg->n_heads * 8));
 }
 
 // ---- context ----------------------------------------------------------------------------------
+constexpr int kStagingSlots = 4;
 struct StagingSlot {
   void* host = nullptr;
   size_t bytes = 0;
@@ -189,12 +190,15 @@ struct relaygr_ctx {
   std::vector<relaygr_layer_weights> layers;
   const void *ln_out_g, *ln_out_b, *w_score;
   float b_score;
-  char* scratch;
+  char* scratch;                        // the caller's buffer: [packed weights | call scratch]
   size_t scratch_bytes;
   std::vector<const uint16_t*> w1_packed, w2_packed;   // bf16: panels at the start of scratch
-  StagingSlot staging[4];
+  StagingSlot staging[kStagingSlots];   // pinned, allocated once at creation
   int next_slot = 0;
 };
+
+// Device memory one call lays its buffers out in (the part of a context's buffer behind the packed weights).
+struct CallScratch { char* base; size_t bytes; };
 
 extern "C" int relaygr_ctx_create(const relaygr_model_config* cfg, const relaygr_weights* w, void* scratch_dev,
                                   size_t scratch_bytes, relaygr_ctx** out) {
@@ -215,10 +219,10 @@ extern "C" int relaygr_ctx_create(const relaygr_model_config* cfg, const relaygr
   c->ln_out_g = w->ln_out_g; c->ln_out_b = w->ln_out_b; c->w_score = w->w_score; c->b_score = w->b_score;
   c->scratch = (char*)scratch_dev;
   c->scratch_bytes = scratch_bytes;
+  if (scratch_bytes < wpack_bytes(*cfg)) { delete c; return fail(RELAYGR_ENOSPC, "ctx_create: scratch smaller than the packed weights"); }
   if (is_half16(*cfg)) {
     // re-pack W1 and W2 of every layer into MFMA panels, once
     const size_t d = cfg->d_model;
-    if (scratch_bytes < wpack_bytes(*cfg)) { delete c; return fail(RELAYGR_ENOSPC, "ctx_create: scratch smaller than the packed weights"); }
     uint16_t* wp = (uint16_t*)scratch_dev;
     for (int l = 0; l < cfg->n_layers; ++l) {
       uint16_t* w1p = wp + (size_t)l * 5 * d * d;
@@ -233,6 +237,27 @@ extern "C" int relaygr_ctx_create(const relaygr_model_config* cfg, const relaygr
     }
     hipError_t e = hipDeviceSynchronize();
     if (e != hipSuccess) { delete c; return fail(RELAYGR_EHIP, "ctx_create: packing weights: %s", hipGetErrorString(e)); }
+  }
+  // Pinned staging for the per-call descriptor blob, sized once from what the scratch buffer can hold: a call
+  // has at most one row per d*4 bytes of call scratch (the residual stream alone takes that), one attention
+  // work item per 64 rows plus two per user, and a buffer sized by relaygr_scratch_bytes for max_users holds
+  // two K/V tiles per user; calls beyond that are refused (RELAYGR_ENOSPC), so no compute call allocates.
+  {
+    const size_t call_bytes = scratch_bytes - wpack_bytes(*cfg);
+    const size_t d = cfg->d_model, e = elem_bytes(*cfg);
+    const size_t rows_est = call_bytes / (d * 4) + 1;
+    const size_t users_est = std::min<size_t>(call_bytes / (4 * kTile * d * e) + 1, 1 << 16);
+    const size_t tiles_est = rows_est / 64 + 2 * users_est;
+    const size_t want = align_up(users_est * sizeof(UserDesc)) + 2 * align_up((users_est + 1) * 4) + align_up(tiles_est * sizeof(AttnTile));
+    for (auto& sl : c->staging) {
+      hipError_t e1 = hipHostMalloc(&sl.host, want, hipHostMallocDefault);
+      hipError_t e2 = e1 == hipSuccess ? hipEventCreateWithFlags(&sl.done, hipEventDisableTiming) : e1;
+      if (e1 != hipSuccess || e2 != hipSuccess) {
+        relaygr_ctx_destroy(c);
+        return fail(RELAYGR_EHIP, "ctx_create: pinned staging of %zu bytes: %s", want, hipGetErrorString(e1 != hipSuccess ? e1 : e2));
+      }
+      sl.bytes = want;
+    }
   }
   *out = c;
   return RELAYGR_OK;
@@ -256,19 +281,16 @@ extern "C" void relaygr_ctx_destroy(relaygr_ctx* c) {
   delete c;
 }
 
-// Pinned staging for the descriptor blob: a ring of 4, each guarded by an event so that a slot is
-// not rewritten while an earlier call's copy may still read it.
+// Pinned staging for the descriptor blob: a ring of slots allocated at context creation, each guarded by an
+// event so that a slot is not rewritten while an earlier call's copy may still read it.  The only host wait of
+// a compute call is here: when the upload of the call kStagingSlots calls ago has not completed yet.
 static int staging_acquire(relaygr_ctx* c, size_t bytes, StagingSlot** out) {
   StagingSlot& s = c->staging[c->next_slot];
-  c->next_slot = (c->next_slot + 1) & 3;
-  if (!s.done) HIP_TRY(hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
+  if (s.bytes < bytes)
+    return fail(RELAYGR_ENOSPC, "batch descriptors need %zu bytes of staging, the context holds %zu (sized from its scratch buffer: "
+                "too many users or row tiles for one call)", bytes, s.bytes);
+  c->next_slot = (c->next_slot + 1) % kStagingSlots;
   if (s.pending) { HIP_TRY(hipEventSynchronize(s.done)); s.pending = false; }
-  if (s.bytes < bytes) {
-    if (s.host) { HIP_TRY(hipHostFree(s.host)); s.host = nullptr; s.bytes = 0; }
-    size_t want = std::max<size_t>(align_up(bytes, 4096) * 2, 1 << 16);
-    HIP_TRY(hipHostMalloc(&s.host, want, hipHostMallocDefault));
-    s.bytes = want;
-  }
   *out = &s;
   return RELAYGR_OK;
 }
@@ -514,7 +536,7 @@ static int check_offsets(const int32_t* off, int n, const char* what) {
 }
 
 template <typename T>
-static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode mode, float* scores, hipStream_t st) {
+static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode mode, float* scores, const CallScratch& cs, hipStream_t st) {
   const relaygr_model_config& cfg = c->cfg;
   const int d = cfg.d_model, H = cfg.n_heads, dh = d / H, NL = cfg.n_layers, n = b->n_users;
   const bool bf16 = is_half16(cfg);   // either 16-bit type: the MFMA path
@@ -572,6 +594,12 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
     ud.sfx_tile0 = sfx_tiles * (int64_t)(2 * kTile * d);
     if (mode != kPrefill) { nrow += S + M; sfx_tiles += (S + kTile - 1) / kTile; }
     if (prow + nrow >= (1ll << 31) - 1) return fail(RELAYGR_EINVAL, "batch has 2^31 rows or more");
+  }
+  if (mode == kPrefill && b->handles) {   // two users writing one pool entry would race
+    std::vector<relaygr_kv_handle> hs;
+    for (int u = 0; u < n; ++u) if (b->handles[u] != RELAYGR_NO_CACHE) hs.push_back(b->handles[u]);
+    std::sort(hs.begin(), hs.end());
+    if (std::adjacent_find(hs.begin(), hs.end()) != hs.end()) return fail(RELAYGR_EINVAL, "prefill: two users of the batch carry the same handle");
   }
   pstart[n] = (int32_t)prow;
   p.n_prows = (int)prow; p.n_nrows = (int)nrow; p.n_rows = (int)(prow + nrow);
@@ -634,10 +662,10 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
   // -- scratch
   p.nsplit = wanted_splits(n_tiles_all, H, min_key_tiles);
   carve(cfg, p);
-  while (p.total > c->scratch_bytes && p.nsplit > 1) { p.nsplit -= 1; carve(cfg, p); }
-  if (p.total > c->scratch_bytes)
-    return fail(RELAYGR_ENOSPC, "scratch too small: call needs %zu bytes, context has %zu", p.total, c->scratch_bytes);
-  char* S0 = c->scratch;
+  while (p.total > cs.bytes && p.nsplit > 1) { p.nsplit -= 1; carve(cfg, p); }
+  if (p.total > cs.bytes)
+    return fail(RELAYGR_ENOSPC, "scratch too small: call needs %zu bytes, %zu are available", p.total, cs.bytes);
+  char* S0 = cs.base;
   float* x = (float*)(S0 + p.off_x);
   T* xh = (T*)(S0 + p.off_xh);
   T* ubuf = (T*)(S0 + p.off_u);
@@ -865,7 +893,8 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
   return RELAYGR_OK;
 }
 
-static int run(relaygr_ctx* c, relaygr_kv_pool* pool, const relaygr_batch* b, Mode mode, float* scores, void* stream) {
+static int run(relaygr_ctx* c, relaygr_kv_pool* pool, const relaygr_batch* b, Mode mode, float* scores, void* stream,
+               const CallScratch* other = nullptr) {
   if (!c || !b) return fail(RELAYGR_EINVAL, "null context or batch");
   if (b->n_users < 0) return fail(RELAYGR_EINVAL, "n_users < 0");
   if (b->n_users == 0) return RELAYGR_OK;
@@ -881,9 +910,12 @@ static int run(relaygr_ctx* c, relaygr_kv_pool* pool, const relaygr_batch* b, Mo
       return fail(RELAYGR_EINVAL, "pool and context were created for different model shapes");
   }
   hipStream_t st = (hipStream_t)stream;
-  if (c->cfg.dtype == RELAYGR_DTYPE_FP32) return run_typed<float>(c, kp, b, mode, scores, st);
-  if (c->cfg.dtype == RELAYGR_DTYPE_FP16) return run_typed<__half>(c, kp, b, mode, scores, st);
-  return run_typed<__hip_bfloat16>(c, kp, b, mode, scores, st);
+  const size_t wp = wpack_bytes(c->cfg);
+  const CallScratch own = {c->scratch + wp, c->scratch_bytes - wp};
+  const CallScratch& cs = other ? *other : own;
+  if (c->cfg.dtype == RELAYGR_DTYPE_FP32) return run_typed<float>(c, kp, b, mode, scores, cs, st);
+  if (c->cfg.dtype == RELAYGR_DTYPE_FP16) return run_typed<__half>(c, kp, b, mode, scores, cs, st);
+  return run_typed<__hip_bfloat16>(c, kp, b, mode, scores, cs, st);
 }
 
 extern "C" int relaygr_prefill_prefix(relaygr_ctx* ctx, relaygr_kv_pool* pool, const relaygr_batch* batch, void* hip_stream) {

@@ -71,9 +71,13 @@ extern "C" int relaygr_kv_pool_reload(relaygr_kv_pool* pool, uint64_t user_id, i
 
 // ---- the expander ------------------------------------------------------------------------------
 // The DRAM tier is a second pool of the same page geometry whose slab is one pinned host arena
-// allocated at creation: no allocation happens on the serving path.  Only the expander's copy
-// stream ever touches the arena, and copies on one stream run in order, so DRAM slots can be
-// recycled without waiting.  HBM extents are read by the caller's streams, so an extent becomes
+// allocated at creation: no allocation happens on the serving path.  Spills (HBM -> DRAM) and
+// reloads (DRAM -> HBM) run on two streams of the expander's own, so that the two directions of
+// the host link overlap and a reload -- which sits on a ranking request's critical path (the
+// `load` step) -- never queues behind other users' spills or behind the ranking stream a spill
+// waits for.  The arena is kept consistent with events instead of stream order: a reload waits
+// for the spills still in flight into the pages it reads, a spill waits for the reloads still in
+// flight out of the pages it overwrites.  HBM extents are read by the caller's streams, so an extent becomes
 // reclaimable only after the event that follows its spill has completed.  Reclaimable entries stay
 // in HBM (a repeat request still hits them) until an allocation needs their pages: the HBM pool is
 // then a sliding window over users, consumed entries leaving it oldest retirement first (Section
@@ -84,11 +88,14 @@ struct PendingFree {
   relaygr_kv_handle handle;
   hipEvent_t spilled;
   bool cancelled;
+  int64_t dram_page0, dram_pages;   // arena pages the spill writes (0 pages: no image)
 };
 struct Reload {
   relaygr_kv_handle handle;   // the HBM entry being filled
   hipEvent_t done;
+  int64_t dram_page0, dram_pages;   // arena pages the reload reads
 };
+inline bool overlap(int64_t a0, int64_t an, int64_t b0, int64_t bn) { return an > 0 && bn > 0 && a0 < b0 + bn && b0 < a0 + an; }
 }  // namespace
 
 struct relaygr_expander {
@@ -96,7 +103,7 @@ struct relaygr_expander {
   KvPool dram;                          // page allocator over the pinned arena
   void* arena = nullptr;
   int max_inflight = 1;
-  hipStream_t copy_stream = nullptr;
+  hipStream_t spill_stream = nullptr, reload_stream = nullptr;   // default priority, one per direction
   std::unordered_map<uint64_t, uint64_t> last_use;   // DRAM-resident user -> LRU stamp
   std::vector<PendingFree> pending_free;        // retired, spill not yet known to be complete
   std::deque<relaygr_kv_handle> reclaimable;    // retired and spilled: still in HBM, oldest first
@@ -204,12 +211,17 @@ extern "C" int relaygr_expander_create(relaygr_kv_pool* pool, size_t dram_budget
   const size_t pb = page_bytes(ex->hbm);
   const int64_t pages = (int64_t)(dram_budget_bytes / pb);
   if (pages * (int64_t)ex->hbm->page_tokens >= (1ll << 31)) { delete ex; return fail(RELAYGR_EINVAL, "expander_create: DRAM budget holds 2^31 tokens or more"); }
-  hipError_t e = hipStreamCreateWithFlags(&ex->copy_stream, hipStreamNonBlocking);   // default priority
+  hipError_t e = hipStreamCreateWithFlags(&ex->spill_stream, hipStreamNonBlocking);   // default priority
+  if (e == hipSuccess) {
+    e = hipStreamCreateWithFlags(&ex->reload_stream, hipStreamNonBlocking);
+    if (e != hipSuccess) (void)hipStreamDestroy(ex->spill_stream);
+  }
   if (e != hipSuccess) { delete ex; return fail(RELAYGR_EHIP, "expander_create: %s", hipGetErrorString(e)); }
   if (pages > 0) {
     e = hipHostMalloc(&ex->arena, (size_t)pages * pb, hipHostMallocDefault);
     if (e != hipSuccess) {
-      (void)hipStreamDestroy(ex->copy_stream);
+      (void)hipStreamDestroy(ex->spill_stream);
+      (void)hipStreamDestroy(ex->reload_stream);
       delete ex;
       return fail(RELAYGR_EHIP, "expander_create: pinning %zu bytes of host memory: %s", (size_t)pages * pb, hipGetErrorString(e));
     }
@@ -228,12 +240,14 @@ extern "C" int relaygr_expander_create(relaygr_kv_pool* pool, size_t dram_budget
 
 extern "C" void relaygr_expander_destroy(relaygr_expander* ex) {
   if (!ex) return;
-  (void)hipStreamSynchronize(ex->copy_stream);
+  (void)hipStreamSynchronize(ex->spill_stream);
+  (void)hipStreamSynchronize(ex->reload_stream);
   poll(ex);
   for (auto& pf : ex->pending_free) (void)hipEventDestroy(pf.spilled);
   for (auto& r : ex->reloads) (void)hipEventDestroy(r.done);
   for (auto e : ex->spare_events) (void)hipEventDestroy(e);
-  (void)hipStreamDestroy(ex->copy_stream);
+  (void)hipStreamDestroy(ex->spill_stream);
+  (void)hipStreamDestroy(ex->reload_stream);
   if (ex->arena) (void)hipHostFree(ex->arena);
   delete ex;
 }
@@ -257,20 +271,26 @@ extern "C" int relaygr_expander_retire(relaygr_expander* ex, relaygr_kv_handle h
     return fail(RELAYGR_EHIP, "expander_retire: cannot create events");
   }
   HIP_TRY(hipEventRecord(consumed, (hipStream_t)stream));
-  HIP_TRY(hipStreamWaitEvent(ex->copy_stream, consumed, 0));
+  HIP_TRY(hipStreamWaitEvent(ex->spill_stream, consumed, 0));
   ex->spare_events.push_back(consumed);   // the wait is enqueued; the event may be recorded again later
   int rc = RELAYGR_OK;
   PoolEntry slot;
+  int64_t dp0 = 0, dpn = 0;
   if (dram_slot(ex, e.user_id, e.prefix_len, &slot)) {
-    HIP_TRY(hipMemcpyAsync(extent_ptr(&ex->dram, slot), extent_ptr(ex->hbm, e), bytes, hipMemcpyDeviceToHost, ex->copy_stream));
+    dp0 = slot.page0; dpn = slot.npages;
+    // the slot may be recycled pages that a reload still reads (the image that lived there was displaced after
+    // its reload was queued): the spill overwrites them only after that reload
+    for (auto& r : ex->reloads)
+      if (overlap(dp0, dpn, r.dram_page0, r.dram_pages)) HIP_TRY(hipStreamWaitEvent(ex->spill_stream, r.done, 0));
+    HIP_TRY(hipMemcpyAsync(extent_ptr(&ex->dram, slot), extent_ptr(ex->hbm, e), bytes, hipMemcpyDeviceToHost, ex->spill_stream));
     ex->last_use[e.user_id] = ++ex->clock;
     ex->stats[4] += 1;
   } else {
     // no DRAM for it: the entry still becomes reclaimable once the stream has consumed it
     rc = fail(RELAYGR_ENOSPC, "expander_retire: no DRAM for %zu bytes; the entry has no image", bytes);
   }
-  HIP_TRY(hipEventRecord(spilled, ex->copy_stream));
-  ex->pending_free.push_back({h, spilled, false});
+  HIP_TRY(hipEventRecord(spilled, ex->spill_stream));
+  ex->pending_free.push_back({h, spilled, false, dp0, dpn});
   return rc;
 }
 
@@ -284,7 +304,7 @@ extern "C" int relaygr_expander_lookup(relaygr_expander* ex, uint64_t user_id, v
     for (auto& pf : ex->pending_free)
       if (pf.handle == h) pf.cancelled = true;              // keep it live; its DRAM copy still completes
     forget_reclaimable(ex, h);                              // live again until it is retired again
-    // a reload of this very entry may still be in flight on the copy stream: order the caller behind
+    // a reload of this very entry may still be in flight on the reload stream: order the caller behind
     // it, and behind nothing else (a hit does not wait for other users' spills and reloads)
     for (auto& r : ex->reloads)
       if (r.handle == h) HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, r.done, 0));
@@ -319,13 +339,18 @@ extern "C" int relaygr_expander_lookup(relaygr_expander* ex, uint64_t user_id, v
   ex->hbm->resolve(h, &e);
   hipEvent_t done = get_event(ex);
   if (!done) { ex->hbm->release(h); return fail(RELAYGR_EHIP, "expander_lookup: cannot create an event"); }
-  // copies on the copy stream run in order, so a spill into this slot that is still running finishes first
-  hipError_t he = hipMemcpyAsync(extent_ptr(ex->hbm, e), extent_ptr(&ex->dram, slot), (size_t)slot.npages * page_bytes(ex->hbm),
-                                 hipMemcpyHostToDevice, ex->copy_stream);
+  // a spill into these arena pages that is still in flight (this image's own, most likely) finishes first;
+  // spills of other pages, and whatever ranking streams they wait for, do not hold the reload up
+  hipError_t he = hipSuccess;
+  for (auto& pf : ex->pending_free)
+    if (he == hipSuccess && overlap(slot.page0, slot.npages, pf.dram_page0, pf.dram_pages)) he = hipStreamWaitEvent(ex->reload_stream, pf.spilled, 0);
+  if (he == hipSuccess)
+    he = hipMemcpyAsync(extent_ptr(ex->hbm, e), extent_ptr(&ex->dram, slot), (size_t)slot.npages * page_bytes(ex->hbm),
+                        hipMemcpyHostToDevice, ex->reload_stream);
   if (he != hipSuccess) { ex->hbm->release(h); ex->spare_events.push_back(done); return fail(RELAYGR_EHIP, "expander_lookup: %s", hipGetErrorString(he)); }
-  HIP_TRY(hipEventRecord(done, ex->copy_stream));
+  HIP_TRY(hipEventRecord(done, ex->reload_stream));
   HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, done, 0));
-  ex->reloads.push_back({h, done});
+  ex->reloads.push_back({h, done, slot.page0, slot.npages});
   if (ex->rate_bps > 0.0) ex->tokens -= image_bytes;
   ex->last_use[user_id] = ++ex->clock;
   ex->stats[1] += 1;

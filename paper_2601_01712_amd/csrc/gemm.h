@@ -20,7 +20,7 @@ typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
 
 // The two 16-bit storage types of the MFMA path (bf16: the benchmark's; fp16: the half precision the
-// paper mentions as lowering the rank stage, Section 5.2).  Kernels are written against this
+// paper mentions as lowering the rank stage, Section 4.2).  Kernels are written against this
 // interface: bit patterns in, fp32 out; pack2 rounds to nearest even; mfma is the 32x32x16 product
 // of two 8-element fragments.
 struct Bf16 {

@@ -11,9 +11,9 @@ round-to-nearest-even, or fp32) and returned as float32 arrays holding exactly
 representable values, so the CPU oracle and the GPU path consume identical
 numbers.  Nothing in this module evaluates any part of the model.
 
-Workload shapes follow the paper's evaluation ranges (Section 5.1, "Models and
+Workload shapes follow the paper's evaluation ranges (Section 4.1, "Models and
 workloads": lengths from 1K to tens of thousands of tokens, widths 128-1024,
-several to tens of layers; Section 5.4: about 512 candidates per query, up to
+several to tens of layers; Section 4.4: about 512 candidates per query, up to
 2048) and the five benchmark configurations this repository is measured on.
 """
 from __future__ import annotations
@@ -158,15 +158,15 @@ WORKLOADS: Dict[str, Workload] = {
                    prefix_len=8192, n_cands=1000, n_suffix=0),
     "C5": Workload("C5", ModelConfig(8, 512, 8, "bf16"), seed=5, n_users=64,
                    prefix_len=None, n_cands=None, n_suffix=None, miss_tenths=3),
-    # the paper's extensibility axes (Section 5.4): embedding width up to 1024, depth 8 -> 16 layers
+    # the paper's extensibility axes (Section 4.4): embedding width up to 1024, depth 8 -> 16 layers
     "X1": Workload("X1", ModelConfig(8, 1024, 8, "bf16"), seed=6, n_users=16,
                    prefix_len=4096, n_cands=512, n_suffix=0),
     "X2": Workload("X2", ModelConfig(16, 512, 8, "bf16"), seed=7, n_users=16,
                    prefix_len=4096, n_cands=512, n_suffix=0),
-    # the half precision the paper mentions as lowering the rank stage (Section 5.2): C3 in IEEE fp16
+    # the half precision the paper mentions as lowering the rank stage (Section 4.2): C3 in IEEE fp16
     "X3": Workload("X3", ModelConfig(8, 512, 8, "fp16"), seed=8, n_users=16,
                    prefix_len=4096, n_cands=512, n_suffix=0),
-    # the backbone variant that differs only in its attention computation (Section 5.4): C3 with
+    # the backbone variant that differs only in its attention computation (Section 4.4): C3 with
     # softmax attention over the visible keys
     "X4": Workload("X4", ModelConfig(8, 512, 8, "bf16", attention="softmax"), seed=9, n_users=16,
                    prefix_len=4096, n_cands=512, n_suffix=0),

@@ -199,6 +199,6 @@ def test_header_is_valid_c99_and_links_against_the_library(tmp_path):
     subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
                     str(src), "-o", str(exe), "-L", lib_dir, "-lrelaygr", f"-Wl,-rpath,{lib_dir}"], check=True)
     out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
-    assert int(out[0]) == 32 * 1024 * 1024          # the paper's example: 2K tokens, 8 layers, d 256, fp32 (Section 5.1)
+    assert int(out[0]) == 32 * 1024 * 1024          # the paper's example: 2K tokens, 8 layers, d 256, fp32 (Section 4.1)
     assert int(out[1]) == rg.RELAYGR_EINVAL
     assert int(out[2]) == len(names) == len(rg.EXPORTS)

@@ -61,22 +61,22 @@ def test_c4_full_size_sampled_user_and_kv_footprint():
 
 
 def test_x1_width_1024():
-    """Section 5.4's width axis: d = 1024 (d_head = 128)."""
+    """Section 4.4's width axis: d = 1024 (d_head = 128)."""
     run_full("X1", sample_users=[3])
 
 
 def test_x2_depth_16_layers():
-    """Section 5.4's depth axis: 16 layers."""
+    """Section 4.4's depth axis: 16 layers."""
     run_full("X2", sample_users=[7])
 
 
 def test_x3_fp16():
-    """The half precision the paper mentions (Section 5.2): C3's shape in IEEE fp16."""
+    """The half precision the paper mentions (Section 4.2): C3's shape in IEEE fp16."""
     run_full("X3", sample_users=[9])
 
 
 def test_x4_softmax_attention():
-    """The backbone variant that differs only in its attention computation (Section 5.4), read as a
+    """The backbone variant that differs only in its attention computation (Section 4.4), read as a
     softmax over the visible keys: C3's shape."""
     run_full("X4", sample_users=[4])
 

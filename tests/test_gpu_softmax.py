@@ -1,5 +1,5 @@
 """GPU parity for the second attention form (softmax over the visible keys; the backbone variant
-of the paper's Section 5.4, whose formula the paper does not give): the HIP path, called through the
+of the paper's Section 4.4, whose formula the paper does not give): the HIP path, called through the
 C ABI with relaygr_ctx_set_attention(RELAYGR_ATTN_SOFTMAX), against the CPU oracle on the same seeded
 inputs, to the same tolerances as the first form (1e-4 fp32, 2e-2 bf16, 2.5e-3 fp16 of
 max(1, max|oracle|)).  Cases span several key tiles, row tiles and key splits, ragged tails, suffixes,

@@ -3,7 +3,7 @@
 The paper prints no model outputs, so the oracle is pinned to what the paper
 and the mathematics fix: the relay-race identity (Section 2.3), the
 candidate-independence of psi (Section 3.1), the printed KV-cache size
-(Section 5.1 / table "KV caches"), a scalar brute-force evaluator on tiny
+(Section 4.1 / table "KV caches"), a scalar brute-force evaluator on tiny
 inputs, closed forms for degenerate weights and degenerate sequences, and
 library routines for LayerNorm and SiLU.  The last group plants plausible
 mistakes in a copy of the oracle and checks that a pin catches each.

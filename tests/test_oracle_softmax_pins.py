@@ -1,6 +1,6 @@
 """Pins for the oracle's second attention form (CPU only).
 
-Section 5.4 of the paper evaluates a backbone variant that differs from the
+Section 4.4 of the paper evaluates a backbone variant that differs from the
 first only in its attention computation and prints neither a formula nor an
 output for it, so the reading (a softmax over the visible keys in place of
 SiLU(.)/n) is pinned to what the mathematics fixes: a library attention
