@@ -218,6 +218,25 @@ int  relaygr_prefill_prefix(relaygr_ctx* ctx, relaygr_kv_pool* pool, const relay
 int  relaygr_rank_with_cache(relaygr_ctx* ctx, relaygr_kv_pool* pool, const relaygr_batch* batch,
                              float* scores_dev, void* hip_stream);
 
+/* relaygr_rank_with_cache for callers that cannot allocate device memory or bring a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * same scores as relaygr_rank_with_cache, but the call's working buffers (residual stream, projections,
+ * attention partial sums, row tables, batch descriptors) are laid out in a buffer that lives inside the
+ * library -- RELAYGR_STATIC_SCRATCH_BYTES of device memory per GPU, held from the moment the library is
+ * loaded until the process ends -- instead of in the context's scratch buffer (of which only the re-packed
+ * weights at its head are read).  The call allocates and frees nothing, on the device or pinned on the host.
+ * A call whose buffers do not fit (about 2000 suffix + candidate rows at d_model 512 with eight key-range
+ * splits; fewer splits are tried first) is RELAYGR_ENOSPC and nothing is enqueued.  Every call on a GPU,
+ * from any context, shares that GPU's buffer, which keeps the previous call's contents: calls that may
+ * overlap on one GPU (two streams, two threads) race -- serialise them, or give the other stream
+ * relaygr_rank_with_cache.  Nothing in the buffer needs clearing between calls: every kernel writes what a
+ * later one reads. */
+#define RELAYGR_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+int  relaygr_rank_with_cache_static(relaygr_ctx* ctx, relaygr_kv_pool* pool, const relaygr_batch* batch,
+                                    float* scores_dev, void* hip_stream);
+/* RELAYGR_STATIC_SCRATCH_BYTES as the loaded library was built. */
+size_t relaygr_static_scratch_bytes(void);
+
 /* Baseline: full inference inline for every user (Section 4.1 "Baselines"); handles are ignored
  * and no pool is touched.  Same output as relaygr_rank_with_cache. */
 int  relaygr_rank_full_recompute(relaygr_ctx* ctx, const relaygr_batch* batch,

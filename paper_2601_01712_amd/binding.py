@@ -28,6 +28,7 @@ EXPORTS = [
     "relaygr_kv_pool_create", "relaygr_kv_pool_destroy", "relaygr_kv_pool_alloc", "relaygr_kv_pool_free",
     "relaygr_kv_pool_lookup", "relaygr_kv_pool_entry_len", "relaygr_kv_pool_stats", "relaygr_kv_pool_locate",
     "relaygr_prefill_prefix", "relaygr_rank_with_cache", "relaygr_rank_full_recompute",
+    "relaygr_rank_with_cache_static", "relaygr_static_scratch_bytes",
     "relaygr_ctx_profile_enable", "relaygr_ctx_profile_sample", "relaygr_ctx_profile_read",
     "relaygr_kv_pool_entry_bytes", "relaygr_kv_pool_spill", "relaygr_kv_pool_reload",
     "relaygr_expander_create", "relaygr_expander_destroy", "relaygr_expander_retire",
@@ -114,6 +115,8 @@ def load_library() -> C.CDLL:
         "relaygr_prefill_prefix": (C.c_int, [vp, vp, P(BatchC), vp]),
         "relaygr_rank_with_cache": (C.c_int, [vp, vp, P(BatchC), vp, vp]),
         "relaygr_rank_full_recompute": (C.c_int, [vp, P(BatchC), vp, vp]),
+        "relaygr_rank_with_cache_static": (C.c_int, [vp, vp, P(BatchC), vp, vp]),
+        "relaygr_static_scratch_bytes": (sz, []),
         "relaygr_ctx_profile_enable": (C.c_int, [vp, C.c_uint32]),
         "relaygr_ctx_profile_sample": (C.c_int, [vp, i32]),
         "relaygr_ctx_set_attention": (C.c_int, [vp, i32]),
@@ -507,6 +510,18 @@ def relaygr_rank_with_cache(ctx: Context, pool: Optional[KvPool], batch: Batch, 
     _check(load_library().relaygr_rank_with_cache(ctx.handle, pool.handle if pool is not None else None, C.byref(bc),
                                                   scores.data_ptr(), _stream_ptr(stream)))
     return scores
+
+
+def relaygr_rank_with_cache_static(ctx: Context, pool: Optional[KvPool], batch: Batch, scores: torch.Tensor, stream=None) -> torch.Tensor:
+    """relaygr_rank_with_cache on the library's own scratch; `scores` must be given (nothing is allocated)."""
+    bc = batch.c_struct()
+    _check(load_library().relaygr_rank_with_cache_static(ctx.handle, pool.handle if pool is not None else None, C.byref(bc),
+                                                         scores.data_ptr(), _stream_ptr(stream)))
+    return scores
+
+
+def relaygr_static_scratch_bytes() -> int:
+    return load_library().relaygr_static_scratch_bytes()
 
 
 def relaygr_rank_full_recompute(ctx: Context, batch: Batch, scores: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:

@@ -8,7 +8,9 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
+#include <string>
 #include <type_traits>
 #include <vector>
 
@@ -165,6 +167,34 @@ extern "C" size_t relaygr_scratch_bytes(const relaygr_model_config* cfg, int32_t
   return base + align_up(small_rows * 7 * ((size_t)cfg->d_model * 4 + (size_t)cfg->n_heads * 8));
 }
 
+// ---- scratch that lives in the library (for callers that cannot allocate) ----------------------
+// relaygr_rank_with_cache_static lays its call out here instead of in the context's buffer.  Each GPU holds
+// its own copy of the array at its own address; in host code the array's name is only a stand-in, so the
+// device address is looked up once per device (hipGetSymbolAddress, with that device current) and that
+// pointer is what kernels, copies and fills are given.
+constexpr size_t kStaticScratchBytes = RELAYGR_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_static_mu;
+static char* g_static_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device, looked up on that device's first use.
+static int static_scratch(char** out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(RELAYGR_EINVAL, "static scratch: device index %d out of range", dev);
+  std::lock_guard<std::mutex> lk(g_static_mu);
+  if (!g_static_ptr[dev]) {
+    void* ptr = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return fail(RELAYGR_EHIP, "static scratch: hipGetSymbolAddress returned a null address");
+    g_static_ptr[dev] = (char*)ptr;
+  }
+  *out = g_static_ptr[dev];
+  return RELAYGR_OK;
+}
+
 // ---- context ----------------------------------------------------------------------------------
 constexpr int kStagingSlots = 4;
 struct StagingSlot {
@@ -258,6 +288,11 @@ extern "C" int relaygr_ctx_create(const relaygr_model_config* cfg, const relaygr
       }
       sl.bytes = want;
     }
+  }
+  {   // set-up for relaygr_rank_with_cache_static: this device's address of the library's own scratch
+    char* unused = nullptr;
+    int rc = static_scratch(&unused);
+    if (rc != RELAYGR_OK) { relaygr_ctx_destroy(c); return rc; }
   }
   *out = c;
   return RELAYGR_OK;
@@ -928,6 +963,21 @@ extern "C" int relaygr_rank_with_cache(relaygr_ctx* ctx, relaygr_kv_pool* pool, 
                                        void* hip_stream) {
   return run(ctx, pool, batch, kRankCached, scores_dev, hip_stream);
 }
+
+extern "C" int relaygr_rank_with_cache_static(relaygr_ctx* ctx, relaygr_kv_pool* pool, const relaygr_batch* batch, float* scores_dev,
+                                              void* hip_stream) {
+  char* base = nullptr;
+  int rc = static_scratch(&base);      // a table lookup after the first call on this device
+  if (rc != RELAYGR_OK) return rc;
+  const CallScratch cs = {base, kStaticScratchBytes};
+  rc = run(ctx, pool, batch, kRankCached, scores_dev, hip_stream, &cs);
+  if (rc == RELAYGR_ENOSPC)
+    return fail(rc, "rank_with_cache_static: the call does not fit the library's %zu-byte scratch (%s); use relaygr_rank_with_cache",
+                kStaticScratchBytes, std::string(relaygr_last_error()).c_str());
+  return rc;
+}
+
+extern "C" size_t relaygr_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 extern "C" int relaygr_rank_full_recompute(relaygr_ctx* ctx, const relaygr_batch* batch, float* scores_dev, void* hip_stream) {
   return run(ctx, nullptr, batch, kRankFull, scores_dev, hip_stream);
