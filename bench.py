@@ -457,15 +457,6 @@ def main() -> int:
             "hbm_frac_of_8TBps": round(kv_bytes / (avg_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4),
         }
 
-    # ---- what the chip sustains on this MFMA in a pure MFMA loop (its power limit lowers the clock as operand bits
-    # toggle): context for the fraction of the published peak above
-    if roof is not None and half16:
-        torch.cuda.synchronize()
-        pc, pr = rg.relaygr_probe_mfma(False), rg.relaygr_probe_mfma(True)
-        roof["mfma_loop_sustained"] = {"constant_operands_TFLOPs": round(pc["tflops"], 1), "constant_operands_GHz": round(pc["shader_ghz"], 3),
-                                       "random_operands_TFLOPs": round(pr["tflops"], 1), "random_operands_GHz": round(pr["shader_ghz"], 3)}
-        roof["frac_of_sustained_random"] = round(roof["achieved"] / pr["tflops"], 4)
-
     # ---- CPU oracle on a bounded sample: whole users of this workload (median length first), full recompute,
     # until about ten seconds of CPU work are done
     cpu = None

@@ -223,6 +223,7 @@ struct relaygr_ctx {
   char* scratch;                        // the caller's buffer: [packed weights | call scratch]
   size_t scratch_bytes;
   std::vector<const uint16_t*> w1_packed, w2_packed;   // bf16: panels at the start of scratch
+  int n_cus = 256;                      // compute units of the device the context was created on
   StagingSlot staging[kStagingSlots];   // pinned, allocated once at creation
   int next_slot = 0;
 };
@@ -249,6 +250,11 @@ extern "C" int relaygr_ctx_create(const relaygr_model_config* cfg, const relaygr
   c->ln_out_g = w->ln_out_g; c->ln_out_b = w->ln_out_b; c->w_score = w->w_score; c->b_score = w->b_score;
   c->scratch = (char*)scratch_dev;
   c->scratch_bytes = scratch_bytes;
+  {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+      c->n_cus = cus;
+  }
   if (scratch_bytes < wpack_bytes(*cfg)) { delete c; return fail(RELAYGR_ENOSPC, "ctx_create: scratch smaller than the packed weights"); }
   if (is_half16(*cfg)) {
     // re-pack W1 and W2 of every layer into MFMA panels, once
@@ -810,6 +816,19 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
         fp.users = d_users; fp.rt = rt; fp.d = d; fp.dh = dh; fp.n_prows = p.n_prows; fp.layer = l;
         fp.row_begin = r0; fp.row_end = r1; fp.n_mtiles = (r1 - r0 + 64 * kF1TM - 1) / (64 * kF1TM);
         fp.cm = cm; fp.q_mul = q_mul;
+        // launches of a few thousand rows take the weight-stationary kernel: one persistent workgroup per compute unit,
+        // (compute units / column slices) row groups, a multiple of 8 so that each XCD takes whole row groups
+        const int n_slices = cm.nblk * (d / 128);
+        const int n_rg = d <= 512 ? (c->n_cus / n_slices) & ~7 : 0;
+        if (r1 - r0 >= kF1WsMinRows && (r0 & 63) == 0 && n_rg >= 8) {
+          const dim3 grid(n_slices * n_rg);
+          switch (d) {
+            case 128: hipLaunchKernelGGL((f1_ws_bf16_kernel<HT, 128>), grid, dim3(512), 0, st, fp); break;
+            case 256: hipLaunchKernelGGL((f1_ws_bf16_kernel<HT, 256>), grid, dim3(512), 0, st, fp); break;
+            default: hipLaunchKernelGGL((f1_ws_bf16_kernel<HT, 512>), grid, dim3(512), 0, st, fp); break;
+          }
+          return;
+        }
         int total = fp.n_mtiles * cm.nblk * (d / (64 * kF1TN));
         hipLaunchKernelGGL(f1_gemm_bf16_kernel<HT>, dim3((total + 7) / 8 * 8), dim3(256), 0, st, fp);
       }

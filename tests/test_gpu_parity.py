@@ -93,6 +93,19 @@ def test_bf16_head_sizes(d, H):
     run_three_routes(synth.ModelConfig(2, d, H, "bf16"), 70 + H, [300, 129], [5, 0], [140, 66])
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+@pytest.mark.parametrize("d,H,boost", [(128, 2, BOOST), (256, 4, BOOST), (512, 8, None)])
+def test_launches_of_thousands_of_rows_take_the_weight_stationary_projection(dtype, d, H, boost):
+    """Row counts above 4096 per projection launch (the persistent, weight-stationary form of the u|v|q|k
+    GEMM) with everything its epilogue has to place: prefix rows of three users with ragged last tiles and
+    filler rows between them, K and V tiles of the pool (cached users) and of scratch (the uncached user),
+    suffix rows scattered into suffix tiles, candidate rows, a last unit that ends inside a 64-row block;
+    ranking on the cache runs the same launch over new rows only, full recompute over prefix and new rows
+    in one row space.  Boosted weights at the small widths, so that a misplaced K/V element shows."""
+    run_three_routes(synth.ModelConfig(2, d, H, dtype), 530 + d, [2500, 1300, 700], [70, 5, 0], [2100, 1900, 301],
+                     page_tokens=128, miss=(1,), boost=boost)
+
+
 # ------------------------------------------------------------------------------------ fp16
 @pytest.mark.parametrize("L,S,M", [
     ([1], [0], [1]), ([65, 300], [0, 70], [3, 129]), ([513, 0, 128], [64, 2, 0], [257, 9, 1]), ([1000], [17], [400]),
