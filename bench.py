@@ -6,14 +6,18 @@ and candidate tokens through all layers against the prefix K/V already resident 
 then the score head): the `rank` stage the paper's headline metric is quoted on.  The stages that
 produce or replace that cache are timed beside it in the same run -- relaygr_prefill_prefix (the
 `pre` stage) and relaygr_rank_full_recompute (the baseline of full inline inference) -- and
-reported in the same JSON line, together with the attention kernel's roofline figures and the CPU
-oracle timed on a bounded sample.
+reported in the same JSON line, together with the roofline figures of the three kernels of a layer
+(attention: the dominant one; the u|v|q|k projection GEMM; the layer tail), compact records of the
+long-sequence workload (C4) and the jagged mixed hit/miss workload (C5), and the CPU oracle timed on
+a bounded sample.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C3]
 """
 from __future__ import annotations
 
 import argparse
+import ctypes
+import gc
 import json
 import os
 import sys
@@ -25,12 +29,14 @@ if ROOT not in sys.path:
 
 import numpy as np  # noqa: E402
 
-PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA
+PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 / fp16 MFMA
 PEAK_FP32_TFLOPS = 157.3     # fp32 vector
 PEAK_HBM_GBPS = 8000.0
+LATENCY_CALLS = 500          # rank calls behind every p50 / p99 (whatever --steps says)
 
 # HBM bytes per attention launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs), scaled by
-# what the same counters read for a plain 1 GiB copy (x2.0 and x1.0); profiles/bench_C3_kernels.md.
+# what the same counters read for a plain 1 GiB copy (x2.0 and x1.0); profiles/bench_C3_kernels.md.  Only the
+# C3 rank launch has been counted; other workloads report null.
 MEASURED_ATTN_TRAFFIC_BYTES = {"C3": (73939 * 2 + 32770) * 1024}
 
 WORKLOAD_TEXT = {
@@ -52,6 +58,338 @@ def percentile(xs, q):
         return None
     k = min(len(xs) - 1, max(0, int(np.ceil(q / 100.0 * len(xs))) - 1))
     return xs[k]
+
+
+def lat_summary(lat):
+    return {"p50": round(percentile(lat, 50), 4), "p99": round(percentile(lat, 99), 4), "mean": round(float(np.mean(lat)), 4),
+            "calls": len(lat)}
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+# ------------------------------------------------------------------------------------------------
+# one workload: inputs, pool, pre-inference, timed ranking, full recompute, kernel timings
+# ------------------------------------------------------------------------------------------------
+class Loaded:
+    """A workload resident on the GPU: context, pool with the cached users' prefixes pre-inferred, device batches."""
+
+    def __init__(self, torch, rg, synth, name, batches=1, prefill_steps=10, profile_all=False):
+        from synth.generator import user_slices
+        self.torch, self.rg, self.synth, self.name = torch, rg, synth, name
+        self.user_slices = user_slices
+        wl = synth.WORKLOADS[name]
+        self.wl, self.cfg = wl, wl.model
+        cfg = self.cfg
+        t0 = time.time()
+        self.weights = synth.make_weights(cfg, wl.seed)
+        shapes = [synth.make_lengths(wl, bi) for bi in range(batches)]
+        self.host = [synth.make_batch(wl, bi) for bi in range(batches)]
+        self.L, self.S, self.M, self.cached = shapes[0]
+        n = wl.n_users
+        self.n = n
+        log(f"{name}: {batches} batch(es) generated in {time.time() - t0:.1f}s (batch 0: users {n}, prefix tokens {int(self.L.sum())}, "
+            f"suffix {int(self.S.sum())}, candidates {int(self.M.sum())})")
+        max_L = max(int(s[0].sum()) for s in shapes)
+        max_new = max(int(s[1].sum() + s[2].sum()) for s in shapes)
+        self.ctx = rg.Context(cfg, self.weights, n, max_L, max_new)
+        self.page_tokens = 256
+        self.pool_bytes = sum(rg.relaygr_kv_pool_bytes_for(self.ctx.cfg, int(l), self.page_tokens) for s in shapes for l in s[0])
+        self.pool = rg.KvPool(self.ctx.cfg, cfg.dtype, self.pool_bytes, self.page_tokens)
+        ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
+        self.ev = ev
+        # ---- pre-inference for the users each batch marks as cached; batch 0's is timed
+        self.cycle, self.handles, self.shapes = [], [], shapes
+        self.prefill_ms, self.prefill_kernels = [], None
+        for bi, (hb, (L, S, M, cached)) in enumerate(zip(self.host, shapes)):
+            hit = [u for u in range(n) if cached[u] and L[u] > 0]
+            h = np.zeros(n, dtype=np.uint64)
+            for u in hit:
+                h[u] = rg.relaygr_kv_pool_alloc(self.pool, int(hb["user_ids"][u]), int(L[u]))
+            pre = self.sub_batch(hit, hb, h)
+            if bi == 0:
+                self.hit, self.pre = hit, pre
+                for i in range(1 + prefill_steps):
+                    a, b = ev(), ev()
+                    a.record()
+                    rg.relaygr_prefill_prefix(self.ctx, self.pool, pre)
+                    b.record()
+                    torch.cuda.synchronize()
+                    if i > 0:
+                        self.prefill_ms.append(a.elapsed_time(b))
+                if profile_all and hit:
+                    rg.relaygr_ctx_profile_enable(self.ctx, rg.binding.KERNEL_CLASSES)
+                    rg.relaygr_prefill_prefix(self.ctx, self.pool, pre)
+                    self.prefill_kernels = {c: round(rg.relaygr_ctx_profile_read(self.ctx, c)[0], 4) for c in rg.binding.KERNEL_CLASSES}
+                    rg.relaygr_ctx_profile_enable(self.ctx, [])
+            else:
+                rg.relaygr_prefill_prefix(self.ctx, self.pool, pre)
+                torch.cuda.synchronize()
+            self.handles.append(h)
+            self.cycle.append((rg.Batch(hb, cfg.dtype, handles=h), int(M.sum())))
+        self.db = self.cycle[0][0]
+        self.sumM = int(self.M.sum())
+        self.scores = torch.empty(max(m for _, m in self.cycle), dtype=torch.float32, device="cuda:0")
+
+    def sub_batch(self, users, hb, handles):
+        """Prefix-only batch of the listed users (what relaygr_prefill_prefix takes)."""
+        d = self.cfg.d_model
+        segs = [self.user_slices(hb, u) for u in users]
+        nb = {"n_users": len(users), "user_ids": np.asarray([hb["user_ids"][u] for u in users], dtype=np.uint64),
+              "prefix_emb": np.concatenate([s[0] for s in segs]) if segs else np.zeros((0, d), np.float32),
+              "prefix_off": np.concatenate([[0], np.cumsum([len(s[0]) for s in segs])]).astype(np.int32),
+              "suffix_emb": np.zeros((0, d), np.float32), "suffix_off": np.zeros(len(users) + 1, np.int32),
+              "cand_emb": np.zeros((0, d), np.float32), "cand_off": np.zeros(len(users) + 1, np.int32)}
+        return self.rg.Batch(nb, self.cfg.dtype, handles=[handles[u] for u in users])
+
+    def rank(self, i=0, stream=None):
+        self.rg.relaygr_rank_with_cache(self.ctx, self.pool, self.cycle[i % len(self.cycle)][0], self.scores, stream=stream)
+
+    def latency_sample(self, calls=LATENCY_CALLS):
+        """Per-call latency of `calls` rank calls (cycling through the batches), each bracketed by HIP events."""
+        evs = [(self.ev(), self.ev()) for _ in range(calls)]
+        self.torch.cuda.synchronize()
+        for i, (a, b) in enumerate(evs):
+            a.record()
+            self.rank(i)
+            b.record()
+        self.torch.cuda.synchronize()
+        return [a.elapsed_time(b) for a, b in evs]
+
+    def full_recompute(self, calls, profile_all=False):
+        rg, torch = self.rg, self.torch
+        ms = []
+        for i in range(1 + calls if calls > 0 else 0):
+            a, b = self.ev(), self.ev()
+            a.record()
+            rg.relaygr_rank_full_recompute(self.ctx, self.db, self.scores)
+            b.record()
+            torch.cuda.synchronize()
+            if i > 0:
+                ms.append(a.elapsed_time(b))
+        kernels = None
+        if profile_all and ms:
+            rg.relaygr_ctx_profile_enable(self.ctx, rg.binding.KERNEL_CLASSES)
+            rg.relaygr_rank_full_recompute(self.ctx, self.db, self.scores)
+            kernels = {c: round(rg.relaygr_ctx_profile_read(self.ctx, c)[0], 4) for c in rg.binding.KERNEL_CLASSES}
+            rg.relaygr_ctx_profile_enable(self.ctx, [])
+        return ms, kernels, self.scores[:self.sumM].cpu().numpy().copy()
+
+    # ---- algorithmic work of one rank call on batch bi, per layer (what the rooflines divide by)
+    def layer_work(self, bi):
+        cfg, n = self.cfg, self.n
+        L, S, M, _ = self.shapes[bi]
+        handles = self.handles[bi]
+        d, e, NL = cfg.d_model, cfg.elem_bytes, cfg.n_layers
+        key_visits = sum(int(M[u]) * int(L[u] + S[u]) + sum(int(L[u]) + t + 1 for t in range(int(S[u]))) for u in range(n))
+        causal_visits = sum(int(L[u]) * (int(L[u]) + 1) // 2 for u in range(n) if not handles[u])
+        new_rows = int(S.sum() + M.sum())
+        miss_rows = sum(int(L[u]) for u in range(n) if not handles[u])
+        attn_flops = [4.0 * d * (key_visits + causal_visits)] * (NL - 1) + [4.0 * d * key_visits]
+        # K,V of every key sequence once; q in (bf16) and the fp32 output sums of the rows attended
+        attn_bytes = [2.0 * (int(L.sum()) + int(S.sum())) * d * e + (new_rows + miss_rows) * d * (e + 4)] * (NL - 1) + \
+                     [2.0 * (int(L.sum()) + int(S.sum())) * d * e + new_rows * d * (e + 4)]
+        # projection: 8 d^2 FLOP per row (k, v only for last-layer prefix rows: 4 d^2)
+        f1_flops = [8.0 * d * d * (new_rows + miss_rows)] * (NL - 1) + [8.0 * d * d * new_rows + 4.0 * d * d * miss_rows]
+        # layer tail: 2 d^2 FLOP per row; o in (fp32), u in, residual row in and out (fp32), next layer's normalised row out
+        tail_rows = [new_rows + miss_rows] * (NL - 1) + [new_rows]
+        tail_flops = [2.0 * d * d * r for r in tail_rows]
+        tail_bytes = [r * d * (4 + e + 8 + e) for r in tail_rows]
+        return {"attn": (attn_flops, attn_bytes), "f1": (f1_flops, None), "f2": (tail_flops, tail_bytes)}
+
+    def close(self):
+        self.ctx.close()
+        self.pool.close()
+
+
+def kernel_rooflines(w: Loaded, kernel_ms, sampled_calls, half16, config_name):
+    """Roofline records of the three kernels of a layer from the library's live HIP-event timings: average algorithmic
+    work per launch over the launches that were timed / average launch duration."""
+    per_batch = [w.layer_work(bi) for bi in range(len(w.cycle))]
+
+    def mean_over(cls, which):
+        vals = [v for i in sampled_calls for v in (per_batch[i % len(per_batch)][cls][which] or [])]
+        return float(np.mean(vals)) if vals else None
+
+    peak = PEAK_BF16_TFLOPS if half16 else PEAK_FP32_TFLOPS
+    out = {}
+    attn_ms, attn_n = kernel_ms.get("attn", (0.0, 0))
+    if attn_n:
+        avg_ms = attn_ms / attn_n
+        flops, nbytes = mean_over("attn", 0), mean_over("attn", 1)
+        achieved = flops / (avg_ms * 1e-3) / 1e12
+        hbm_frac = nbytes / (avg_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS
+        out = {"kernel": "attn_bf16_kernel" if half16 else "attn_f32_kernel", "bound": "mfma" if half16 else "alu",
+               "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+               "traffic": MEASURED_ATTN_TRAFFIC_BYTES.get(config_name),
+               "traffic_note": "rocprofv3 FETCH_SIZE x2.0 + WRITE_SIZE x1.0 of one rank launch (profiles/bench_C3_kernels.md)"
+               if config_name in MEASURED_ATTN_TRAFFIC_BYTES else "not counted for this workload",
+               "avg_launch_ms": round(avg_ms, 4), "launches": attn_n, "flop_per_launch": flops,
+               "algorithmic_bytes_per_launch": nbytes, "algorithmic_GBps": round(nbytes / (avg_ms * 1e-3) / 1e9, 1),
+               "hbm_frac_of_8TBps": round(hbm_frac, 4),
+               "binding": "vector ALU + matrix cores (every score element costs an exp2 and a reciprocal); HBM binds only below "
+                          "about 100 candidates per user, see attention_small_m_sweep"}
+    f1_ms, f1_n = kernel_ms.get("f1", (0.0, 0))
+    if f1_n and half16:
+        avg_ms = f1_ms / f1_n
+        flops = mean_over("f1", 0)
+        achieved = flops / (avg_ms * 1e-3) / 1e12
+        out["f1"] = {"kernel": "f1_ws_bf16_kernel (f1_gemm_bf16_kernel below 4096 rows)", "bound": "mfma", "achieved": round(achieved, 2),
+                     "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "avg_launch_ms": round(avg_ms, 4),
+                     "launches": f1_n, "flop_per_launch": flops}
+    f2_ms, f2_n = kernel_ms.get("f2", (0.0, 0))
+    if f2_n and half16:
+        avg_ms = f2_ms / f2_n
+        flops, nbytes = mean_over("f2", 0), mean_over("f2", 1)
+        gbps = nbytes / (avg_ms * 1e-3) / 1e9
+        out["tail"] = {"kernel": "f2_ln_bf16_kernel", "bound": "hbm", "achieved": round(gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                       "frac": round(gbps / PEAK_HBM_GBPS, 4), "avg_launch_ms": round(avg_ms, 4), "launches": f2_n,
+                       "algorithmic_bytes_per_launch": nbytes, "TFLOPs": round(flops / (avg_ms * 1e-3) / 1e12, 1)}
+    return out
+
+
+def timed_rank(w: Loaded, steps, warmup, profile_all):
+    """The timed region: `steps` rank calls bracketed by synchronise; the layer's kernels are timed live in every 4th call."""
+    torch, rg = w.torch, w.rg
+    for i in range(warmup):
+        w.rank(i)
+    torch.cuda.synchronize()
+    classes = rg.binding.KERNEL_CLASSES if profile_all else ["attn", "f1", "f2"]
+    stride = 1 if profile_all else 4
+    rg.relaygr_ctx_profile_enable(w.ctx, classes)
+    rg.relaygr_ctx_profile_sample(w.ctx, stride)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for i in range(steps):
+        w.rank(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    kernel_ms = {c: rg.relaygr_ctx_profile_read(w.ctx, c) for c in classes}
+    rg.relaygr_ctx_profile_enable(w.ctx, [])
+    rg.relaygr_ctx_profile_sample(w.ctx, 1)
+    cands = sum(w.cycle[i % len(w.cycle)][1] for i in range(steps))
+    sampled = list(range(0, steps, stride))
+    return elapsed, cands, kernel_ms, sampled
+
+
+# ------------------------------------------------------------------------------------------------
+# ranking beside pre-inference (the paper's operating point)
+# ------------------------------------------------------------------------------------------------
+def masked_stream(n_cus_on, n_cus=256):
+    """A HIP stream of default priority restricted to n_cus_on compute units spread evenly over the chip
+    (hipExtStreamCreateWithCUMask); returns (handle, destroy)."""
+    hip = ctypes.CDLL("libamdhip64.so")
+    words = (n_cus + 31) // 32
+    mask = (ctypes.c_uint32 * words)()
+    # n_cus_on of every n_cus, evenly: bit i is on iff floor((i+1) * on / n) > floor(i * on / n)
+    for i in range(n_cus):
+        if ((i + 1) * n_cus_on) // n_cus > (i * n_cus_on) // n_cus:
+            mask[i // 32] |= 1 << (i % 32)
+    s = ctypes.c_void_p()
+    hip.hipGetErrorString.restype = ctypes.c_char_p
+    rc = hip.hipExtStreamCreateWithCUMask(ctypes.byref(s), ctypes.c_uint32(words), mask)
+    if rc != 0:
+        hip.hipGetLastError()      # the failure must not linger as the thread's last HIP error
+        raise RuntimeError(f"hipExtStreamCreateWithCUMask: error {rc} ({hip.hipGetErrorString(rc).decode()})")
+    return s.value, lambda: hip.hipStreamDestroy(ctypes.c_void_p(s.value))
+
+
+def rank_beside_prefill(w: Loaded, solo_ms_per_step, solo_scores, n_rank=200):
+    """Section 3.2, "Concurrency inside a special instance": pre-inference for other users runs beside ranking on the
+    same accelerator.  A second context and pool pre-infer the same prefixes on a second stream of default priority
+    while the first keeps ranking.  Variants: the second stream unrestricted, or restricted to a share of the compute
+    units (CU mask), and the pre-inference issued in chunks of users instead of one call."""
+    torch, rg = w.torch, w.rg
+    n, L, hit = w.n, w.L, w.hit
+    hb = w.host[0]
+    ctx2 = rg.Context(w.cfg, w.weights, n, int(L.sum()), 0)
+    pool2 = rg.KvPool(ctx2.cfg, w.cfg.dtype, sum(rg.relaygr_kv_pool_bytes_for(ctx2.cfg, int(l), w.page_tokens) for l in L), w.page_tokens)
+    h2 = np.zeros(n, dtype=np.uint64)
+    for u in hit:
+        h2[u] = rg.relaygr_kv_pool_alloc(pool2, int(hb["user_ids"][u]), int(L[u]))
+    prefill_ms = float(np.mean(w.prefill_ms))
+    prefix_tokens = sum(int(L[u]) for u in hit)
+    ev = w.ev
+    out = {"solo_prefill_ms": round(prefill_ms, 4), "prefix_tokens_per_prefill": prefix_tokens, "variants": []}
+
+    def run_variant(label, stream_handle, chunk_users):
+        chunks = [hit[i:i + chunk_users] for i in range(0, len(hit), chunk_users)]
+        pres = [w.sub_batch(c, hb, h2) for c in chunks]
+        per_prefill = max(1, int(round(prefill_ms / solo_ms_per_step)))   # rank calls that fit beside one whole prefill
+        evs = [(ev(), ev()) for _ in range(n_rank)]
+        n_pre = 0
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i, (a, b) in enumerate(evs):
+            if i % per_prefill == 0:
+                for pb in pres:
+                    rg.relaygr_prefill_prefix(ctx2, pool2, pb, stream=stream_handle)
+                n_pre += 1
+            a.record()
+            w.rank(0)
+            b.record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        lat = [a.elapsed_time(b) for a, b in evs]
+        same = bool(np.array_equal(w.scores[:w.sumM].cpu().numpy(), solo_scores))
+        out["variants"].append({"prefill_stream": label, "users_per_prefill_call": chunk_users, "rank_latency_ms": lat_summary(lat),
+                                "candidates_per_s": round(w.sumM * n_rank / wall, 1),
+                                "prefix_tokens_per_s": round(prefix_tokens * n_pre / wall, 1),
+                                "scores_identical_to_solo_run": same})
+
+    s2 = torch.cuda.Stream()
+    run_variant("all compute units", s2, len(hit))
+    run_variant("all compute units", s2, max(1, len(hit) // 8))
+    for on in (128, 64):
+        try:
+            handle, destroy = masked_stream(on)
+        except Exception as exc:  # noqa: BLE001
+            out["variants"].append({"prefill_stream": f"{on} of 256 compute units", "error": str(exc)})
+            continue
+        run_variant(f"{on} of 256 compute units", handle, len(hit))
+        run_variant(f"{on} of 256 compute units", handle, max(1, len(hit) // 8))
+        torch.cuda.synchronize()
+        destroy()
+    ctx2.close()
+    pool2.close()
+    torch.cuda.empty_cache()
+    return out
+
+
+def dram_tier(w: Loaded, solo_scores):
+    """The DRAM tier's `load` step (Section 3.4; the load component of the latency breakdown, Section 4.2 "Where the savings
+    come from"): one user's psi spilled to pinned host memory, its extent freed, the image reloaded, the ranking repeated."""
+    torch, rg = w.torch, w.rg
+    u = w.hit[0]
+    handles = w.handles[0]
+    hu = int(handles[u])
+    nbytes = rg.relaygr_kv_pool_entry_bytes(w.pool, hu)
+    image = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+    spill_ms, load_ms = [], []
+    ev = w.ev
+    for i in range(6):
+        a, b, c2, d2 = ev(), ev(), ev(), ev()
+        a.record()
+        rg.relaygr_kv_pool_spill(w.pool, hu, image)
+        b.record()
+        torch.cuda.synchronize()
+        rg.relaygr_kv_pool_free(w.pool, hu)
+        c2.record()
+        hu = rg.relaygr_kv_pool_reload(w.pool, int(w.host[0]["user_ids"][u]), int(w.L[u]), image)
+        d2.record()
+        torch.cuda.synchronize()
+        if i > 0:
+            spill_ms.append(a.elapsed_time(b))
+            load_ms.append(c2.elapsed_time(d2))
+    handles[u] = hu
+    w.db.set_handles(handles)
+    w.rank(0)
+    torch.cuda.synchronize()
+    return {"user_prefix_tokens": int(w.L[u]), "image_bytes": int(nbytes),
+            "spill_ms": round(float(np.mean(spill_ms)), 4), "load_ms": round(float(np.mean(load_ms)), 4),
+            "load_GBps": round(nbytes / (float(np.mean(load_ms)) * 1e-3) / 1e9, 1),
+            "scores_identical_after_reload": bool(np.array_equal(w.scores[:w.sumM].cpu().numpy(), solo_scores))}
 
 
 def small_m_sweep(torch, rg, synth, n_users=128, L=8192, Ms=(16, 32, 64, 128), steps=20):
@@ -160,6 +498,62 @@ def single_request_breakdown(torch, rg, synth, cfg, weights, shapes=((1024, 512)
     return out
 
 
+def cpu_oracle_sample(w: Loaded, cached_scores, budget_s=10.0):
+    """The float64 oracle on a bounded sample: whole users of the workload (median length first), full recompute,
+    until about ten seconds of CPU work are done; the GPU's scores for those users are compared in passing."""
+    import oracle
+    torch = w.torch
+    L, M = w.L, w.M
+    order = [int(u) for u in np.argsort(np.abs(L - np.median(L)), kind="stable") if M[u] > 0]
+    co = w.host[0]["cand_off"]
+    used, n_c, dt, err, ref_max = [], 0, 0.0, 0.0, 0.0
+    for u0 in order[:8]:
+        p, s, c = w.user_slices(w.host[0], u0)
+        t1 = time.perf_counter()
+        ref = oracle.full_recompute(w.cfg, w.weights, p, s, c)
+        dt += time.perf_counter() - t1
+        used.append((u0, len(p), len(s), len(c)))
+        n_c += len(c)
+        err = max(err, float(np.abs(cached_scores[co[u0]:co[u0 + 1]] - ref).max()))
+        ref_max = max(ref_max, float(np.abs(ref).max()))
+        if dt >= budget_s:
+            break
+    return {"value": round(n_c / dt, 2), "unit": "candidates/s", "cores": int(torch.get_num_threads()),
+            "kind": "oracle", "sample": f"users {[u for u, _, _, _ in used]} of {w.name} (prefix, suffix, candidates: "
+            f"{[(a, b_, c_) for _, a, b_, c_ in used]}), full recompute in float64, {dt:.1f}s",
+            "gpu_vs_oracle_max_abs_err": err, "oracle_max_abs": ref_max}
+
+
+def compact_block(torch, rg, synth, name, batches, rank_calls, full_calls):
+    """A workload beside the main one, in the same run: per-user K/V bytes, rank p50/p99 over `rank_calls` calls (cycling
+    through `batches` seeded batches), candidates/s, full recompute and prefill beside it, the layer's kernels."""
+    gc.collect()
+    w = Loaded(torch, rg, synth, name, batches=batches, prefill_steps=2)
+    half16 = w.cfg.dtype in ("bf16", "fp16")
+    elapsed, cands, kernel_ms, sampled = timed_rank(w, rank_calls, 5, False)
+    lat = w.latency_sample(rank_calls)
+    w.rank(0)
+    torch.cuda.synchronize()
+    cached_scores = w.scores[:w.sumM].cpu().numpy().copy()
+    full_ms, _, full_scores = w.full_recompute(full_calls)
+    roof = kernel_rooflines(w, kernel_ms, sampled, half16, name)
+    out = {"workload": WORKLOAD_TEXT[name], "users": w.n, "batches_cycled": batches,
+           "uncached_users_batch0": int(w.n - len(w.hit)),
+           "kv_bytes_per_user": {"min": int(rg.relaygr_kv_footprint_bytes(w.ctx.cfg, int(w.L.min()))),
+                                 "max": int(rg.relaygr_kv_footprint_bytes(w.ctx.cfg, int(w.L.max())))},
+           "candidates_per_s": round(cands / elapsed, 1), "ms_per_rank_call": round(elapsed * 1e3 / rank_calls, 4),
+           "rank_latency_ms": lat_summary(lat),
+           "full_recompute_ms": round(float(np.mean(full_ms)), 4) if full_ms else None,
+           "speedup_cached_vs_full_batch0": round(float(np.mean(full_ms)) / float(np.mean(lat[0::batches])), 3) if full_ms else None,
+           "max_abs_diff_cached_vs_full": float(np.abs(full_scores - cached_scores).max()) if full_ms else None,
+           "prefill_ms": round(float(np.mean(w.prefill_ms)), 4) if w.prefill_ms else None,
+           "roofline": roof}
+    w.close()
+    del w
+    torch.cuda.empty_cache()
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -169,7 +563,7 @@ def main() -> int:
     ap.add_argument("--full-steps", type=int, default=None, help="timed full-recompute calls (default 100; 20 for C4, C5, X1, X2)")
     ap.add_argument("--prefill-steps", type=int, default=10, help="timed prefill calls")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--profile-all", action="store_true", help="time every kernel class, not only attention")
+    ap.add_argument("--profile-all", action="store_true", help="time every kernel class in every call, not three classes in every 4th")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE")
     ap.add_argument("--no-concurrent", action="store_true", help="skip the rank-beside-prefill measurement on two streams")
@@ -178,6 +572,7 @@ def main() -> int:
                     help="distinct seeded batches the timed rank calls cycle through (default 32 for the jagged C5, else 1)")
     ap.add_argument("--no-single", action="store_true", help="skip the one-user-per-call latency breakdown (pre / load / rank)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the small-M sweep of the attention kernel (its HBM-bound regime)")
+    ap.add_argument("--no-others", action="store_true", help="skip the compact C4 and C5 records beside the main workload")
     args = ap.parse_args()
     if args.batches is None:
         args.batches = 32 if args.config == "C5" else 1
@@ -206,321 +601,83 @@ def main() -> int:
         del src, dst
         torch.cuda.empty_cache()
 
-    wl = synth.WORKLOADS[args.config]
-    cfg = wl.model
+    w = Loaded(torch, rg, synth, args.config, batches=args.batches, prefill_steps=args.prefill_steps, profile_all=args.profile_all)
+    cfg = w.cfg
     half16 = cfg.dtype in ("bf16", "fp16")     # the MFMA path
-    t0 = time.time()
-    weights = synth.make_weights(cfg, wl.seed)
-    batch = synth.make_batch(wl, 0)
-    L, S, M, cached = synth.make_lengths(wl, 0)
-    n = wl.n_users
-    sumL, sumS, sumM = int(L.sum()), int(S.sum()), int(M.sum())
-    print(f"[bench] {args.config}: inputs generated in {time.time() - t0:.1f}s "
-          f"(users {n}, prefix tokens {sumL}, suffix {sumS}, candidates {sumM})", file=sys.stderr, flush=True)
-
-    # further batches of the same workload (other seeds): only the timed rank calls cycle through them, so that the
-    # latency percentiles of a jagged workload see its shape variance; everything else is measured on batch 0
-    extra = []
-    for bi in range(1, args.batches):
-        t1 = time.time()
-        eb = synth.make_batch(wl, bi)
-        eL, eS, eM, ecached = synth.make_lengths(wl, bi)
-        extra.append({"batch": eb, "L": eL, "S": eS, "M": eM, "cached": ecached})
-        print(f"[bench] {args.config}: batch {bi} generated in {time.time() - t1:.1f}s (prefix tokens {int(eL.sum())}, "
-              f"candidates {int(eM.sum())})", file=sys.stderr, flush=True)
-    max_L = max([sumL] + [int(e["L"].sum()) for e in extra])
-    max_new = max([sumS + sumM] + [int(e["S"].sum() + e["M"].sum()) for e in extra])
-    ctx = rg.Context(cfg, weights, n, max_L, max_new)
-    page_tokens = 256
-    pool_bytes = sum(rg.relaygr_kv_pool_bytes_for(ctx.cfg, int(l), page_tokens) for l in L)
-    pool_bytes += sum(rg.relaygr_kv_pool_bytes_for(ctx.cfg, int(l), page_tokens) for e in extra for l in e["L"])
-    pool = rg.KvPool(ctx.cfg, cfg.dtype, pool_bytes, page_tokens)
-    db = rg.Batch(batch, cfg.dtype)
-
-    # ---- pre-inference for the users the workload marks as cached
-    hit = [u for u in range(n) if cached[u] and L[u] > 0]
-    handles = np.zeros(n, dtype=np.uint64)
-    for u in hit:
-        handles[u] = rg.relaygr_kv_pool_alloc(pool, int(batch["user_ids"][u]), int(L[u]))
-    handles_of_batch0 = handles
-    from synth.generator import user_slices
-
-    def sub_batch(users, batch=batch, handles=None):
-        d = cfg.d_model
-        handles = handles_of_batch0 if handles is None else handles
-        segs = [user_slices(batch, u) for u in users]
-
-        def off(k):
-            return np.concatenate([[0], np.cumsum([len(s[k]) for s in segs])]).astype(np.int32)
-        nb = {"n_users": len(users), "user_ids": np.asarray([batch["user_ids"][u] for u in users], dtype=np.uint64),
-              "prefix_emb": np.concatenate([s[0] for s in segs]) if segs else np.zeros((0, d), np.float32),
-              "prefix_off": off(0),
-              "suffix_emb": np.zeros((0, d), np.float32), "suffix_off": np.zeros(len(users) + 1, np.int32),
-              "cand_emb": np.zeros((0, d), np.float32), "cand_off": np.zeros(len(users) + 1, np.int32)}
-        return rg.Batch(nb, cfg.dtype, handles=[handles[u] for u in users])
-
-    pre = sub_batch(hit)
-    ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
-    prefill_ms = []
-    for i in range(1 + args.prefill_steps):
-        a, b = ev(), ev()
-        a.record()
-        rg.relaygr_prefill_prefix(ctx, pool, pre)
-        b.record()
-        torch.cuda.synchronize()
-        if i > 0:
-            prefill_ms.append(a.elapsed_time(b))
-    prefill_kernels = None
-    if args.profile_all and hit:
-        rg.relaygr_ctx_profile_enable(ctx, rg.binding.KERNEL_CLASSES)
-        rg.relaygr_prefill_prefix(ctx, pool, pre)
-        prefill_kernels = {c: round(rg.relaygr_ctx_profile_read(ctx, c)[0], 4) for c in rg.binding.KERNEL_CLASSES}
-        rg.relaygr_ctx_profile_enable(ctx, [])
-    db.set_handles(handles)
-    cycle = [(db, sumM)]
-    for e in extra:
-        eh = np.zeros(n, dtype=np.uint64)
-        ehit = [u for u in range(n) if e["cached"][u] and e["L"][u] > 0]
-        for u in ehit:
-            eh[u] = rg.relaygr_kv_pool_alloc(pool, int(e["batch"]["user_ids"][u]), int(e["L"][u]))
-        rg.relaygr_prefill_prefix(ctx, pool, sub_batch(ehit, e["batch"], eh))
-        torch.cuda.synchronize()
-        e["handles"] = eh
-        cycle.append((rg.Batch(e["batch"], cfg.dtype, handles=eh), int(e["M"].sum())))
-    scores = torch.empty(max(m for _, m in cycle), dtype=torch.float32, device="cuda:0")
 
     # ---- the timed region: K rank calls on the cached prefix.  The interpreter's cyclic collector is parked first: a
     # full collection over the input generator's heap otherwise lands inside one call (about 30 ms once per few
     # thousand binding calls), which is the caller's interpreter, not the path under test.
-    import gc
     gc.collect()
     gc.freeze()
-    for i in range(args.warmup):
-        rg.relaygr_rank_with_cache(ctx, pool, cycle[i % len(cycle)][0], scores)
-    torch.cuda.synchronize()
-    classes = rg.binding.KERNEL_CLASSES if args.profile_all else ["attn"]
-    rg.relaygr_ctx_profile_enable(ctx, classes)
-    # the dominant kernel is timed live in every 4th call of the timed region (all calls with --profile-all)
-    rg.relaygr_ctx_profile_sample(ctx, 1 if args.profile_all else 4)
-    evs = [(ev(), ev()) for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t_start = time.perf_counter()
-    for i, (a, b) in enumerate(evs):
-        a.record()
-        rg.relaygr_rank_with_cache(ctx, pool, cycle[i % len(cycle)][0], scores)
-        b.record()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t_start
-    cands_scored = sum(cycle[i % len(cycle)][1] for i in range(args.steps))
-    lat = [a.elapsed_time(b) for a, b in evs]
-    kernel_ms = {c: rg.relaygr_ctx_profile_read(ctx, c) for c in classes}
-    rg.relaygr_ctx_profile_enable(ctx, [])
-    rg.relaygr_ctx_profile_sample(ctx, 1)
-    timed_calls = (args.steps + 3) // 4 if not args.profile_all else args.steps
+    elapsed, cands_scored, kernel_ms, sampled = timed_rank(w, args.steps, args.warmup, args.profile_all)
     ms_per_step = elapsed * 1e3 / args.steps
     value = cands_scored / elapsed
-    if len(cycle) > 1:      # the comparisons below are on batch 0
-        rg.relaygr_rank_with_cache(ctx, pool, db, scores)
-        torch.cuda.synchronize()
-    cached_scores = scores[:sumM].cpu().numpy().copy()
+    # per-call latency: its own sample of LATENCY_CALLS calls (at least; --steps if larger), independent of --steps
+    lat = w.latency_sample(max(LATENCY_CALLS, args.steps))
+    w.rank(0)                                  # the comparisons below are on batch 0
+    torch.cuda.synchronize()
+    cached_scores = w.scores[:w.sumM].cpu().numpy().copy()
 
     # ---- the baseline in the same run: full inference inline
-    full_ms = []
-    for i in range(1 + args.full_steps if args.full_steps > 0 else 0):
-        a, b = ev(), ev()
-        a.record()
-        rg.relaygr_rank_full_recompute(ctx, db, scores)
-        b.record()
-        torch.cuda.synchronize()
-        if i > 0:
-            full_ms.append(a.elapsed_time(b))
-    full_kernels = None
-    if args.profile_all and full_ms:
-        rg.relaygr_ctx_profile_enable(ctx, rg.binding.KERNEL_CLASSES)
-        rg.relaygr_rank_full_recompute(ctx, db, scores)
-        full_kernels = {c: round(rg.relaygr_ctx_profile_read(ctx, c)[0], 4) for c in rg.binding.KERNEL_CLASSES}
-        rg.relaygr_ctx_profile_enable(ctx, [])
-    full_scores = scores[:sumM].cpu().numpy()
+    full_ms, full_kernels, full_scores = w.full_recompute(args.full_steps, args.profile_all)
     full_mean = float(np.mean(full_ms)) if full_ms else None
-    max_diff = float(np.abs(full_scores - cached_scores).max()) if (sumM and full_ms) else None
+    max_diff = float(np.abs(full_scores - cached_scores).max()) if (w.sumM and full_ms) else None
 
-    # ---- the paper's operating point (Section 3.2, "Concurrency inside a special instance"): pre-inference for other
-    # users runs beside ranking on the same accelerator.  A second context and pool pre-infer the same prefixes on a
-    # second stream of default priority while the first keeps ranking; what is reported is the rank latency under that load.
     concurrent = None
-    if not args.no_concurrent and hit and half16:
-        ctx2 = rg.Context(cfg, weights, n, sumL, 0)
-        pool2 = rg.KvPool(ctx2.cfg, cfg.dtype, pool_bytes, page_tokens)
-        h2 = [rg.relaygr_kv_pool_alloc(pool2, int(batch["user_ids"][u]), int(L[u])) for u in hit]
-        pre2 = sub_batch(hit)
-        pre2.set_handles(h2)
-        s2 = torch.cuda.Stream()
-        n_conc = max(20, args.steps // 2)
-        per_prefill = max(1, int(round(float(np.mean(prefill_ms)) / ms_per_step)))   # rank calls that fit beside one prefill
-        evs2 = [(ev(), ev()) for _ in range(n_conc)]
-        pe = []
-        torch.cuda.synchronize()
-        t2 = time.perf_counter()
-        for i, (a, b) in enumerate(evs2):
-            if i % per_prefill == 0:
-                pa, pb_ = ev(), ev()
-                pa.record(s2)
-                rg.relaygr_prefill_prefix(ctx2, pool2, pre2, stream=s2)
-                pb_.record(s2)
-                pe.append((pa, pb_))
-            a.record()
-            rg.relaygr_rank_with_cache(ctx, pool, db, scores)
-            b.record()
-        torch.cuda.synchronize()
-        wall2 = time.perf_counter() - t2
-        lat2 = [a.elapsed_time(b) for a, b in evs2]
-        pre_lat = [a.elapsed_time(b) for a, b in pe]
-        same = bool(np.array_equal(scores[:sumM].cpu().numpy(), cached_scores))
-        concurrent = {"rank_calls": n_conc, "prefill_calls": len(pe),
-                      "rank_latency_ms": {"p50": round(percentile(lat2, 50), 4), "p99": round(percentile(lat2, 99), 4)},
-                      "prefill_latency_ms": {"p50": round(percentile(pre_lat, 50), 4), "max": round(max(pre_lat), 4)},
-                      "candidates_per_s": round(sumM * n_conc / wall2, 1),
-                      "prefix_tokens_per_s": round(sum(int(L[u]) for u in hit) * len(pe) / wall2, 1),
-                      "scores_identical_to_solo_run": same}
-        ctx2.close()
-        pool2.close()
-        del ctx2, pool2, pre2
-        torch.cuda.empty_cache()
+    if not args.no_concurrent and w.hit and half16:
+        concurrent = rank_beside_prefill(w, ms_per_step, cached_scores)
+        concurrent["solo_rank_latency_ms"] = lat_summary(lat)
+    dram = dram_tier(w, cached_scores) if (not args.no_dram and w.hit) else None
+    roof = kernel_rooflines(w, kernel_ms, sampled, half16, args.config) or None
+    cpu = None if args.no_cpu_baseline else cpu_oracle_sample(w, cached_scores)
 
-    # ---- the DRAM tier's `load` step (Section 3.4; the load component of the latency breakdown, Section 4.2 "Where the savings come from"): one user's psi
-    # spilled to pinned host memory, its extent freed, the image reloaded, and the same ranking repeated on it
-    dram = None
-    if not args.no_dram and hit:
-        u = hit[0]
-        hu = int(handles[u])
-        nbytes = rg.relaygr_kv_pool_entry_bytes(pool, hu)
-        image = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
-        spill_ms, load_ms = [], []
-        for i in range(6):
-            a, b, c2, d2 = ev(), ev(), ev(), ev()
-            a.record()
-            rg.relaygr_kv_pool_spill(pool, hu, image)
-            b.record()
-            torch.cuda.synchronize()
-            rg.relaygr_kv_pool_free(pool, hu)
-            c2.record()
-            hu = rg.relaygr_kv_pool_reload(pool, int(batch["user_ids"][u]), int(L[u]), image)
-            d2.record()
-            torch.cuda.synchronize()
-            if i > 0:
-                spill_ms.append(a.elapsed_time(b))
-                load_ms.append(c2.elapsed_time(d2))
-        handles[u] = hu
-        db.set_handles(handles)
-        rg.relaygr_rank_with_cache(ctx, pool, db, scores)
-        torch.cuda.synchronize()
-        dram = {"user_prefix_tokens": int(L[u]), "image_bytes": int(nbytes),
-                "spill_ms": round(float(np.mean(spill_ms)), 4), "load_ms": round(float(np.mean(load_ms)), 4),
-                "load_GBps": round(nbytes / (float(np.mean(load_ms)) * 1e-3) / 1e9, 1),
-                "scores_identical_after_reload": bool(np.array_equal(scores[:sumM].cpu().numpy(), cached_scores))}
-
-    # ---- roofline of the dominant kernel (attention over the cached prefix + suffix)
-    d = cfg.d_model
-    e = cfg.elem_bytes
-    # keys each new row visits: candidates see L+S, suffix row t sees L+t+1
-    def attn_flops_per_layer(L, S, M, handles):
-        """FLOP of the attention launches of one rank call on a batch: 4 d per (row, visible key), candidates see L+S
-        keys, suffix row t sees L+t+1; layers but the last also carry the uncached users' causal prefix pass."""
-        key_visits = sum(int(M[u]) * int(L[u] + S[u]) + sum(int(L[u]) + t + 1 for t in range(int(S[u]))) for u in range(n))
-        causal_visits = sum(int(L[u]) * (int(L[u]) + 1) // 2 for u in range(n) if not handles[u])
-        new_rows = 4.0 * d * key_visits
-        return [new_rows + 4.0 * d * causal_visits] * (cfg.n_layers - 1) + [new_rows]
-
-    per_batch = [attn_flops_per_layer(L, S, M, handles)] + [attn_flops_per_layer(e["L"], e["S"], e["M"], e["handles"]) for e in extra]
-    flops_per_launch = per_batch[0][-1]
-    miss_L = sum(int(L[u]) for u in range(n) if not handles[u])
-    attn_ms, attn_n = kernel_ms["attn"]
-    roof = None
-    if attn_n:
-        # the launches timed live are those of every 4th call (every call with --profile-all); call i ran batch i mod N
-        stride = 1 if args.profile_all else 4
-        timed_layers = [f for i in range(0, args.steps, stride) for f in per_batch[i % len(per_batch)]]
-        avg_flops = float(np.mean(timed_layers))
-        avg_ms = attn_ms / attn_n
-        peak = PEAK_BF16_TFLOPS if half16 else PEAK_FP32_TFLOPS   # fp16 and bf16 share the dense MFMA peak
-        achieved = avg_flops / (avg_ms * 1e-3) / 1e12
-        kv_bytes = 2.0 * (sumL + sumS) * d * e + (sumS + sumM) * d * (e + 4)   # K,V once; q in; fp32 partial out
-        roof = {
-            "kernel": "attn_bf16_kernel" if half16 else "attn_f32_kernel",
-            "bound": "mfma" if half16 else "alu",
-            "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-            "traffic": MEASURED_ATTN_TRAFFIC_BYTES.get(args.config),
-            "avg_launch_ms": round(avg_ms, 4), "launches": attn_n,
-            "flop_per_launch": avg_flops,
-            "algorithmic_bytes_per_launch": kv_bytes,
-            "algorithmic_GBps": round(kv_bytes / (avg_ms * 1e-3) / 1e9, 1),
-            "hbm_frac_of_8TBps": round(kv_bytes / (avg_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4),
-        }
-
-    # ---- CPU oracle on a bounded sample: whole users of this workload (median length first), full recompute,
-    # until about ten seconds of CPU work are done
-    cpu = None
-    if not args.no_cpu_baseline:
-        import oracle
-        order = [int(u) for u in np.argsort(np.abs(L - np.median(L)), kind="stable") if M[u] > 0]
-        co = batch["cand_off"]
-        used, n_c, dt, err, ref_max = [], 0, 0.0, 0.0, 0.0
-        for u0 in order[:8]:
-            p, s, c = user_slices(batch, u0)
-            t1 = time.perf_counter()
-            ref = oracle.full_recompute(cfg, weights, p, s, c)
-            dt += time.perf_counter() - t1
-            used.append((u0, len(p), len(s), len(c)))
-            n_c += len(c)
-            err = max(err, float(np.abs(cached_scores[co[u0]:co[u0 + 1]] - ref).max()))
-            ref_max = max(ref_max, float(np.abs(ref).max()))
-            if dt >= 10.0:
-                break
-        cpu = {"value": round(n_c / dt, 2), "unit": "candidates/s", "cores": int(torch.get_num_threads()),
-               "kind": "oracle", "sample": f"users {[u for u, _, _, _ in used]} of {args.config} (prefix, suffix, candidates: "
-               f"{[(a, b_, c_) for _, a, b_, c_ in used]}), full recompute in float64, {dt:.1f}s",
-               "gpu_vs_oracle_max_abs_err": err, "oracle_max_abs": ref_max}
-
-    kv_bytes = {"min": int(rg.relaygr_kv_footprint_bytes(ctx.cfg, int(L.min()))),
-                "max": int(rg.relaygr_kv_footprint_bytes(ctx.cfg, int(L.max())))}
-    sweep = single = None
-    if not (args.no_sweep and args.no_single) and half16:
-        ctx.close(); pool.close()
-        del ctx, pool, db, pre
-        torch.cuda.empty_cache()
-        if not args.no_single:
-            single = single_request_breakdown(torch, rg, synth, cfg, weights)
-            torch.cuda.empty_cache()
-        if not args.no_sweep:
-            sweep = small_m_sweep(torch, rg, synth)
-
+    kv_bytes = {"min": int(rg.relaygr_kv_footprint_bytes(w.ctx.cfg, int(w.L.min()))),
+                "max": int(rg.relaygr_kv_footprint_bytes(w.ctx.cfg, int(w.L.max())))}
+    timed_calls = len(sampled)
     out = {
         "metric": "candidates scored/sec, ranking on the cached prefix (rank stage); p99 rank latency and full recompute beside it",
         "value": round(value, 1), "unit": "candidates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": WORKLOAD_TEXT[args.config], "users": n, "prefix_tokens": sumL, "suffix_tokens": sumS,
-                   "candidates": sumM, "uncached_users": int(n - len(hit)), "page_tokens": page_tokens,
+        "config": {"workload": WORKLOAD_TEXT[args.config], "users": w.n, "prefix_tokens": int(w.L.sum()), "suffix_tokens": int(w.S.sum()),
+                   "candidates": w.sumM, "uncached_users": int(w.n - len(w.hit)), "page_tokens": w.page_tokens,
                    "batches_cycled": args.batches},
-        "rank_latency_ms": {"p50": round(percentile(lat, 50), 4), "p99": round(percentile(lat, 99), 4),
-                            "mean": round(float(np.mean(lat)), 4)},
+        "rank_latency_ms": lat_summary(lat),
         "full_recompute": {"ms": round(full_mean, 4) if full_mean else None,
-                           "candidates_per_s": round(sumM / (full_mean * 1e-3), 1) if full_mean else None,
+                           "candidates_per_s": round(w.sumM / (full_mean * 1e-3), 1) if full_mean else None,
                            "calls": len(full_ms), "max_abs_diff_vs_cached": max_diff, "kernel_ms": full_kernels},
         "speedup_cached_vs_full": round(full_mean / ms_per_step, 3) if full_mean else None,
-        "prefill": {"ms": round(float(np.mean(prefill_ms)), 4) if prefill_ms else None, "prefix_tokens": int(sum(L[u] for u in hit)),
-                    "tokens_per_s": round(sum(int(L[u]) for u in hit) / (np.mean(prefill_ms) * 1e-3), 1) if prefill_ms else None},
-        "prefill_kernel_ms": prefill_kernels,
+        "prefill": {"ms": round(float(np.mean(w.prefill_ms)), 4) if w.prefill_ms else None, "prefix_tokens": int(sum(w.L[u] for u in w.hit)),
+                    "tokens_per_s": round(sum(int(w.L[u]) for u in w.hit) / (np.mean(w.prefill_ms) * 1e-3), 1) if w.prefill_ms else None},
+        "prefill_kernel_ms": w.prefill_kernels,
         "kv_bytes_per_user": kv_bytes,
         "kernel_ms_per_step": {c: round(ms / timed_calls, 4) for c, (ms, cnt) in kernel_ms.items()},
         "roofline": roof,
         "rank_beside_prefill": concurrent,
-        "attention_small_m_sweep": sweep,
         "dram_tier": dram,
-        "single_request_latency": single,
         "cpu_baseline": cpu,
-        "paper_context": "RelayGR on Ascend 910C NPUs: up to 1.5x longer sequences and 3.6x SLO-compliant throughput (system-level, not comparable)",
     }
+    weights = w.weights
+    w.close()
+    del w
+    torch.cuda.empty_cache()
+    gc.unfreeze()
+
+    if half16 and not args.no_single:
+        out["single_request_latency"] = single_request_breakdown(torch, rg, synth, cfg, weights)
+        torch.cuda.empty_cache()
+    if half16 and not args.no_sweep:
+        out["attention_small_m_sweep"] = small_m_sweep(torch, rg, synth)
+        torch.cuda.empty_cache()
+    if not args.no_others:
+        others = {}
+        if args.config != "C4":
+            others["C4"] = compact_block(torch, rg, synth, "C4", batches=1, rank_calls=LATENCY_CALLS, full_calls=5)
+        if args.config != "C5":
+            others["C5"] = compact_block(torch, rg, synth, "C5", batches=8, rank_calls=LATENCY_CALLS, full_calls=3)
+        out["other_workloads"] = others
+    out["paper_context"] = "RelayGR on Ascend 910C NPUs: up to 1.5x longer sequences and 3.6x SLO-compliant throughput (system-level, not comparable)"
     print(json.dumps(out), flush=True)
     return 0
 

@@ -182,7 +182,10 @@ def relaygr_scratch_bytes(cfg: ModelConfigC, max_users: int, max_prefix_tokens: 
     return load_library().relaygr_scratch_bytes(C.byref(cfg), max_users, max_prefix_tokens, max_new_tokens)
 
 
-def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
+def _stream_ptr(stream) -> int:
+    """HIP stream handle of a torch stream (default: torch's current stream) or a raw hipStream_t given as an int."""
+    if isinstance(stream, int):
+        return stream
     s = stream if stream is not None else torch.cuda.current_stream()
     return int(s.cuda_stream)
 

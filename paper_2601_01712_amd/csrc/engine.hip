@@ -964,6 +964,7 @@ static int run(relaygr_ctx* c, relaygr_kv_pool* pool, const relaygr_batch* b, Mo
       return fail(RELAYGR_EINVAL, "pool and context were created for different model shapes");
   }
   hipStream_t st = (hipStream_t)stream;
+  (void)hipGetLastError();   // a failure the caller's own HIP calls left behind is not this call's: launch checks below start clean
   const size_t wp = wpack_bytes(c->cfg);
   const CallScratch own = {c->scratch + wp, c->scratch_bytes - wp};
   const CallScratch& cs = other ? *other : own;
