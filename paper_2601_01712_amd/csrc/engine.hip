@@ -815,7 +815,7 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
         fp.u = (uint16_t*)ubuf; fp.q = (uint16_t*)qbuf; fp.knew = (uint16_t*)knew; fp.vnew = (uint16_t*)vnew; fp.sfx = (uint16_t*)sfx;
         fp.users = d_users; fp.rt = rt; fp.d = d; fp.dh = dh; fp.n_prows = p.n_prows; fp.layer = l;
         fp.row_begin = r0; fp.row_end = r1; fp.n_mtiles = (r1 - r0 + 64 * kF1TM - 1) / (64 * kF1TM);
-        fp.cm = cm; fp.q_mul = q_mul;
+        fp.cm = cm; fp.q_mul = q_mul; fp.stream_out = (r1 - r0) >= kF1StreamMinRows ? 1 : 0;
         // launches of a few thousand rows take the weight-stationary kernel: one persistent workgroup per compute unit,
         // (compute units / column slices) row groups, a multiple of 8 so that each XCD takes whole row groups
         const int n_slices = cm.nblk * (d / 128);

@@ -143,6 +143,7 @@ struct F1Params {
   int d, dh, n_prows, layer, row_begin, row_end, n_mtiles;
   ColMap cm;
   float q_mul;
+  int stream_out;           // weight-stationary kernel: outputs leave with streaming stores (launches that write far more than L2 holds)
 };
 
 
@@ -212,7 +213,7 @@ __global__ __launch_bounds__(256, 2) void f1_gemm_bf16_kernel(F1Params p) {
             w[2 * h] = H::pack2(v[0], v[1]);
             w[2 * h + 1] = H::pack2(v[2], v[3]);
           }
-          st_stream(reinterpret_cast<uint4*>(frag + (((db * 2 + kb) * 2 + m) * 64 + lane) * 8), make_uint4(w[0], w[1], w[2], w[3]));
+          *reinterpret_cast<uint4*>(frag + (((db * 2 + kb) * 2 + m) * 64 + lane) * 8) = make_uint4(w[0], w[1], w[2], w[3]);
         }
       }
     }
@@ -263,10 +264,10 @@ __global__ __launch_bounds__(256, 2) void f1_gemm_bf16_kernel(F1Params p) {
     if (kind == kRowPad && (blk == 0 || blk == 2)) continue;
     uint4 val = *reinterpret_cast<const uint4*>(&lds[t * kStageLd + fc * 8]);
     const int c = c0 + fc * 8;                             // feature inside the block
-    if (blk == 0) { st_stream(reinterpret_cast<uint4*>(p.u + (size_t)row * d + c), val); continue; }
-    if (blk == 2) { st_stream(reinterpret_cast<uint4*>(p.q + (size_t)row * d + c), val); continue; }
+    if (blk == 0) { *reinterpret_cast<uint4*>(p.u + (size_t)row * d + c) = val; continue; }
+    if (blk == 2) { *reinterpret_cast<uint4*>(p.q + (size_t)row * d + c) = val; continue; }
     if (kind == kRowCand) {
-      st_stream(reinterpret_cast<uint4*>((blk == 3 ? p.knew : p.vnew) + (size_t)(row - p.n_prows) * d + c), val);
+      *reinterpret_cast<uint4*>((blk == 3 ? p.knew : p.vnew) + (size_t)(row - p.n_prows) * d + c) = val;
       continue;
     }
     const int head = c / dh, f = c - head * dh;
@@ -285,7 +286,7 @@ __global__ __launch_bounds__(256, 2) void f1_gemm_bf16_kernel(F1Params p) {
     }
     const int rr = idx & 63;
     if (blk == 3) {
-      st_stream(reinterpret_cast<uint4*>(base + KvLayout16::k_off(rr, f, dh)), val);
+      *reinterpret_cast<uint4*>(base + KvLayout16::k_off(rr, f, dh)) = val;
     } else {   // V of a suffix row: its 8 features go to 8 different fragments
       const uint16_t* e = reinterpret_cast<const uint16_t*>(&val);
 #pragma unroll
@@ -305,11 +306,16 @@ __global__ __launch_bounds__(256, 2) void f1_gemm_bf16_kernel(F1Params p) {
 // landed, so the two wavefronts of a SIMD drift apart and one's epilogue (vector ALU, stores) runs beside
 // the other's main loop (matrix cores).  The accumulators start from the bias.  Results are staged through
 // 4 KiB of wavefront-private LDS (32 tokens x 64 features, 16-byte chunks swizzled by token so that neither
-// the 8-byte writes nor the 16-byte reads pile up on a bank) and leave as 128-byte row segments with
-// streaming stores; V of prefix rows takes the token-major product, whose accumulators are V-tile
-// fragments as they stand.  Measured against the tiled kernel above (65 536 x 2048 x 512): 152 us against 205.
+// the 8-byte writes nor the 16-byte reads pile up on a bank) and leave as 128-byte row segments; V of prefix
+// rows takes the token-major product, whose accumulators are V-tile fragments as they stand.  Launches that
+// write far more than the L2s hold use streaming stores (see st_stream): with plain stores the output lines
+// evict the token panels the workgroups of an XCD share and the kernel runs at the speed of the re-fetches
+// (65 536 x 2048 x 512 stand-alone: 225 us plain, 152 us streaming, 205 us for the tiled kernel above); small
+// launches keep plain stores, because what they write fits the L2s and the attention and layer-tail kernels
+// read it straight back (8192 rows: the layer tail is 2 us slower behind streaming stores).
 constexpr int kF1WsPF = 4;          // k-steps of token fragments in flight per wavefront
 constexpr int kF1WsMinRows = 4096;  // below this the tiled kernel's many small workgroups fill the chip better
+constexpr int kF1StreamMinRows = 16384;   // from here on a launch writes 64 MiB and more (at d = 512): streaming stores
 
 template <typename H, int D, bool FEATURE_MAJOR>
 __device__ __forceinline__ void f1_ws_mainloop(const uint16_t* __restrict__ tp0, const uint16_t* __restrict__ tp1,
@@ -344,6 +350,11 @@ __device__ __forceinline__ void f1_ws_mainloop(const uint16_t* __restrict__ tp0,
       }
     }
   }
+}
+
+__device__ __forceinline__ void st_out(uint4* dst, uint4 v, int stream) {
+  if (stream) st_stream(dst, v);
+  else *dst = v;
 }
 
 template <typename H, int D>
@@ -432,7 +443,7 @@ __global__ __launch_bounds__(512, 1) void f1_ws_bf16_kernel(F1Params p) {
               w[2 * h] = H::pack2(v[0], v[1]);
               w[2 * h + 1] = H::pack2(v[2], v[3]);
             }
-            st_stream(reinterpret_cast<uint4*>(frag + (((db * 2 + kb) * 2 + m) * 64 + lane) * 8), make_uint4(w[0], w[1], w[2], w[3]));
+            st_out(reinterpret_cast<uint4*>(frag + (((db * 2 + kb) * 2 + m) * 64 + lane) * 8), make_uint4(w[0], w[1], w[2], w[3]), p.stream_out);
           }
         }
       }
@@ -488,10 +499,10 @@ __global__ __launch_bounds__(512, 1) void f1_ws_bf16_kernel(F1Params p) {
           if (kind < 0) continue;                                // beyond the launch's last row
           if (kind == kRowPad && (blk == 0 || blk == 2)) continue;
           const int c = c0 + jh * 64 + fc * 8;                   // feature inside the block
-          if (blk == 0) { st_stream(reinterpret_cast<uint4*>(p.u + (size_t)row * d + c), val); continue; }
-          if (blk == 2) { st_stream(reinterpret_cast<uint4*>(p.q + (size_t)row * d + c), val); continue; }
+          if (blk == 0) { st_out(reinterpret_cast<uint4*>(p.u + (size_t)row * d + c), val, p.stream_out); continue; }
+          if (blk == 2) { st_out(reinterpret_cast<uint4*>(p.q + (size_t)row * d + c), val, p.stream_out); continue; }
           if (kind == kRowCand) {
-            st_stream(reinterpret_cast<uint4*>((blk == 3 ? p.knew : p.vnew) + (size_t)(row - p.n_prows) * d + c), val);
+            st_out(reinterpret_cast<uint4*>((blk == 3 ? p.knew : p.vnew) + (size_t)(row - p.n_prows) * d + c), val, p.stream_out);
             continue;
           }
           const int head = c / dh, f = c - head * dh;
@@ -510,7 +521,7 @@ __global__ __launch_bounds__(512, 1) void f1_ws_bf16_kernel(F1Params p) {
           }
           const int rr = pos & 63;
           if (blk == 3) {
-            st_stream(reinterpret_cast<uint4*>(base + KvLayout16::k_off(rr, f, dh)), val);
+            st_out(reinterpret_cast<uint4*>(base + KvLayout16::k_off(rr, f, dh)), val, p.stream_out);
           } else {   // V of a suffix row: its 8 features go to 8 different fragments
             const uint16_t* e = reinterpret_cast<const uint16_t*>(&val);
 #pragma unroll

@@ -362,9 +362,10 @@ def test_reload_does_not_wait_for_a_spill_held_up_by_another_stream():
         rg.relaygr_expander_retire(ex, int(h.handles[1]))
         _settle(ex)
         rg.relaygr_expander_trim(ex, 0)                              # user 1 lives in DRAM only
-        sa, sb = torch.cuda.Stream(), torch.cuda.Stream()            # default priority
-        with torch.cuda.stream(sa):
-            torch.cuda._sleep(400_000_000)                           # a bounded spin kernel: stream A is busy for a while
+        # stream A is torch's current stream, B one more: with the expander's two that makes four, the number of hardware
+        # queues a process has here (streams that share a hardware queue wait for each other whatever the events say)
+        sa, sb = torch.cuda.current_stream(), torch.cuda.Stream()    # default priority
+        torch.cuda._sleep(400_000_000)                               # a bounded spin kernel (about 170 ms): stream A is busy for a while
         rg.relaygr_expander_retire(ex, int(h.handles[0]), stream=sa)  # this spill waits for stream A
         h1, src = rg.relaygr_expander_lookup(ex, _uid(batch, 1), stream=sb)
         assert src == 1
@@ -376,7 +377,7 @@ def test_reload_does_not_wait_for_a_spill_held_up_by_another_stream():
         st = _settle(ex)
         assert st["spills"] == 2 and st["dram_hits"] == 1
         if not a_still_busy:
-            pytest.skip("stream A had finished before the reload: inconclusive")
+            pytest.skip("stream A had finished when the reload completed: inconclusive (the streams may share a hardware queue)")
     finally:
         ex.close()
         h.close()
