@@ -37,6 +37,12 @@ struct AttnParams {
   int n_tiles;        // work items in this launch
   int d, n_heads, layer;
   float score_mul;    // multiplies <q,k> before SiLU (alpha, or 1 if q is stored pre-scaled)
+  // MFMA kernel, SiLU form: a candidate's own key (the diagonal of the candidate block: a per-row dot product, never an
+  // M x M tile) is added by the work item of key split 0, from the row-major k and v of the new rows; null: left to the
+  // layer-tail kernel
+  const void* knew;   // [new rows][d]
+  const void* vnew;
+  int n_prows;        // rows before the first new row
 };
 
 // Key-tile schedule of one work item, shared by both kernels.
@@ -350,6 +356,62 @@ __global__ __launch_bounds__(NW * 64, (DH >= 128) ? 1 : 512 / (NW * 64)) void at
 #pragma unroll
   for (int qb = 0; qb < NQ; ++qb) { mref[qb] = -INFINITY; lsum[qb] = 0.f; }
 
+  // The candidate's own key (SiLU form): the sums of key split 0 start from it instead of from zero.  Its k and v rows
+  // are requested here, ahead of the first key tiles, and used once those are on their way.  q and k carry the same
+  // scaling as in the key tiles (t in log2 units), the term takes the common ln 2 at the end; fp32 throughout.  A
+  // row's q fragments are split over its two lanes (g = 0, 1).
+  // With several key splits the row blocks' own keys are dealt over the splits' work items (block qb to split qb mod nsplit),
+  // so that no work item carries all of them.
+  const bool own_key = !SOFTMAX && p.knew != nullptr && at.kind == 1 && split < NQ;
+  uint4 kself[NQ][KS];
+  uint2 vself[NQ][DB][4];
+  bool cand[NQ];
+#pragma unroll
+  for (int qb = 0; qb < NQ; ++qb) {
+    const int lr = wave * 32 * NQ + qb * 32 + l32;
+    cand[qb] = own_key && (qb % p.nsplit) == split && lr < at.nrows && at.pos0 + lr >= ud.S;   // new rows: suffix rows, then candidates
+    if (cand[qb]) {
+      const size_t nb = (size_t)(at.row0 + lr - p.n_prows) * p.d + head * DH;
+      const uint16_t* kn = reinterpret_cast<const uint16_t*>(p.knew) + nb;
+      const uint16_t* vn = reinterpret_cast<const uint16_t*>(p.vnew) + nb;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) kself[qb][ks] = *reinterpret_cast<const uint4*>(kn + ks * 16 + g * 8);
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) vself[qb][db][e4] = *reinterpret_cast<const uint2*>(vn + db * 32 + 8 * e4 + 4 * g);
+    }
+  }
+  auto start_from_own_key = [&]() {
+    if (!own_key) return;                       // uniform over the workgroup
+#pragma unroll
+    for (int qb = 0; qb < NQ; ++qb) {
+      float dot = 0.f;
+      if (cand[qb]) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          const uint32_t qw[4] = {qf[qb][ks].x, qf[qb][ks].y, qf[qb][ks].z, qf[qb][ks].w};
+          const uint32_t kw[4] = {kself[qb][ks].x, kself[qb][ks].y, kself[qb][ks].z, kself[qb][ks].w};
+#pragma unroll
+          for (int i = 0; i < 8; ++i) dot += H::of_word(qw[i >> 1], i) * H::of_word(kw[i >> 1], i);
+        }
+      }
+      dot += __shfl_xor(dot, 32, 64);
+      const float pe = cand[qb] ? dot / (1.0f + __builtin_amdgcn_exp2f(-dot)) : 0.f;
+      if (cand[qb]) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int e4 = 0; e4 < 4; ++e4) {
+            oacc[db][qb][4 * e4] = pe * H::of_word(vself[qb][db][e4].x, 0);
+            oacc[db][qb][4 * e4 + 1] = pe * H::of_word(vself[qb][db][e4].x, 1);
+            oacc[db][qb][4 * e4 + 2] = pe * H::of_word(vself[qb][db][e4].y, 0);
+            oacc[db][qb][4 * e4 + 3] = pe * H::of_word(vself[qb][db][e4].y, 1);
+          }
+      }
+    }
+  };
+
   const uint16_t* kv_base = reinterpret_cast<const uint16_t*>(ud.kv) + ud.kv_tile0 + (int64_t)p.layer * ud.kv_layer_stride +
                             (int64_t)head * TILE;
   const uint16_t* sfx_base = reinterpret_cast<const uint16_t*>(p.sfx) + ud.sfx_tile0 + (int64_t)head * TILE;
@@ -369,10 +431,12 @@ __global__ __launch_bounds__(NW * 64, (DH >= 128) ? 1 : 512 / (NW * 64)) void at
   // a wavefront whose rows all lie beyond the work item's last row only helps move tiles
   const bool wave_active = wave * 32 * NQ < at.nrows;
   const int nt = tr.t1 - tr.t0;
+  if (nt == 0) start_from_own_key();
   if (nt > 0) {
     issue_tile(tr.t0, 0);
+    if (nt > 1) issue_tile(tr.t0 + 1, 1);
+    start_from_own_key();             // its loads are older than the tiles'
     if (nt > 1) {
-      issue_tile(tr.t0 + 1, 1);
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"(CHUNKS) : "memory");   // tile 0 landed, tile 1 may still fly
     } else {
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");

@@ -849,6 +849,9 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
     ap.tiles = d_tiles; ap.users = d_users; ap.rt = rt; ap.q = qbuf; ap.sfx = sfx; ap.part = part;
     ap.split_stride = (size_t)R * d; ap.nsplit = p.nsplit; ap.d = d; ap.n_heads = H; ap.layer = l; ap.score_mul = score_mul;
     ap.ml = ml; ap.ml_stride = (size_t)R * H * 2;
+    // 16-bit SiLU form: the attention kernel adds the candidates' own keys, so the layer tail does not read q, k, v again
+    const bool self_in_attn = bf16 && !softmax;
+    ap.knew = self_in_attn ? (const void*)knew : nullptr; ap.vnew = vnew; ap.n_prows = p.n_prows;
     int nt = last ? p.n_tiles_new : n_tiles_all;
     ap.n_tiles = nt;
     if (nt > 0) {
@@ -899,7 +902,7 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
           fp.w_score = (const uint16_t*)c->w_score; fp.b_score = c->b_score; fp.scores = score_here ? scores : nullptr;
           fp.row_begin = a0; fp.row_end = R; fp.eps = cfg.ln_eps;
           fp.part = part; fp.nsplit = p.nsplit; fp.split_stride = (size_t)R * d;
-          fp.u = (const uint16_t*)ubuf; fp.q = (const uint16_t*)qbuf; fp.knew = (const uint16_t*)knew; fp.vnew = (const uint16_t*)vnew;
+          fp.u = (const uint16_t*)ubuf; fp.q = self_in_attn ? nullptr : (const uint16_t*)qbuf; fp.knew = (const uint16_t*)knew; fp.vnew = (const uint16_t*)vnew;
           fp.gate_gain = (const uint16_t*)lw.ln_at_g; fp.gate_offs = (const uint16_t*)lw.ln_at_b;
           fp.n_prows = p.n_prows; fp.dh = dh; fp.qk_mul = gate_mul;
           fp.ml = softmax ? ml : nullptr; fp.ml_stride = (size_t)R * H * 2; fp.n_heads = H;

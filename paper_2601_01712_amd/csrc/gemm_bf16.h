@@ -554,7 +554,7 @@ struct F2LnParams {
   int nsplit;
   size_t split_stride;
   const uint16_t* u;        // [rows, D]
-  const uint16_t* q;        // [rows, D] (pre-scaled)
+  const uint16_t* q;        // [rows, D] (pre-scaled); null: the attention kernel has added the candidates' own keys already
   const uint16_t* knew;     // [new rows, D] row-major k and v of suffix and candidate rows
   const uint16_t* vnew;
   const uint16_t* gate_gain;
@@ -653,7 +653,7 @@ __device__ __forceinline__ void load_gate_row(const F2LnParams& p, int row, bool
     }
   }
   ld_bf16_run<E>(p.u + base, gr.ub);
-  if (row >= p.n_prows) {           // suffix and candidate rows have row-major q, k, v (only candidates use them)
+  if (row >= p.n_prows && p.q != nullptr) {   // suffix and candidate rows have row-major q, k, v (only candidates use them)
     const size_t nb = (size_t)(row - p.n_prows) * D + lane * E;
     ld_bf16_run<E>(p.q + base, gr.qb);
     ld_bf16_run<E>(p.knew + nb, gr.kb);
@@ -672,7 +672,9 @@ __device__ __forceinline__ void finish_gate_rows(const F2LnParams& p, GateRow<D 
   for (int r = 0; r < G; ++r) {
     int n = gr[r].n;
     float lsum = gr[r].lpart;
-    if (gr[r].kind == kRowCand) {      // the candidate's own key: SiLU(alpha <q_c, k_c>) v_c per head
+    if (gr[r].kind == kRowCand && p.q == nullptr) {
+      n += 1;                          // the own key is in the sums already; it counts as a visible key
+    } else if (gr[r].kind == kRowCand) {      // the candidate's own key: SiLU(alpha <q_c, k_c>) v_c per head
       float dot = 0.f;
 #pragma unroll
       for (int i = 0; i < E; ++i) dot += H::of_word(gr[r].qb[i >> 1], i) * H::of_word(gr[r].kb[i >> 1], i);
