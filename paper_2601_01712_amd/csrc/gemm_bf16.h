@@ -492,7 +492,11 @@ __global__ __launch_bounds__(512, 1) void f1_ws_bf16_kernel(F1Params p) {
         __builtin_amdgcn_wave_barrier();   // LDS serves a wavefront's accesses in order: the reads below see the writes above
 #pragma unroll
         for (int n = 0; n < 4; ++n) {
-          const int tk = (lane >> 3) + 8 * n, fc = lane & 7;
+          const int tk = (lane >> 3) + 8 * n;
+          int fc = lane & 7;
+          // (opaque to the compiler: otherwise it hoists the index arithmetic of the rare suffix-V scatter below out of
+          // the unit loop, 32 values per lane that it then has to spill -- 16 MiB of scratch writes per launch)
+          asm volatile("" : "+v"(fc));
           uint4 val = *reinterpret_cast<const uint4*>(st + tk * 64 + ((fc ^ (tk & 7)) << 3));
           const int row = m0 + i * 32 + tk;
           const int kind = kinds[n];
@@ -776,7 +780,7 @@ template <typename H, int D, int NW, int RB, bool SM, int OCC = 1>
 __global__ __launch_bounds__(NW * 64, OCC) void f2_ln_bf16_kernel(F2LnParams p) {
   constexpr int KS = D / 16;            // k-steps
   constexpr int FB = D / 32 / NW;       // 32-feature blocks per wavefront
-  constexpr int PF = FB >= 4 ? 2 : (OCC == 2 ? 4 : 8);   // k-steps of weight fragments in flight per wavefront
+  constexpr int PF = FB >= 4 ? 2 : (OCC == 2 ? 4 : 8);   // k-steps of weight fragments in flight per wavefront (16 spills: 38 % slower)
   constexpr int ROWS = 32 * RB;         // rows per workgroup: RB blocks of 32 share one pass over W2
   static_assert(FB >= 1 && FB * NW * 32 == D && KS % PF == 0, "shape");
   static_assert(RB * KS * 1024 <= 65536, "token fragments fit static LDS");
