@@ -393,7 +393,7 @@ __global__ __launch_bounds__(NW * 64, (DH >= 128) ? 1 : 512 / (NW * 64)) void at
           const uint32_t qw[4] = {qf[qb][ks].x, qf[qb][ks].y, qf[qb][ks].z, qf[qb][ks].w};
           const uint32_t kw[4] = {kself[qb][ks].x, kself[qb][ks].y, kself[qb][ks].z, kself[qb][ks].w};
 #pragma unroll
-          for (int i = 0; i < 8; ++i) dot += H::of_word(qw[i >> 1], i) * H::of_word(kw[i >> 1], i);
+          for (int i = 0; i < 4; ++i) dot = H::dot2(qw[i], kw[i], dot);
         }
       }
       dot += __shfl_xor(dot, 32, 64);
