@@ -829,8 +829,14 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
           }
           return;
         }
+        if (r1 - r0 <= kF1SmallMaxRows) {       // a few hundred rows: small tiles, deep pipeline
+          fp.n_mtiles = (r1 - r0 + 64 * kF1SmallTM - 1) / (64 * kF1SmallTM);
+          int total = fp.n_mtiles * cm.nblk * (d / (64 * kF1TN));
+          hipLaunchKernelGGL((f1_gemm_bf16_kernel<HT, kF1SmallTM, kF1SmallStages>), dim3((total + 7) / 8 * 8), dim3(256), 0, st, fp);
+          return;
+        }
         int total = fp.n_mtiles * cm.nblk * (d / (64 * kF1TN));
-        hipLaunchKernelGGL(f1_gemm_bf16_kernel<HT>, dim3((total + 7) / 8 * 8), dim3(256), 0, st, fp);
+        hipLaunchKernelGGL((f1_gemm_bf16_kernel<HT, kF1TM, kF1Stages>), dim3((total + 7) / 8 * 8), dim3(256), 0, st, fp);
       }
     };
     if (last && p.n_prows) {

@@ -51,6 +51,7 @@ struct GemmTile {
   static constexpr int LDS_ELEMS = NSTAGE * STAGE;
   static constexpr int LOADS_PER_WAVE = PIECES / 4;
   static_assert(PIECES % 4 == 0, "pieces are dealt evenly to the 4 wavefronts");
+  static_assert(TM == 1 || TM % 2 == 0, "a tile is half a 128-row panel or whole panels");
 };
 
 // FEATURE_MAJOR: features are the MFMA row operand (lane = token column, 4-feature runs per lane).
@@ -68,8 +69,13 @@ __device__ __forceinline__ void gemm_mainloop(const uint16_t* __restrict__ A, co
     for (int p = wave; p < G::PIECES; p += 4) {
       const uint16_t* src;
       if (p < G::TOK_PIECES) {
-        int panel = p >> 3, ksl = (p >> 2) & 1, rb = p & 3;
-        src = A + ((size_t)((m0 >> 7) + panel) * KS + (kt * 2 + ksl)) * 2048 + rb * 512;
+        if constexpr (TM >= 2) {     // whole 128-row panels: pieces ordered [panel][k-step][row block]
+          int panel = p >> 3, ksl = (p >> 2) & 1, rb = p & 3;
+          src = A + ((size_t)((m0 >> 7) + panel) * KS + (kt * 2 + ksl)) * 2048 + rb * 512;
+        } else {                     // a 64-row tile is half a panel (m0 is a multiple of 64): [k-step][row block]
+          int ksl = p >> 1, rb = ((m0 >> 5) & 3) + (p & 1);
+          src = A + ((size_t)(m0 >> 7) * KS + (kt * 2 + ksl)) * 2048 + rb * 512;
+        }
       } else {
         int q = p - G::TOK_PIECES;
         int panel = q >> 3, ksl = (q >> 2) & 1, nb = q & 3;
@@ -111,7 +117,8 @@ __device__ __forceinline__ void gemm_mainloop(const uint16_t* __restrict__ A, co
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         int rbAll = wm * TM + i;   // 32-row block inside the workgroup tile
-        tf[ksl][i] = *reinterpret_cast<const uint4*>(tokp + (((rbAll >> 2) * 2 + ksl) * 4 + (rbAll & 3)) * 512);
+        if constexpr (TM >= 2) tf[ksl][i] = *reinterpret_cast<const uint4*>(tokp + (((rbAll >> 2) * 2 + ksl) * 4 + (rbAll & 3)) * 512);
+        else tf[ksl][i] = *reinterpret_cast<const uint4*>(tokp + (ksl * 2 + rbAll) * 512);
       }
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
@@ -149,12 +156,17 @@ struct F1Params {
 
 constexpr int kF1TM = 4, kF1TN = 2, kF1Stages = 3;   // 256 tokens x 128 features per workgroup
 constexpr int kStageLd = 64 * kF1TN + 8;          // epilogue staging row stride (elements)
+// Launches of a few hundred rows (one user's candidates): the big tile gives the chip a few dozen workgroups, each
+// waiting a memory round trip per k-step with two stages in flight.  The small tile (64 tokens) with eight stages has
+// half of K in flight per workgroup and four times the workgroups.
+constexpr int kF1SmallTM = 1, kF1SmallStages = 8, kF1SmallMaxRows = 4095;
 
-template <typename H>
-__global__ __launch_bounds__(256, 2) void f1_gemm_bf16_kernel(F1Params p) {
-  constexpr int TM = kF1TM, TN = kF1TN;
-  using G = GemmTile<TM, TN, kF1Stages>;
-  constexpr int LDS_ELEMS = (G::LDS_ELEMS > 256 * kStageLd) ? G::LDS_ELEMS : 256 * kStageLd;
+template <typename H, int TM, int NSTAGE>
+__global__ __launch_bounds__(256, TM == 4 ? 2 : 1) void f1_gemm_bf16_kernel(F1Params p) {
+  constexpr int TN = kF1TN;
+  constexpr int ROWS = 64 * TM;                  // tokens per workgroup tile
+  using G = GemmTile<TM, TN, NSTAGE>;
+  constexpr int LDS_ELEMS = (G::LDS_ELEMS > ROWS * kStageLd) ? G::LDS_ELEMS : ROWS * kStageLd;
   __shared__ __attribute__((aligned(16))) uint16_t lds[LDS_ELEMS];
 
   const int ntiles_per_blk = p.cm.d / G::BNf;
@@ -180,7 +192,7 @@ __global__ __launch_bounds__(256, 2) void f1_gemm_bf16_kernel(F1Params p) {
   if (blk == 1 && prefix_tile) {
     // ---- V of prefix rows: token-major product; the accumulator of a 32-token x 32-feature block
     // is, lane for lane, two V-tile fragments (m = 0, 1), stored as 1 KiB contiguous runs.
-    gemm_mainloop<H, TM, TN, kF1Stages, false>(p.A, p.W, d, m0, n0, lds, acc);
+    gemm_mainloop<H, TM, TN, NSTAGE, false>(p.A, p.W, d, m0, n0, lds, acc);
     const int user = p.rt.user[m0];
     const UserDesc ud = p.users[user];
     const int pos0 = p.rt.idx[m0];
@@ -193,7 +205,7 @@ __global__ __launch_bounds__(256, 2) void f1_gemm_bf16_kernel(F1Params p) {
       const float bias = H::to_f32(p.bias[n0 + wn * 64 + j * 32 + l32]);
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
-        const int tok0 = pos0 + wm * 128 + i * 32;          // first token of this 32-token block
+        const int tok0 = pos0 + wm * (32 * TM) + i * 32;    // first token of this 32-token block
         if (tok0 >= Lceil) continue;
         const int kb = (tok0 >> 5) & 1;
         uint16_t* frag = kvb + (int64_t)(tok0 >> 6) * ud.kv_tile_stride + (int64_t)head * 2 * kTile * dh + kTile * dh;
@@ -224,16 +236,17 @@ __global__ __launch_bounds__(256, 2) void f1_gemm_bf16_kernel(F1Params p) {
   // every global store is a 16-byte chunk of 8 consecutive features of one token.
   // In the store phase a thread owns 16-byte chunk (tid & 15) of rows (tid >> 4) + 16*it of the
   // tile; fetch those rows' kinds now, so that the lookups complete under the main loop.
-  int kinds[16];
+  constexpr int ITS = ROWS / 16;                 // 16 rows per pass of the store phase
+  int kinds[ITS];
 #pragma unroll
-  for (int it = 0; it < 16; ++it) {
+  for (int it = 0; it < ITS; ++it) {
     const int row = m0 + (tid >> 4) + 16 * it;
     kinds[it] = row < p.row_end ? p.rt.kind[row] : kRowPad;
   }
   // a prefix tile belongs to one user and holds consecutive prefix positions from pos0 on
   const int tile_user = prefix_tile ? p.rt.user[m0] : 0;
   const int pos0 = prefix_tile ? p.rt.idx[m0] : 0;
-  gemm_mainloop<H, TM, TN, kF1Stages, true>(p.A, p.W, d, m0, n0, lds, acc);
+  gemm_mainloop<H, TM, TN, NSTAGE, true>(p.A, p.W, d, m0, n0, lds, acc);
   const float mul = (blk == 2) ? p.q_mul : 1.0f;
 #pragma unroll
   for (int j = 0; j < TN; ++j)
@@ -245,7 +258,7 @@ __global__ __launch_bounds__(256, 2) void f1_gemm_bf16_kernel(F1Params p) {
       const float b2 = H::to_f32(bb.y & 0xFFFF), b3 = H::to_f32(bb.y >> 16);
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
-        const int t = wm * 128 + i * 32 + l32;
+        const int t = wm * (32 * TM) + i * 32 + l32;
         uint2 w;
         w.x = H::pack2(silu_fast(acc[i][j][4 * e4] + b0) * mul, silu_fast(acc[i][j][4 * e4 + 1] + b1) * mul);
         w.y = H::pack2(silu_fast(acc[i][j][4 * e4 + 2] + b2) * mul, silu_fast(acc[i][j][4 * e4 + 3] + b3) * mul);
@@ -254,9 +267,9 @@ __global__ __launch_bounds__(256, 2) void f1_gemm_bf16_kernel(F1Params p) {
     }
   __syncthreads();
   const UserDesc tud = p.users[tile_user];
-  // 256 tokens x 16 chunks of 8 features
+  // ROWS tokens x 16 chunks of 8 features
 #pragma unroll
-  for (int it = 0; it < 16; ++it) {
+  for (int it = 0; it < ITS; ++it) {
     const int t = (tid >> 4) + 16 * it, fc = tid & 15;
     const int row = m0 + t;
     if (row >= p.row_end) continue;
