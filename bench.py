@@ -37,7 +37,7 @@ LATENCY_CALLS = 500          # rank calls behind every p50 / p99 (whatever --ste
 # HBM bytes per attention launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs), scaled by
 # what the same counters read for a plain 1 GiB copy (x2.0 and x1.0); profiles/bench_C3_kernels.md.  Only the
 # C3 rank launch has been counted; other workloads report null.
-MEASURED_ATTN_TRAFFIC_BYTES = {"C3": (73939 * 2 + 32770) * 1024}
+MEASURED_ATTN_TRAFFIC_BYTES = {"C3": (82149 * 2 + 32768) * 1024}
 
 WORKLOAD_TEXT = {
     "C1": "C1: fp32, 2 layers, d=64, 2 heads; 1 user, prefix 256, 16 candidates",
@@ -187,9 +187,11 @@ class Loaded:
         new_rows = int(S.sum() + M.sum())
         miss_rows = sum(int(L[u]) for u in range(n) if not handles[u])
         attn_flops = [4.0 * d * (key_visits + causal_visits)] * (NL - 1) + [4.0 * d * key_visits]
-        # K,V of every key sequence once; q in (bf16) and the fp32 output sums of the rows attended
-        attn_bytes = [2.0 * (int(L.sum()) + int(S.sum())) * d * e + (new_rows + miss_rows) * d * (e + 4)] * (NL - 1) + \
-                     [2.0 * (int(L.sum()) + int(S.sum())) * d * e + new_rows * d * (e + 4)]
+        # K,V of every key sequence once; q in (bf16) and the fp32 output sums of the rows attended; in the 16-bit SiLU form
+        # the kernel also reads each candidate's own k and v row (the term its sums start from)
+        own_kv = 2.0 * int(M.sum()) * d * e if (e == 2 and cfg.attention == "silu") else 0.0
+        attn_bytes = [2.0 * (int(L.sum()) + int(S.sum())) * d * e + (new_rows + miss_rows) * d * (e + 4) + own_kv] * (NL - 1) + \
+                     [2.0 * (int(L.sum()) + int(S.sum())) * d * e + new_rows * d * (e + 4) + own_kv]
         # projection: 8 d^2 FLOP per row (k, v only for last-layer prefix rows: 4 d^2)
         f1_flops = [8.0 * d * d * (new_rows + miss_rows)] * (NL - 1) + [8.0 * d * d * new_rows + 4.0 * d * d * miss_rows]
         # layer tail: 2 d^2 FLOP per row; o in (fp32), u in, residual row in and out (fp32), next layer's normalised row out
