@@ -617,71 +617,124 @@ __device__ __forceinline__ void ld_bf16_run(const uint16_t* src, uint32_t (&w)[E
   }
 }
 
-// One row of the attention combine + gate, by one wavefront, lane owning features [lane*E, lane*E+E):
-// loads are issued by load_gate_row for several rows before any of them is reduced.
-template <int E>
+// One row of the attention combine + gate, by one wavefront, lane owning features [lane*E, lane*E+E).
+// SELF: the row's own q, k, v are wanted (softmax form: the candidate's own key is merged here; in the
+// SiLU form the attention kernel has it in its sums already).
+template <int E, bool SELF>
 struct GateRow {
   float o[E];
-  uint32_t ub[E / 2], qb[E / 2], kb[E / 2], vb[E / 2];
+  uint32_t ub[E / 2], qb[SELF ? E / 2 : 1], kb[SELF ? E / 2 : 1], vb[SELF ? E / 2 : 1];
   int n, kind;
   float mpart, lpart;   // softmax form: reference score of o and the matching sum of weights
 };
 
-template <int D, bool SM>
-__device__ __forceinline__ void load_gate_row(const F2LnParams& p, int row, bool ok, int lane, GateRow<D / 64>& gr) {
-  constexpr int E = D / 64;
-  // nothing here waits for the row's kind: every load of the row is issued at once
-  gr.kind = ok ? p.rt.kind[row] : kRowPad;
-  gr.n = ok ? p.rt.lim[row] : 1;
+template <int E>
+__device__ __forceinline__ void ld_f32_run(const float* src, float (&v)[E]) {
+  if constexpr (E == 2) {
+    const float2 t = *reinterpret_cast<const float2*>(src);
+    v[0] = t.x; v[1] = t.y;
+  } else {
 #pragma unroll
-  for (int i = 0; i < E; ++i) gr.o[i] = 0.f;
-#pragma unroll
-  for (int i = 0; i < E / 2; ++i) gr.ub[i] = gr.qb[i] = gr.kb[i] = gr.vb[i] = 0u;
-  gr.mpart = 0.f; gr.lpart = 1.f;
-  if (!ok) return;
-  const size_t base = (size_t)row * D + lane * E;
-  // softmax form: split s counts with weight 2^(m_s - M), M the largest m_s of this lane's head
-  const float* mlr = nullptr;
-  float M = 0.f;
-  gr.lpart = 0.f;
-  if constexpr (SM) {
-    mlr = p.ml + ((size_t)row * p.n_heads + lane * E / p.dh) * 2;
-    M = -INFINITY;
-    for (int s = 0; s < p.nsplit; ++s) M = fmaxf(M, mlr[s * p.ml_stride]);
-  }
-  gr.mpart = M;
-  for (int s = 0; s < p.nsplit; ++s) {
-    const float* src = p.part + s * p.split_stride + base;
-    float w = 1.0f;
-    if constexpr (SM) {
-      const float2 v = *reinterpret_cast<const float2*>(mlr + s * p.ml_stride);
-      w = (v.x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(v.x - M);
-      gr.lpart += w * v.y;
+    for (int c = 0; c < E / 4; ++c) {
+      const float4 t = *reinterpret_cast<const float4*>(src + 4 * c);
+      v[4 * c] = t.x; v[4 * c + 1] = t.y; v[4 * c + 2] = t.z; v[4 * c + 3] = t.w;
     }
-    if constexpr (E == 2) {
-      const float2 v = *reinterpret_cast<const float2*>(src);
-      gr.o[0] += w * v.x; gr.o[1] += w * v.y;
-    } else {
-#pragma unroll
-      for (int c = 0; c < E / 4; ++c) {
-        const float4 v = *reinterpret_cast<const float4*>(src + 4 * c);
-        gr.o[4 * c] += w * v.x; gr.o[4 * c + 1] += w * v.y; gr.o[4 * c + 2] += w * v.z; gr.o[4 * c + 3] += w * v.w;
-      }
-    }
-  }
-  ld_bf16_run<E>(p.u + base, gr.ub);
-  if (row >= p.n_prows && p.q != nullptr) {   // suffix and candidate rows have row-major q, k, v (only candidates use them)
-    const size_t nb = (size_t)(row - p.n_prows) * D + lane * E;
-    ld_bf16_run<E>(p.q + base, gr.qb);
-    ld_bf16_run<E>(p.knew + nb, gr.kb);
-    ld_bf16_run<E>(p.vnew + nb, gr.vb);
   }
 }
+
+// The key-split partial sums of G rows, summed in split order.  The loads of one split (all G rows) are in
+// flight while the split before it is added, two splits at a time: a call with 8 key splits waits for about
+// five round trips to memory per group of rows, not for one per row and split.  begin() issues the rows'
+// other inputs and the first split; the caller may issue further loads before finish() walks the splits.
+// Rows beyond the launch read the workgroup's first row instead and are marked as filler.
+template <int D, bool SM, int G>
+struct GateLoad {
+  static constexpr int E = D / 64;
+  size_t base[G];
+  const float* mlr[G];
+  float M[G];
+  float bufA[G][E];
+  float2 mlA[G];
+
+  __device__ __forceinline__ void issue(const F2LnParams& p, int sp, float (&buf)[G][E], float2 (&mlb)[G]) {
+#pragma unroll
+    for (int r = 0; r < G; ++r) {
+      ld_f32_run<E>(p.part + sp * p.split_stride + base[r], buf[r]);
+      if constexpr (SM) mlb[r] = *reinterpret_cast<const float2*>(mlr[r] + sp * p.ml_stride);
+    }
+  }
+  __device__ __forceinline__ void add(GateRow<E, SM> (&gr)[G], const float (&buf)[G][E], const float2 (&mlb)[G]) {
+#pragma unroll
+    for (int r = 0; r < G; ++r) {
+      float w = 1.0f;
+      if constexpr (SM) {
+        w = (mlb[r].x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mlb[r].x - M[r]);
+        gr[r].lpart += w * mlb[r].y;
+      }
+#pragma unroll
+      for (int i = 0; i < E; ++i) gr[r].o[i] += w * buf[r][i];
+    }
+  }
+  __device__ __forceinline__ void begin(const F2LnParams& p, int row_first, int row_safe, int lane, GateRow<E, SM> (&gr)[G]) {
+#pragma unroll
+    for (int r = 0; r < G; ++r) {
+      const bool ok = row_first + r < p.row_end;
+      const int row = ok ? row_first + r : row_safe;
+      const int kind = p.rt.kind[row];
+      gr[r].kind = ok ? kind : kRowPad;
+      gr[r].n = p.rt.lim[row];
+      base[r] = (size_t)row * D + lane * E;
+      ld_bf16_run<E>(p.u + base[r], gr[r].ub);
+      mlr[r] = nullptr;
+      M[r] = 0.f;
+      if constexpr (SM) {
+#pragma unroll
+        for (int i = 0; i < E / 2; ++i) gr[r].qb[i] = gr[r].kb[i] = gr[r].vb[i] = 0u;
+        if (row >= p.n_prows) {   // suffix and candidate rows have row-major q, k, v (only candidates use them)
+          const size_t nb = (size_t)(row - p.n_prows) * D + lane * E;
+          ld_bf16_run<E>(p.q + base[r], gr[r].qb);
+          ld_bf16_run<E>(p.knew + nb, gr[r].kb);
+          ld_bf16_run<E>(p.vnew + nb, gr[r].vb);
+        }
+        // split s counts with weight 2^(m_s - M), M the largest m_s of this lane's head
+        mlr[r] = p.ml + ((size_t)row * p.n_heads + lane * E / p.dh) * 2;
+        float m = -INFINITY;
+#pragma unroll
+        for (int sp = 0; sp < 8; ++sp) m = fmaxf(m, mlr[r][(size_t)min(sp, p.nsplit - 1) * p.ml_stride]);   // at most 8 key splits
+        M[r] = m;
+      }
+      gr[r].mpart = M[r];
+      gr[r].lpart = SM ? 0.f : 1.f;
+#pragma unroll
+      for (int i = 0; i < E; ++i) gr[r].o[i] = 0.f;
+    }
+    issue(p, 0, bufA, mlA);
+  }
+  __device__ __forceinline__ void finish(const F2LnParams& p, GateRow<E, SM> (&gr)[G]) {
+    if constexpr (E >= 16) {   // d = 1024: a second buffer would not fit the registers; one split (all rows) at a time
+      for (int sp = 0; sp < p.nsplit; ++sp) {
+        add(gr, bufA, mlA);
+        if (sp + 1 < p.nsplit) issue(p, sp + 1, bufA, mlA);
+      }
+      return;
+    }
+    float bufB[G][E];
+    float2 mlB[G];
+    int sp = 0;
+    for (; sp + 1 < p.nsplit; sp += 2) {
+      issue(p, sp + 1, bufB, mlB);
+      add(gr, bufA, mlA);
+      if (sp + 2 < p.nsplit) issue(p, sp + 2, bufA, mlA);
+      add(gr, bufB, mlB);
+    }
+    if (sp < p.nsplit) add(gr, bufA, mlA);
+  }
+};
 
 // Finishes G rows at once (their reductions interleave) and writes y (bf16) into the token
 // fragments: local row lr0 + i of the workgroup goes to row block (lr0+i)/32, row (lr0+i)%32.
 template <typename H, int D, int G, bool SM, int FRAG>
-__device__ __forceinline__ void finish_gate_rows(const F2LnParams& p, GateRow<D / 64> (&gr)[G], int lane, uint16_t* tok, int lr0,
+__device__ __forceinline__ void finish_gate_rows(const F2LnParams& p, GateRow<D / 64, SM> (&gr)[G], int lane, uint16_t* tok, int lr0,
                                                  const uint32_t (&gw)[D / 128], const uint32_t (&ow)[D / 128]) {
   constexpr int E = D / 64, KS = D / 16;
   float s[G], inv_n[G];
@@ -689,9 +742,9 @@ __device__ __forceinline__ void finish_gate_rows(const F2LnParams& p, GateRow<D 
   for (int r = 0; r < G; ++r) {
     int n = gr[r].n;
     float lsum = gr[r].lpart;
-    if (gr[r].kind == kRowCand && p.q == nullptr) {
-      n += 1;                          // the own key is in the sums already; it counts as a visible key
-    } else if (gr[r].kind == kRowCand) {      // the candidate's own key: SiLU(alpha <q_c, k_c>) v_c per head
+    if constexpr (!SM) {
+      if (gr[r].kind == kRowCand) n += 1;   // the own key is in the attention kernel's sums already; it counts as a visible key
+    } else if (gr[r].kind == kRowCand) {      // the candidate's own key, per head
       float dot = 0.f;
 #pragma unroll
       for (int i = 0; i < E; ++i) dot += H::of_word(gr[r].qb[i >> 1], i) * H::of_word(gr[r].kb[i >> 1], i);
@@ -703,21 +756,14 @@ __device__ __forceinline__ void finish_gate_rows(const F2LnParams& p, GateRow<D 
       else if (hl == 16) dot = lanes16_sum(dot);
       else if (hl == 32) dot = lanes32_sum(dot);
       else if (hl == 64) dot = wave_sum_dpp(dot);
-      if constexpr (SM) {
-        // softmax form: the stored q carries alpha * log2(e), so dot is the own key's score in the units
-        // of m; bring the merged splits and the own key to their common maximum
-        const float Mn = fmaxf(gr[r].mpart, dot);
-        const float c = (gr[r].mpart == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(gr[r].mpart - Mn);
-        const float ws = __builtin_amdgcn_exp2f(dot - Mn);
+      // the stored q carries alpha * log2(e), so dot is the own key's score in the units of m; bring the
+      // merged splits and the own key to their common maximum
+      const float Mn = fmaxf(gr[r].mpart, dot);
+      const float c = (gr[r].mpart == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(gr[r].mpart - Mn);
+      const float ws = __builtin_amdgcn_exp2f(dot - Mn);
 #pragma unroll
-        for (int i = 0; i < E; ++i) gr[r].o[i] = gr[r].o[i] * c + ws * H::of_word(gr[r].vb[i >> 1], i);
-        lsum = lsum * c + ws;
-      } else {
-        const float pself = silu_f32(dot * p.qk_mul);
-#pragma unroll
-        for (int i = 0; i < E; ++i) gr[r].o[i] += pself * H::of_word(gr[r].vb[i >> 1], i);
-        n += 1;
-      }
+      for (int i = 0; i < E; ++i) gr[r].o[i] = gr[r].o[i] * c + ws * H::of_word(gr[r].vb[i >> 1], i);
+      lsum = lsum * c + ws;
     }
     inv_n[r] = SM ? 1.0f / (lsum > 0.f ? lsum : 1.0f) : 1.0f / (float)(n > 0 ? n : 1);
     s[r] = 0.f;
@@ -770,19 +816,17 @@ __device__ __forceinline__ void finish_gate_rows(const F2LnParams& p, GateRow<D 
 // kernel, whose W2 stream waits on latency; the same warm-up made the f1 GEMM 9 % slower -- its
 // operand stream is bound by L2 -> LDS bandwidth, not latency -- and is not used there.)
 // Touches lines [share * per, share * per + per) of `lines` lines, per = lines / n_shares, at most
-// MAXLD loads per thread; returns a word that depends on them (to be consumed by a never-taken
-// branch once the loads are known to have landed).
+// MAXLD loads per thread, all issued at once (a thread with fewer lines to touch repeats its last one);
+// v receives the words (to be consumed by a never-taken branch once the loads are known to have landed).
 template <int MAXLD>
-__device__ __forceinline__ int l2_touch(const void* base, int lines, int share, int n_shares, int tid, int n_threads) {
+__device__ __forceinline__ void l2_touch(const void* base, int lines, int share, int n_shares, int tid, int n_threads, int (&v)[MAXLD]) {
   const int per = lines / n_shares;
   const char* b = reinterpret_cast<const char*>(base) + (size_t)share * per * 128;
-  int acc = 0;
 #pragma unroll
   for (int u = 0; u < MAXLD; ++u) {
-    const int i = tid + u * n_threads;
-    if (i < per) acc ^= *reinterpret_cast<const int*>(b + (size_t)i * 128);
+    const int i = min(tid + u * n_threads, per - 1);
+    v[u] = (u == 0 || (u * n_threads < per)) ? *reinterpret_cast<const int*>(b + (size_t)i * 128) : 0;
   }
-  return acc;
 }
 
 // OCC = 2: built to fit two workgroups on a compute unit (128 registers per lane), so that one's gate
@@ -809,15 +853,12 @@ __global__ __launch_bounds__(NW * 64, OCC) void f2_ln_bf16_kernel(F2LnParams p) 
   // The gate makes the tokens: each wavefront takes ROWS/NW rows, a few at a time
   // so that their loads are in flight together.  The first group's loads go out before anything
   // else, since they are what the workgroup needs first.
-  constexpr int RPW = ROWS / NW, GMAX = OCC == 2 ? 2 : (RB * FB >= 4 ? (D >= 1024 ? 1 : 2) : 4), GROUP = RPW < GMAX ? RPW : GMAX;
+  constexpr int RPW = ROWS / NW, GMAX = OCC == 2 ? 2 : (RB * FB >= 4 ? (D >= 1024 ? 1 : 2) : (SM ? 2 : 4)), GROUP = RPW < GMAX ? RPW : GMAX;
   static_assert(RPW >= 1 && RPW % GROUP == 0, "rows per wavefront");
-  GateRow<D / 64> gr[GROUP];
+  GateRow<D / 64, SM> gr[GROUP];
   uint32_t gw[D / 128], ow[D / 128];
-#pragma unroll
-  for (int i = 0; i < GROUP; ++i) {
-    const int lr = wave * RPW + i;
-    load_gate_row<D, SM>(p, row0 + lr, row0 + lr < p.row_end, lane, gr[i]);
-  }
+  GateLoad<D, SM, GROUP> gl;
+  gl.begin(p, row0 + wave * RPW, row0, lane, gr);
   ld_bf16_run<D / 64>(p.gate_gain + lane * (D / 64), gw);
   ld_bf16_run<D / 64>(p.gate_offs + lane * (D / 64), ow);
 
@@ -825,7 +866,8 @@ __global__ __launch_bounds__(NW * 64, OCC) void f2_ln_bf16_kernel(F2LnParams p) 
   // eighth one) each ask for a slice now, so that the product phase below finds W2 in L2
   const int wgs_per_xcd = (int)gridDim.x >> 3;
   const int n_slices = wgs_per_xcd < 1 ? 1 : (wgs_per_xcd < 16 ? wgs_per_xcd : 16);
-  const int touched = l2_touch<4>(p.W, D * D / 64, ((int)blockIdx.x >> 3) % n_slices, n_slices, (int)threadIdx.x, NW * 64);
+  int touched[4];
+  l2_touch<4>(p.W, D * D / 64, ((int)blockIdx.x >> 3) % n_slices, n_slices, (int)threadIdx.x, NW * 64, touched);
 
   // this wavefront's weight fragments: feature block fb lives in panel fb/4, row block fb%4
   const uint16_t* wbase[FB];
@@ -849,7 +891,6 @@ __global__ __launch_bounds__(NW * 64, OCC) void f2_ln_bf16_kernel(F2LnParams p) 
 #pragma unroll
       for (int j = 0; j < FB; ++j) wf[i][j] = *reinterpret_cast<const uint4*>(wbase[j] + (size_t)((i + rot) & (KS - 1)) * 2048);
   };
-  if constexpr (OCC == 1) prefetch_w();
   // The accumulators start from the residual row plus the bias, fetched now so that the gate and
   // the product hide the latency (the row's kind is only needed when results are stored): element
   // e of acc[b][j] is feature (wave*FB + j)*32 + 8*(e/4) + 4*g + e%4 of token row0 + 32*b + l32.
@@ -878,24 +919,23 @@ __global__ __launch_bounds__(NW * 64, OCC) void f2_ln_bf16_kernel(F2LnParams p) 
         }
     }
   };
-  if constexpr (OCC == 1) init_acc();
 
-  // now that everything else is in flight behind them, the first rows are reduced and written as
-  // token fragments; further groups of rows follow
+  // now that everything else is in flight behind their first loads, the first rows are reduced and
+  // written as token fragments; further groups of rows follow
+  gl.finish(p, gr);
+  constexpr bool EARLY_W = OCC == 1 && !SM && D < 1024;      // elsewhere the registers do not allow it
+  if constexpr (EARLY_W) { prefetch_w(); init_acc(); }      // in flight while the rows are normalised and written to LDS
   finish_gate_rows<H, D, GROUP, SM, FRAG>(p, gr, lane, tok, wave * RPW, gw, ow);
 #pragma unroll
   for (int r0 = GROUP; r0 < RPW; r0 += GROUP) {
-#pragma unroll
-    for (int i = 0; i < GROUP; ++i) {
-      const int lr = wave * RPW + r0 + i;
-      load_gate_row<D, SM>(p, row0 + lr, row0 + lr < p.row_end, lane, gr[i]);
-    }
+    gl.begin(p, row0 + wave * RPW + r0, row0, lane, gr);
+    gl.finish(p, gr);
     finish_gate_rows<H, D, GROUP, SM, FRAG>(p, gr, lane, tok, wave * RPW + r0, gw, ow);
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-  if (touched == 0x5a17c0de && p.eps < 0.f) red[0] = 0.f;   // never taken: keeps the warm-up loads
-  if constexpr (OCC == 2) { prefetch_w(); init_acc(); }
+  if ((touched[0] ^ touched[1] ^ touched[2] ^ touched[3]) == 0x5a17c0de && p.eps < 0.f) red[0] = 0.f;   // never taken: keeps the warm-up loads
+  if constexpr (!EARLY_W) { prefetch_w(); init_acc(); }
 
   for (int ks0 = 0; ks0 < KS; ks0 += PF) {
 #pragma unroll
