@@ -329,6 +329,7 @@ __global__ __launch_bounds__(256, TM == 4 ? 2 : 1) void f1_gemm_bf16_kernel(F1Pa
 constexpr int kF1WsPF = 4;          // k-steps of token fragments in flight per wavefront
 constexpr int kF1WsMinRows = 4096;  // below this the tiled kernel's many small workgroups fill the chip better
 constexpr int kF1StreamMinRows = 16384;   // from here on a launch writes 64 MiB and more (at d = 512): streaming stores
+constexpr int kTailVr8MaxRows = 1024;  // layer tail: launches of at most this many rows use 8-row workgroups (d = 256, 512)
 
 template <typename H, int D, bool FEATURE_MAJOR>
 __device__ __forceinline__ void f1_ws_mainloop(const uint16_t* __restrict__ tp0, const uint16_t* __restrict__ tp1,
@@ -642,37 +643,45 @@ __device__ __forceinline__ void ld_f32_run(const float* src, float (&v)[E]) {
   }
 }
 
-// The key-split partial sums of G rows, summed in split order.  The loads of one split (all G rows) are in
-// flight while the split before it is added, two splits at a time: a call with 8 key splits waits for about
-// five round trips to memory per group of rows, not for one per row and split.  begin() issues the rows'
-// other inputs and the first split; the caller may issue further loads before finish() walks the splits.
+// The key-split partial sums of G rows, summed in split order, NB splits (all G rows each) in flight at a
+// time: a call with 8 key splits waits for 8 / NB round trips to memory per group of rows, not for one per
+// row and split.  begin() issues the rows' other inputs and the first NB splits; the caller may issue further
+// loads before finish() adds them up and walks the remaining splits.
 // Rows beyond the launch read the workgroup's first row instead and are marked as filler.
-template <int D, bool SM, int G>
+template <int D, bool SM, int G, int NB>
 struct GateLoad {
   static constexpr int E = D / 64;
   size_t base[G];
   const float* mlr[G];
   float M[G];
-  float bufA[G][E];
-  float2 mlA[G];
+  float buf[NB][G][E];
+  float2 mlb[NB][G];
 
-  __device__ __forceinline__ void issue(const F2LnParams& p, int sp, float (&buf)[G][E], float2 (&mlb)[G]) {
+  __device__ __forceinline__ void issue(const F2LnParams& p, int sp0) {
 #pragma unroll
-    for (int r = 0; r < G; ++r) {
-      ld_f32_run<E>(p.part + sp * p.split_stride + base[r], buf[r]);
-      if constexpr (SM) mlb[r] = *reinterpret_cast<const float2*>(mlr[r] + sp * p.ml_stride);
+    for (int k = 0; k < NB; ++k) {
+      if (sp0 + k >= p.nsplit) break;      // uniform
+#pragma unroll
+      for (int r = 0; r < G; ++r) {
+        ld_f32_run<E>(p.part + (sp0 + k) * p.split_stride + base[r], buf[k][r]);
+        if constexpr (SM) mlb[k][r] = *reinterpret_cast<const float2*>(mlr[r] + (sp0 + k) * p.ml_stride);
+      }
     }
   }
-  __device__ __forceinline__ void add(GateRow<E, SM> (&gr)[G], const float (&buf)[G][E], const float2 (&mlb)[G]) {
+  __device__ __forceinline__ void add(const F2LnParams& p, int sp0, GateRow<E, SM> (&gr)[G]) {
 #pragma unroll
-    for (int r = 0; r < G; ++r) {
-      float w = 1.0f;
-      if constexpr (SM) {
-        w = (mlb[r].x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mlb[r].x - M[r]);
-        gr[r].lpart += w * mlb[r].y;
+    for (int k = 0; k < NB; ++k) {
+      if (sp0 + k >= p.nsplit) break;
+#pragma unroll
+      for (int r = 0; r < G; ++r) {
+        float w = 1.0f;
+        if constexpr (SM) {
+          w = (mlb[k][r].x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mlb[k][r].x - M[r]);
+          gr[r].lpart += w * mlb[k][r].y;
+        }
+#pragma unroll
+        for (int i = 0; i < E; ++i) gr[r].o[i] += w * buf[k][r][i];
       }
-#pragma unroll
-      for (int i = 0; i < E; ++i) gr[r].o[i] += w * buf[r][i];
     }
   }
   __device__ __forceinline__ void begin(const F2LnParams& p, int row_first, int row_safe, int lane, GateRow<E, SM> (&gr)[G]) {
@@ -708,26 +717,14 @@ struct GateLoad {
 #pragma unroll
       for (int i = 0; i < E; ++i) gr[r].o[i] = 0.f;
     }
-    issue(p, 0, bufA, mlA);
+    issue(p, 0);
   }
   __device__ __forceinline__ void finish(const F2LnParams& p, GateRow<E, SM> (&gr)[G]) {
-    if constexpr (E >= 16) {   // d = 1024: a second buffer would not fit the registers; one split (all rows) at a time
-      for (int sp = 0; sp < p.nsplit; ++sp) {
-        add(gr, bufA, mlA);
-        if (sp + 1 < p.nsplit) issue(p, sp + 1, bufA, mlA);
-      }
-      return;
+    add(p, 0, gr);
+    for (int sp0 = NB; sp0 < p.nsplit; sp0 += NB) {
+      issue(p, sp0);
+      add(p, sp0, gr);
     }
-    float bufB[G][E];
-    float2 mlB[G];
-    int sp = 0;
-    for (; sp + 1 < p.nsplit; sp += 2) {
-      issue(p, sp + 1, bufB, mlB);
-      add(gr, bufA, mlA);
-      if (sp + 2 < p.nsplit) issue(p, sp + 2, bufA, mlA);
-      add(gr, bufB, mlB);
-    }
-    if (sp < p.nsplit) add(gr, bufA, mlA);
   }
 };
 
@@ -833,7 +830,10 @@ __device__ __forceinline__ void l2_touch(const void* base, int lines, int share,
 // phase (memory) overlaps the other's product phase (L2 and matrix cores) when a launch has several
 // workgroups per unit: fewer k-steps and gate rows in flight, and the weight fragments and the
 // residual rows are requested after the gate instead of before it.
-template <typename H, int D, int NW, int RB, bool SM, int OCC = 1>
+// VR < 32: a workgroup takes only VR rows (a quarter-filled row block).  For launches of a few hundred
+// rows (one user per call): with 32 rows each they would occupy a few dozen compute units, each pulling
+// 16 KiB of split partial sums per row through its own memory path; with VR = 8 four times as many units share that.
+template <typename H, int D, int NW, int RB, bool SM, int OCC = 1, int VR = 32>
 __global__ __launch_bounds__(NW * 64, OCC) void f2_ln_bf16_kernel(F2LnParams p) {
   constexpr int KS = D / 16;            // k-steps
   constexpr int FB = D / 32 / NW;       // 32-feature blocks per wavefront
@@ -846,18 +846,22 @@ __global__ __launch_bounds__(NW * 64, OCC) void f2_ln_bf16_kernel(F2LnParams p) 
   constexpr int FRAG = 512 + (RB == 1 ? 8 : 0);   // elements between token fragments
   __shared__ __attribute__((aligned(16))) uint16_t tok[RB * KS * FRAG];   // ROWS tokens x D, fragment order
   float* red = reinterpret_cast<float*>(tok);                             // reused after the product: [2][NW][ROWS]
-  const int row0 = p.row_begin + blockIdx.x * ROWS;
+  static_assert(VR == 32 || (RB == 1 && OCC == 1 && VR == NW), "quarter-filled row blocks: one row per wavefront");
+  constexpr int VROWS = VR < 32 ? VR : ROWS;   // rows this workgroup really has
+  const int row0 = p.row_begin + blockIdx.x * VROWS;
   if (row0 >= p.row_end) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, g = lane >> 5;
 
   // The gate makes the tokens: each wavefront takes ROWS/NW rows, a few at a time
   // so that their loads are in flight together.  The first group's loads go out before anything
   // else, since they are what the workgroup needs first.
-  constexpr int RPW = ROWS / NW, GMAX = OCC == 2 ? 2 : (RB * FB >= 4 ? (D >= 1024 ? 1 : 2) : (SM ? 2 : 4)), GROUP = RPW < GMAX ? RPW : GMAX;
+  constexpr int RPW = VROWS / NW, GMAX = OCC == 2 ? 2 : (RB * FB >= 4 ? (D >= 1024 ? 1 : 2) : (SM ? 2 : 4)), GROUP = RPW < GMAX ? RPW : GMAX;
   static_assert(RPW >= 1 && RPW % GROUP == 0, "rows per wavefront");
+  // splits in flight per group of rows: what the registers allow (all 8 when a wavefront has one row)
+  constexpr int NB = VR < 32 ? (D >= 1024 ? 4 : 8) : (D >= 1024 ? 1 : 2);
   GateRow<D / 64, SM> gr[GROUP];
   uint32_t gw[D / 128], ow[D / 128];
-  GateLoad<D, SM, GROUP> gl;
+  GateLoad<D, SM, GROUP, NB> gl;
   gl.begin(p, row0 + wave * RPW, row0, lane, gr);
   ld_bf16_run<D / 64>(p.gate_gain + lane * (D / 64), gw);
   ld_bf16_run<D / 64>(p.gate_offs + lane * (D / 64), ow);
@@ -902,7 +906,7 @@ __global__ __launch_bounds__(NW * 64, OCC) void f2_ln_bf16_kernel(F2LnParams p) 
 #pragma unroll
     for (int b = 0; b < RB; ++b) {
       const int row = row0 + 32 * b + l32;
-      in_range[b] = row < p.row_end;
+      in_range[b] = row < p.row_end && 32 * b + l32 < VROWS;
       kind_ep[b] = p.rt.kind[in_range[b] ? row : row0];
       xrow[b] = p.x + (size_t)(in_range[b] ? row : row0) * D;
 #pragma unroll
@@ -920,11 +924,13 @@ __global__ __launch_bounds__(NW * 64, OCC) void f2_ln_bf16_kernel(F2LnParams p) 
     }
   };
 
-  // now that everything else is in flight behind their first loads, the first rows are reduced and
-  // written as token fragments; further groups of rows follow
-  gl.finish(p, gr);
+  // The residual rows are requested now, behind the rows' first loads; the weight fragments once the
+  // split buffers are free; then the first rows are reduced and written as token fragments, and
+  // further groups of rows follow.
   constexpr bool EARLY_W = OCC == 1 && !SM && D < 1024;      // elsewhere the registers do not allow it
-  if constexpr (EARLY_W) { prefetch_w(); init_acc(); }      // in flight while the rows are normalised and written to LDS
+  if constexpr (EARLY_W) init_acc();
+  gl.finish(p, gr);
+  if constexpr (EARLY_W) prefetch_w();                       // in flight while the rows are normalised and written to LDS
   finish_gate_rows<H, D, GROUP, SM, FRAG>(p, gr, lane, tok, wave * RPW, gw, ow);
 #pragma unroll
   for (int r0 = GROUP; r0 < RPW; r0 += GROUP) {
@@ -937,6 +943,20 @@ __global__ __launch_bounds__(NW * 64, OCC) void f2_ln_bf16_kernel(F2LnParams p) 
   if ((touched[0] ^ touched[1] ^ touched[2] ^ touched[3]) == 0x5a17c0de && p.eps < 0.f) red[0] = 0.f;   // never taken: keeps the warm-up loads
   if constexpr (!EARLY_W) { prefetch_w(); init_acc(); }
 
+  // gain and offset of the LayerNorm that follows the product: requested now where the registers allow it,
+  // so that the output pass does not wait for them
+  constexpr bool EARLY_LN = OCC == 1 && FB <= 2;
+  uint2 lng[FB][4], lno[FB][4];
+  if constexpr (EARLY_LN) {
+#pragma unroll
+    for (int j = 0; j < FB; ++j)
+#pragma unroll
+      for (int e4 = 0; e4 < 4; ++e4) {
+        const int c = (wave * FB + j) * 32 + 8 * e4 + 4 * g;
+        lng[j][e4] = *reinterpret_cast<const uint2*>(p.gain + c);
+        lno[j][e4] = *reinterpret_cast<const uint2*>(p.offs + c);
+      }
+  }
   for (int ks0 = 0; ks0 < KS; ks0 += PF) {
 #pragma unroll
     for (int i = 0; i < PF; ++i) {
@@ -1012,7 +1032,8 @@ __global__ __launch_bounds__(NW * 64, OCC) void f2_ln_bf16_kernel(F2LnParams p) 
 #pragma unroll
         for (int e4 = 0; e4 < 4; ++e4) {
           const int c = (wave * FB + j) * 32 + 8 * e4 + 4 * g;
-          const uint2 gg = *reinterpret_cast<const uint2*>(p.gain + c), oo = *reinterpret_cast<const uint2*>(p.offs + c);
+          const uint2 gg = EARLY_LN ? lng[j][e4] : *reinterpret_cast<const uint2*>(p.gain + c);
+          const uint2 oo = EARLY_LN ? lno[j][e4] : *reinterpret_cast<const uint2*>(p.offs + c);
           const uint2 ww = *reinterpret_cast<const uint2*>(p.w_score + c);
           sc += ((acc[b][j][4 * e4] - mean[b]) * rstd * H::to_f32(gg.x & 0xFFFF) + H::to_f32(oo.x & 0xFFFF)) * H::to_f32(ww.x & 0xFFFF);
           sc += ((acc[b][j][4 * e4 + 1] - mean[b]) * rstd * H::to_f32(gg.x >> 16) + H::to_f32(oo.x >> 16)) * H::to_f32(ww.x >> 16);
@@ -1029,7 +1050,8 @@ __global__ __launch_bounds__(NW * 64, OCC) void f2_ln_bf16_kernel(F2LnParams p) 
 #pragma unroll
       for (int e4 = 0; e4 < 4; ++e4) {
         const int c = (wave * FB + j) * 32 + 8 * e4 + 4 * g;
-        const uint2 gg = *reinterpret_cast<const uint2*>(p.gain + c), oo = *reinterpret_cast<const uint2*>(p.offs + c);
+        const uint2 gg = EARLY_LN ? lng[j][e4] : *reinterpret_cast<const uint2*>(p.gain + c);
+        const uint2 oo = EARLY_LN ? lno[j][e4] : *reinterpret_cast<const uint2*>(p.offs + c);
         float z0 = (acc[b][j][4 * e4] - mean[b]) * rstd * H::to_f32(gg.x & 0xFFFF) + H::to_f32(oo.x & 0xFFFF);
         float z1 = (acc[b][j][4 * e4 + 1] - mean[b]) * rstd * H::to_f32(gg.x >> 16) + H::to_f32(oo.x >> 16);
         float z2 = (acc[b][j][4 * e4 + 2] - mean[b]) * rstd * H::to_f32(gg.y & 0xFFFF) + H::to_f32(oo.y & 0xFFFF);
