@@ -106,6 +106,17 @@ def test_launches_of_thousands_of_rows_take_the_weight_stationary_projection(dty
                      page_tokens=128, miss=(1,), boost=boost)
 
 
+@pytest.mark.parametrize("attention", ["silu", "softmax"])
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+@pytest.mark.parametrize("d,H,boost", [(256, 4, BOOST), (512, 8, None)])
+def test_one_user_calls_take_the_eight_row_layer_tail(dtype, attention, d, H, boost):
+    """One user per call: the key range is cut into 8 splits, and the layer tail of a launch of at most 1024
+    rows runs with 8 rows per workgroup, every split of a row in flight at once; 342 new rows end inside an
+    8-row group.  The full-recompute route of the same user (1442 rows) takes the 32-row tail."""
+    cfg = synth.ModelConfig(2, d, H, dtype, attention=attention)
+    run_three_routes(cfg, 810 + d, [1100], [9], [333], boost=boost)
+
+
 # ------------------------------------------------------------------------------------ fp16
 @pytest.mark.parametrize("L,S,M", [
     ([1], [0], [1]), ([65, 300], [0, 70], [3, 129]), ([513, 0, 128], [64, 2, 0], [257, 9, 1]), ([1000], [17], [400]),
