@@ -919,7 +919,8 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
           // a few hundred rows (one user per call): 8 rows per workgroup, so that four times as many
           // compute units share the split partial sums
           const bool vr8 = (d == 256 || d == 512) && rows <= kTailVr8MaxRows;
-          dim3 grid(vr8 ? (rows + 7) / 8 : (rows + (rb2 ? 63 : 31)) / (rb2 ? 64 : 32));
+          const bool vr16 = (d == 256 || d == 512) && !vr8 && rows <= kTailVr16MaxRows;
+          dim3 grid(vr8 ? (rows + 7) / 8 : vr16 ? (rows + 15) / 16 : (rows + (rb2 ? 63 : 31)) / (rb2 ? 64 : 32));
           auto launch_tail = [&](auto sm) {
             constexpr bool SM = decltype(sm)::value;
             switch (d) {
@@ -930,11 +931,13 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
               case 256:
                 if (rb2) hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 256, 8, 2, SM>), grid, dim3(512), 0, st, fp);
                 else if (vr8) hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 256, 8, 1, SM, 1, 8>), grid, dim3(512), 0, st, fp);
+                else if (vr16) hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 256, 8, 1, SM, 1, 16>), grid, dim3(512), 0, st, fp);
                 else hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 256, 8, 1, SM>), grid, dim3(512), 0, st, fp);
                 break;
               case 512:
                 if (rb2) hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 512, 8, 2, SM, 2>), grid, dim3(512), 0, st, fp);
                 else if (vr8) hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 512, 8, 1, SM, 1, 8>), grid, dim3(512), 0, st, fp);
+                else if (vr16) hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 512, 8, 1, SM, 1, 16>), grid, dim3(512), 0, st, fp);
                 else hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 512, 8, 1, SM>), grid, dim3(512), 0, st, fp);
                 break;
               default: hipLaunchKernelGGL((f2_ln_bf16_kernel<HT, 1024, 8, 1, SM>), grid, dim3(512), 0, st, fp); break;

@@ -157,9 +157,11 @@ struct F1Params {
 constexpr int kF1TM = 4, kF1TN = 2, kF1Stages = 3;   // 256 tokens x 128 features per workgroup
 constexpr int kStageLd = 64 * kF1TN + 8;          // epilogue staging row stride (elements)
 // Launches of a few hundred rows (one user's candidates): the big tile gives the chip a few dozen workgroups, each
-// waiting a memory round trip per k-step with two stages in flight.  The small tile (64 tokens) with eight stages has
-// half of K in flight per workgroup and four times the workgroups.
-constexpr int kF1SmallTM = 1, kF1SmallStages = 8, kF1SmallMaxRows = 4095;
+// waiting a memory round trip per k-step with two stages in flight.  The small tile (64 tokens) with six stages has
+// more than a third of K = 512 in flight per workgroup and four times the workgroups; six stages are 72 KiB of LDS, so
+// that a compute unit holds two such workgroups and a launch of up to 512 of them (2048 rows at d = 512) runs in one
+// round (with eight stages, one workgroup per unit: 2048 rows 30 % slower, 512 rows the same).
+constexpr int kF1SmallTM = 1, kF1SmallStages = 6, kF1SmallMaxRows = 4095;
 
 template <typename H, int TM, int NSTAGE>
 __global__ __launch_bounds__(256, TM == 4 ? 2 : 1) void f1_gemm_bf16_kernel(F1Params p) {
@@ -329,7 +331,8 @@ __global__ __launch_bounds__(256, TM == 4 ? 2 : 1) void f1_gemm_bf16_kernel(F1Pa
 constexpr int kF1WsPF = 4;          // k-steps of token fragments in flight per wavefront
 constexpr int kF1WsMinRows = 4096;  // below this the tiled kernel's many small workgroups fill the chip better
 constexpr int kF1StreamMinRows = 16384;   // from here on a launch writes 64 MiB and more (at d = 512): streaming stores
-constexpr int kTailVr8MaxRows = 1024;  // layer tail: launches of at most this many rows use 8-row workgroups (d = 256, 512)
+constexpr int kTailVr8MaxRows = 1024;   // layer tail: launches of at most this many rows use 8-row workgroups (d = 256, 512),
+constexpr int kTailVr16MaxRows = 4096;  // of at most this many 16-row workgroups: still at most one workgroup per compute unit
 
 template <typename H, int D, bool FEATURE_MAJOR>
 __device__ __forceinline__ void f1_ws_mainloop(const uint16_t* __restrict__ tp0, const uint16_t* __restrict__ tp1,
@@ -830,9 +833,10 @@ __device__ __forceinline__ void l2_touch(const void* base, int lines, int share,
 // phase (memory) overlaps the other's product phase (L2 and matrix cores) when a launch has several
 // workgroups per unit: fewer k-steps and gate rows in flight, and the weight fragments and the
 // residual rows are requested after the gate instead of before it.
-// VR < 32: a workgroup takes only VR rows (a quarter-filled row block).  For launches of a few hundred
-// rows (one user per call): with 32 rows each they would occupy a few dozen compute units, each pulling
-// 16 KiB of split partial sums per row through its own memory path; with VR = 8 four times as many units share that.
+// VR < 32: a workgroup takes only VR rows (a partly filled row block).  For launches of a few hundred to a
+// few thousand rows (one user per call): with 32 rows each they would occupy a few dozen compute units, each
+// pulling 16 KiB of split partial sums per row through its own memory path; with VR = 8 or 16 four times or
+// twice as many units share that.
 template <typename H, int D, int NW, int RB, bool SM, int OCC = 1, int VR = 32>
 __global__ __launch_bounds__(NW * 64, OCC) void f2_ln_bf16_kernel(F2LnParams p) {
   constexpr int KS = D / 16;            // k-steps
@@ -846,7 +850,7 @@ __global__ __launch_bounds__(NW * 64, OCC) void f2_ln_bf16_kernel(F2LnParams p) 
   constexpr int FRAG = 512 + (RB == 1 ? 8 : 0);   // elements between token fragments
   __shared__ __attribute__((aligned(16))) uint16_t tok[RB * KS * FRAG];   // ROWS tokens x D, fragment order
   float* red = reinterpret_cast<float*>(tok);                             // reused after the product: [2][NW][ROWS]
-  static_assert(VR == 32 || (RB == 1 && OCC == 1 && VR == NW), "quarter-filled row blocks: one row per wavefront");
+  static_assert(VR == 32 || (RB == 1 && OCC == 1 && VR % NW == 0 && VR < 32), "partly filled row blocks: one or two rows per wavefront");
   constexpr int VROWS = VR < 32 ? VR : ROWS;   // rows this workgroup really has
   const int row0 = p.row_begin + blockIdx.x * VROWS;
   if (row0 >= p.row_end) return;
@@ -858,7 +862,7 @@ __global__ __launch_bounds__(NW * 64, OCC) void f2_ln_bf16_kernel(F2LnParams p) 
   constexpr int RPW = VROWS / NW, GMAX = OCC == 2 ? 2 : (RB * FB >= 4 ? (D >= 1024 ? 1 : 2) : (SM ? 2 : 4)), GROUP = RPW < GMAX ? RPW : GMAX;
   static_assert(RPW >= 1 && RPW % GROUP == 0, "rows per wavefront");
   // splits in flight per group of rows: what the registers allow (all 8 when a wavefront has one row)
-  constexpr int NB = VR < 32 ? (D >= 1024 ? 4 : 8) : (D >= 1024 ? 1 : 2);
+  constexpr int NB = VR < 32 ? (64 / (GROUP * (D / 64)) > 8 ? 8 : 64 / (GROUP * (D / 64))) : (D >= 1024 ? 1 : 2);
   GateRow<D / 64, SM> gr[GROUP];
   uint32_t gw[D / 128], ow[D / 128];
   GateLoad<D, SM, GROUP, NB> gl;
