@@ -133,11 +133,12 @@ static void carve(const relaygr_model_config& c, Plan& p) {
 }
 
 // Key-range splits wanted so that the attention launch fills the chip: workgroups = tiles * heads
-// * splits, aiming at two per compute unit, never more splits than a row tile has key tiles.
+// * splits, as many as give every compute unit at most two (one more split and some units get a third
+// workgroup, which the whole launch then waits for), never more splits than a row tile has key tiles.
 static int wanted_splits(int n_tiles, int n_heads, int min_key_tiles) {
   if (n_tiles <= 0) return 1;
   int wgs = n_tiles * n_heads;
-  int s = (512 + wgs - 1) / wgs;
+  int s = 512 / wgs;
   s = std::min(s, 8);
   s = std::min(s, std::max(1, min_key_tiles));
   return std::max(s, 1);
