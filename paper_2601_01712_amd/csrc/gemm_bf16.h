@@ -567,8 +567,10 @@ __global__ __launch_bounds__(512, 1) void f1_ws_bf16_kernel(F1Params p) {
 // streams its own slice of the packed W2 from L2 straight into registers (no wavefront shares
 // weights with another, so LDS would add nothing), PF k-steps ahead.  Feature-major product: a lane
 // ends up with one token and runs of 4 features, so the row statistics of the second LayerNorm are
-// a lane-local sum, one cross-half shuffle and one exchange between wavefronts through LDS.  Every
-// global load that does not depend on a result is issued before the first wait.
+// a lane-local sum, one cross-half shuffle and one exchange between wavefronts through LDS.  Global
+// loads that depend on no result go out as early as the registers allow: the rows' split sums, u and
+// the residual rows before the first wait, the weight fragments once the split buffers are free, the
+// second LayerNorm's gain and offset before the product.
 struct F2LnParams {
   // gate inputs
   const float* part;        // [nsplit][rows][D] unnormalised attention sums
