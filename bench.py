@@ -194,11 +194,14 @@ class Loaded:
                      [2.0 * (int(L.sum()) + int(S.sum())) * d * e + new_rows * d * (e + 4) + own_kv]
         # projection: 8 d^2 FLOP per row (k, v only for last-layer prefix rows: 4 d^2)
         f1_flops = [8.0 * d * d * (new_rows + miss_rows)] * (NL - 1) + [8.0 * d * d * new_rows + 4.0 * d * d * miss_rows]
-        # layer tail: 2 d^2 FLOP per row; o in (fp32), u in, residual row in and out (fp32), next layer's normalised row out
+        # layer tail: 2 d^2 FLOP per row; algorithmic bytes per row 4 d e (o, u and the residual row in, the residual row
+        # out, counted in the storage type).  As built the row costs d (4 + e + 8 + e): o and the residual stream are fp32
+        # and the next layer's normalised row goes out as well (split partial sums beyond the first are extra on top).
         tail_rows = [new_rows + miss_rows] * (NL - 1) + [new_rows]
         tail_flops = [2.0 * d * d * r for r in tail_rows]
-        tail_bytes = [r * d * (4 + e + 8 + e) for r in tail_rows]
-        return {"attn": (attn_flops, attn_bytes), "f1": (f1_flops, None), "f2": (tail_flops, tail_bytes)}
+        tail_bytes = [4.0 * r * d * e for r in tail_rows]
+        tail_built = [r * d * (4 + e + 8 + e) for r in tail_rows]
+        return {"attn": (attn_flops, attn_bytes), "f1": (f1_flops, None), "f2": (tail_flops, tail_bytes, tail_built)}
 
     def close(self):
         self.ctx.close()
@@ -243,11 +246,15 @@ def kernel_rooflines(w: Loaded, kernel_ms, sampled_calls, half16, config_name):
     f2_ms, f2_n = kernel_ms.get("f2", (0.0, 0))
     if f2_n and half16:
         avg_ms = f2_ms / f2_n
-        flops, nbytes = mean_over("f2", 0), mean_over("f2", 1)
+        flops, nbytes, built = mean_over("f2", 0), mean_over("f2", 1), mean_over("f2", 2)
         gbps = nbytes / (avg_ms * 1e-3) / 1e9
         out["tail"] = {"kernel": "f2_ln_bf16_kernel", "bound": "hbm", "achieved": round(gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                        "frac": round(gbps / PEAK_HBM_GBPS, 4), "avg_launch_ms": round(avg_ms, 4), "launches": f2_n,
-                       "algorithmic_bytes_per_launch": nbytes, "TFLOPs": round(flops / (avg_ms * 1e-3) / 1e12, 1)}
+                       "algorithmic_bytes_per_launch": nbytes, "bytes_as_built_per_launch": built,
+                       "as_built_GBps": round(built / (avg_ms * 1e-3) / 1e9, 1), "as_built_frac": round(built / (avg_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4),
+                       "note": "algorithmic = 4 d e bytes per row (o, u, residual in; residual out); as built o and the residual are fp32 and the "
+                               "next layer's normalised row is written too: d (4 + e + 8 + e) bytes per row before any split partial sums",
+                       "TFLOPs": round(flops / (avg_ms * 1e-3) / 1e12, 1)}
     return out
 
 
