@@ -40,9 +40,11 @@
  *     the fifth call in a row waits until the upload of the first has completed
  *     (microseconds once the stream has reached it).  Buffers passed to a call
  *     must stay valid and unmodified until that stream has passed the call's work.  A context is one model slot:
- *     it must not be used from two streams or two threads at once (its scratch
- *     buffer and staging area are shared by its calls); several contexts may share
- *     one pool, whose calls (and the expander's and trigger's) are thread-safe.
+ *     its calls share its scratch buffer and staging area, so they run one after the other on the GPU: a call
+ *     given another stream than the context's previous call is made to wait for that call (an event, no host
+ *     wait).  A context must not be used from two threads at once, and relaygr_rank_with_cache_static calls of
+ *     DIFFERENT contexts share the library's scratch and are not ordered against each other; several contexts
+ *     may share one pool, whose calls (and the expander's and trigger's) are thread-safe.
  *   - Every function returning int returns RELAYGR_OK or a negative code; the
  *     text of the last failure on the calling thread is relaygr_last_error().
  *   - dtype selects storage AND arithmetic: RELAYGR_DTYPE_FP32 keeps everything

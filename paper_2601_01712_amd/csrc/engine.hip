@@ -227,6 +227,11 @@ struct relaygr_ctx {
   int n_cus = 256;                      // compute units of the device the context was created on
   StagingSlot staging[kStagingSlots];   // pinned, allocated once at creation
   int next_slot = 0;
+  // A context's calls share its scratch, so they must not overlap on the GPU.  On one stream they cannot; a call
+  // on another stream than the one before it is made to wait for that call (an event recorded at each call's end).
+  hipEvent_t call_done = nullptr;
+  hipStream_t last_stream = nullptr;
+  bool has_call = false;
 };
 
 // Device memory one call lays its buffers out in (the part of a context's buffer behind the packed weights).
@@ -296,6 +301,10 @@ extern "C" int relaygr_ctx_create(const relaygr_model_config* cfg, const relaygr
       sl.bytes = want;
     }
   }
+  {
+    hipError_t e = hipEventCreateWithFlags(&c->call_done, hipEventDisableTiming);
+    if (e != hipSuccess) { relaygr_ctx_destroy(c); return fail(RELAYGR_EHIP, "ctx_create: event: %s", hipGetErrorString(e)); }
+  }
   {   // set-up for relaygr_rank_with_cache_static: this device's address of the library's own scratch
     char* unused = nullptr;
     int rc = static_scratch(&unused);
@@ -320,6 +329,7 @@ extern "C" void relaygr_ctx_destroy(relaygr_ctx* c) {
     if (s.done) { if (s.pending) (void)hipEventSynchronize(s.done); (void)hipEventDestroy(s.done); }
     if (s.host) (void)hipHostFree(s.host);
   }
+  if (c->call_done) (void)hipEventDestroy(c->call_done);
   delete c;
 }
 
@@ -986,9 +996,13 @@ static int run(relaygr_ctx* c, relaygr_kv_pool* pool, const relaygr_batch* b, Mo
   const size_t wp = wpack_bytes(c->cfg);
   const CallScratch own = {c->scratch + wp, c->scratch_bytes - wp};
   const CallScratch& cs = other ? *other : own;
-  if (c->cfg.dtype == RELAYGR_DTYPE_FP32) return run_typed<float>(c, kp, b, mode, scores, cs, st);
-  if (c->cfg.dtype == RELAYGR_DTYPE_FP16) return run_typed<__half>(c, kp, b, mode, scores, cs, st);
-  return run_typed<__hip_bfloat16>(c, kp, b, mode, scores, cs, st);
+  if (c->has_call && c->last_stream != st) HIP_TRY(hipStreamWaitEvent(st, c->call_done, 0));
+  if (c->cfg.dtype == RELAYGR_DTYPE_FP32) rc = run_typed<float>(c, kp, b, mode, scores, cs, st);
+  else if (c->cfg.dtype == RELAYGR_DTYPE_FP16) rc = run_typed<__half>(c, kp, b, mode, scores, cs, st);
+  else rc = run_typed<__hip_bfloat16>(c, kp, b, mode, scores, cs, st);
+  // whatever the call enqueued (all of it, or the part before a failure) is what the next call on another stream waits for
+  if (hipEventRecord(c->call_done, st) == hipSuccess) { c->last_stream = st; c->has_call = true; }
+  return rc;
 }
 
 extern "C" int relaygr_prefill_prefix(relaygr_ctx* ctx, relaygr_kv_pool* pool, const relaygr_batch* batch, void* hip_stream) {

@@ -62,3 +62,33 @@ def test_prefill_and_rank_on_two_streams_share_one_pool():
     finally:
         ctx2.close()
         h.close()
+
+
+def test_a_context_called_on_another_stream_waits_for_its_previous_call():
+    """A context's calls share its scratch.  Pre-inference is enqueued on one stream (held up behind other work),
+    ranking with the same context right away on another stream, with no synchronisation by the caller: the library
+    orders the second call behind the first with an event, and the scores are those of the synchronised run."""
+    cfg = synth.ModelConfig(2, 256, 4, "bf16")
+    L, S, M = [900, 300], [6, 0], [200, 70]
+    weights, batch = build_case(cfg, 151, L, S, M)
+    want = oracle_scores(cfg, weights, batch)
+    h = Harness(cfg, weights, batch, page_tokens=128)
+    try:
+        h.prefill([0, 1])
+        solo = h.rank_cached()
+        h.check(solo, want, "solo")
+        for u in (0, 1):
+            rg.relaygr_kv_pool_free(h.pool, int(h.handles[u]))
+        h.pool.slab.view(torch.int16)[:] = 0x7FC1      # what ranking would read if it ran ahead of the pre-inference
+        hs = [rg.relaygr_kv_pool_alloc(h.pool, int(batch["user_ids"][u]), L[u]) for u in (0, 1)]
+        both = h.sub_batch([0, 1]); both.set_handles(hs)
+        s_pre, s_rank = torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(s_pre):
+            torch.cuda._sleep(100_000_000)             # tens of milliseconds of other work ahead of the pre-inference
+        rg.relaygr_prefill_prefix(h.ctx, h.pool, both, stream=s_pre)
+        out = rg.relaygr_rank_with_cache(h.ctx, h.pool, both, stream=s_rank)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), solo)
+    finally:
+        h.close()
