@@ -42,9 +42,9 @@
  *     must stay valid and unmodified until that stream has passed the call's work.  A context is one model slot:
  *     its calls share its scratch buffer and staging area, so they run one after the other on the GPU: a call
  *     given another stream than the context's previous call is made to wait for that call (an event, no host
- *     wait).  A context must not be used from two threads at once, and relaygr_rank_with_cache_static calls of
- *     DIFFERENT contexts share the library's scratch and are not ordered against each other; several contexts
- *     may share one pool, whose calls (and the expander's and trigger's) are thread-safe.
+ *     wait; a stream under graph capture takes neither the wait nor the event).  A context must not be used
+ *     from two threads at once; several contexts may share one pool, whose calls (and the expander's and
+ *     trigger's) are thread-safe.
  *   - Every function returning int returns RELAYGR_OK or a negative code; the
  *     text of the last failure on the calling thread is relaygr_last_error().
  *   - dtype selects storage AND arithmetic: RELAYGR_DTYPE_FP32 keeps everything
@@ -229,10 +229,12 @@ int  relaygr_rank_with_cache(relaygr_ctx* ctx, relaygr_kv_pool* pool, const rela
  * weights at its head are read).  The call allocates and frees nothing, on the device or pinned on the host.
  * A call whose buffers do not fit (about 2000 suffix + candidate rows at d_model 512 with eight key-range
  * splits; fewer splits are tried first) is RELAYGR_ENOSPC and nothing is enqueued.  Every call on a GPU,
- * from any context, shares that GPU's buffer, which keeps the previous call's contents: calls that may
- * overlap on one GPU (two streams, two threads) race -- serialise them, or give the other stream
- * relaygr_rank_with_cache.  Nothing in the buffer needs clearing between calls: every kernel writes what a
- * later one reads. */
+ * from any context, shares that GPU's buffer, which keeps the previous call's contents: work on it that
+ * overlaps on one GPU races.  The library keeps its own calls apart (a call on another stream than the
+ * previous one on that GPU waits for it with an event; host threads enqueue one at a time), but not what it
+ * cannot see: a captured graph holding such a call must not be replayed while another call or replay on that
+ * GPU may still be running -- serialise those, or give the other stream relaygr_rank_with_cache.  Nothing in
+ * the buffer needs clearing between calls: every kernel writes what a later one reads. */
 #define RELAYGR_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
 int  relaygr_rank_with_cache_static(relaygr_ctx* ctx, relaygr_kv_pool* pool, const relaygr_batch* batch,
                                     float* scores_dev, void* hip_stream);

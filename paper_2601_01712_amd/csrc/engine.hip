@@ -179,9 +179,14 @@ static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 constexpr int kMaxDevices = 64;
 static std::mutex g_static_mu;
 static char* g_static_ptr[kMaxDevices] = {};
+// Calls on the shared array are kept apart on the GPU like a context's calls on its own scratch: each ends with
+// this event (created with the address, at set-up), and a call on another stream than the last one waits for it.
+static hipEvent_t g_static_done[kMaxDevices] = {};
+static hipStream_t g_static_last_stream[kMaxDevices] = {};
+static bool g_static_has_call[kMaxDevices] = {};
 
 // Device address of `scratch` on the current device, looked up on that device's first use.
-static int static_scratch(char** out) {
+static int static_scratch(char** out, int* dev_out = nullptr) {
   int dev = -1;
   HIP_TRY(hipGetDevice(&dev));
   if (dev < 0 || dev >= kMaxDevices) return fail(RELAYGR_EINVAL, "static scratch: device index %d out of range", dev);
@@ -190,9 +195,11 @@ static int static_scratch(char** out) {
     void* ptr = nullptr;
     HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
     if (!ptr) return fail(RELAYGR_EHIP, "static scratch: hipGetSymbolAddress returned a null address");
+    HIP_TRY(hipEventCreateWithFlags(&g_static_done[dev], hipEventDisableTiming));
     g_static_ptr[dev] = (char*)ptr;
   }
   *out = g_static_ptr[dev];
+  if (dev_out) *dev_out = dev;
   return RELAYGR_OK;
 }
 
@@ -975,6 +982,12 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
   return RELAYGR_OK;
 }
 
+static bool stream_is_capturing(hipStream_t st) {
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(st, &cap) != hipSuccess) { (void)hipGetLastError(); return false; }
+  return cap != hipStreamCaptureStatusNone;
+}
+
 static int run(relaygr_ctx* c, relaygr_kv_pool* pool, const relaygr_batch* b, Mode mode, float* scores, void* stream,
                const CallScratch* other = nullptr) {
   if (!c || !b) return fail(RELAYGR_EINVAL, "null context or batch");
@@ -996,12 +1009,15 @@ static int run(relaygr_ctx* c, relaygr_kv_pool* pool, const relaygr_batch* b, Mo
   const size_t wp = wpack_bytes(c->cfg);
   const CallScratch own = {c->scratch + wp, c->scratch_bytes - wp};
   const CallScratch& cs = other ? *other : own;
-  if (c->has_call && c->last_stream != st) HIP_TRY(hipStreamWaitEvent(st, c->call_done, 0));
+  // (a stream under graph capture takes neither the wait nor the event: the captured work is ordered by its graph,
+  // and against the context's other calls by whoever launches that graph)
+  const bool capturing = stream_is_capturing(st);
+  if (!capturing && c->has_call && c->last_stream != st) HIP_TRY(hipStreamWaitEvent(st, c->call_done, 0));
   if (c->cfg.dtype == RELAYGR_DTYPE_FP32) rc = run_typed<float>(c, kp, b, mode, scores, cs, st);
   else if (c->cfg.dtype == RELAYGR_DTYPE_FP16) rc = run_typed<__half>(c, kp, b, mode, scores, cs, st);
   else rc = run_typed<__hip_bfloat16>(c, kp, b, mode, scores, cs, st);
   // whatever the call enqueued (all of it, or the part before a failure) is what the next call on another stream waits for
-  if (hipEventRecord(c->call_done, st) == hipSuccess) { c->last_stream = st; c->has_call = true; }
+  if (!capturing && hipEventRecord(c->call_done, st) == hipSuccess) { c->last_stream = st; c->has_call = true; }
   return rc;
 }
 
@@ -1019,10 +1035,19 @@ extern "C" int relaygr_rank_with_cache(relaygr_ctx* ctx, relaygr_kv_pool* pool, 
 extern "C" int relaygr_rank_with_cache_static(relaygr_ctx* ctx, relaygr_kv_pool* pool, const relaygr_batch* batch, float* scores_dev,
                                               void* hip_stream) {
   char* base = nullptr;
-  int rc = static_scratch(&base);      // a table lookup after the first call on this device
+  int dev = 0;
+  int rc = static_scratch(&base, &dev);      // a table lookup after the first call on this device
   if (rc != RELAYGR_OK) return rc;
   const CallScratch cs = {base, kStaticScratchBytes};
-  rc = run(ctx, pool, batch, kRankCached, scores_dev, hip_stream, &cs);
+  {
+    // one caller at a time enqueues on the shared array, behind the call that used it last
+    std::lock_guard<std::mutex> lk(g_static_mu);
+    hipStream_t st = (hipStream_t)hip_stream;
+    const bool capturing = stream_is_capturing(st);
+    if (!capturing && g_static_has_call[dev] && g_static_last_stream[dev] != st) HIP_TRY(hipStreamWaitEvent(st, g_static_done[dev], 0));
+    rc = run(ctx, pool, batch, kRankCached, scores_dev, hip_stream, &cs);
+    if (!capturing && hipEventRecord(g_static_done[dev], st) == hipSuccess) { g_static_last_stream[dev] = st; g_static_has_call[dev] = true; }
+  }
   if (rc == RELAYGR_ENOSPC)
     return fail(rc, "rank_with_cache_static: the call does not fit the library's %zu-byte scratch (%s); use relaygr_rank_with_cache",
                 kStaticScratchBytes, std::string(relaygr_last_error()).c_str());

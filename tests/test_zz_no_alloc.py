@@ -81,3 +81,33 @@ def test_static_scratch_refuses_what_does_not_fit():
             h2.close()
     finally:
         h.close()
+
+
+def test_static_scratch_calls_on_two_streams_are_kept_apart():
+    """Two contexts use the library's scratch from two streams with no synchronisation between them, the first held
+    up behind other work on its stream: the second call is ordered behind the first by the library (an event), so
+    both give the scores of the existing entry point."""
+    cfg = synth.ModelConfig(2, 256, 4, "bf16")
+    weights, batch = build_case(cfg, 177, [700, 200], [3, 0], [260, 90])
+    h = Harness(cfg, weights, batch, 64)
+    ctx2 = rg.Context(cfg, weights, 2, 900, 353)
+    try:
+        h.prefill()
+        a = h.sub_batch([0]); a.set_handles([h.handles[0]])
+        b = h.sub_batch([1]); b.set_handles([h.handles[1]])
+        want_a = rg.relaygr_rank_with_cache(h.ctx, h.pool, a).cpu().numpy()
+        want_b = rg.relaygr_rank_with_cache(ctx2, h.pool, b).cpu().numpy()
+        out_a = torch.full((a.n_cands,), float("nan"), dtype=torch.float32, device="cuda:0")
+        out_b = torch.full((b.n_cands,), float("nan"), dtype=torch.float32, device="cuda:0")
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(s1):
+            torch.cuda._sleep(100_000_000)
+        rg.relaygr_rank_with_cache_static(h.ctx, h.pool, a, out_a, stream=s1)
+        rg.relaygr_rank_with_cache_static(ctx2, h.pool, b, out_b, stream=s2)
+        torch.cuda.synchronize()
+        assert np.array_equal(out_a.cpu().numpy(), want_a)
+        assert np.array_equal(out_b.cpu().numpy(), want_b)
+    finally:
+        ctx2.close()
+        h.close()
