@@ -42,9 +42,9 @@
  *     must stay valid and unmodified until that stream has passed the call's work.  A context is one model slot:
  *     its calls share its scratch buffer and staging area, so they run one after the other on the GPU: a call
  *     given another stream than the context's previous call is made to wait for that call (an event, no host
- *     wait; a stream under graph capture takes neither the wait nor the event).  A context must not be used
- *     from two threads at once; several contexts may share one pool, whose calls (and the expander's and
- *     trigger's) are thread-safe.
+ *     wait; a stream under graph capture takes neither the wait nor the event), and host threads calling
+ *     with one context enqueue one at a time (the profiling calls of a context are not synchronised with
+ *     them); several contexts may share one pool, whose calls (and the expander's and trigger's) are thread-safe.
  *   - Every function returning int returns RELAYGR_OK or a negative code; the
  *     text of the last failure on the calling thread is relaygr_last_error().
  *   - dtype selects storage AND arithmetic: RELAYGR_DTYPE_FP32 keeps everything

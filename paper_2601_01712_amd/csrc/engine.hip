@@ -239,6 +239,7 @@ struct relaygr_ctx {
   hipEvent_t call_done = nullptr;
   hipStream_t last_stream = nullptr;
   bool has_call = false;
+  std::mutex mu;                        // one host thread at a time plans and enqueues a call of this context
 };
 
 // Device memory one call lays its buffers out in (the part of a context's buffer behind the packed weights).
@@ -993,6 +994,7 @@ static int run(relaygr_ctx* c, relaygr_kv_pool* pool, const relaygr_batch* b, Mo
   if (!c || !b) return fail(RELAYGR_EINVAL, "null context or batch");
   if (b->n_users < 0) return fail(RELAYGR_EINVAL, "n_users < 0");
   if (b->n_users == 0) return RELAYGR_OK;
+  std::lock_guard<std::mutex> call_lock(c->mu);
   c->prof_this_call = (c->prof_calls++ % c->prof_every) == 0;
   int rc;
   if ((rc = check_offsets(b->prefix_off, b->n_users, "prefix")) != RELAYGR_OK) return rc;

@@ -92,3 +92,46 @@ def test_a_context_called_on_another_stream_waits_for_its_previous_call():
         assert np.array_equal(out.cpu().numpy(), solo)
     finally:
         h.close()
+
+
+def test_two_threads_may_call_with_one_context():
+    """Two host threads rank different users with the same context, each on its own stream: the library lets one
+    of them plan and enqueue at a time and orders the calls on the GPU, so every call gives the solo scores."""
+    import threading
+    cfg = synth.ModelConfig(2, 256, 4, "bf16")
+    L, S, M = [600, 260], [4, 0], [180, 75]
+    weights, batch = build_case(cfg, 153, L, S, M)
+    h = Harness(cfg, weights, batch, page_tokens=128)
+    try:
+        h.prefill([0, 1])
+        subs, solo = [], []
+        for u in (0, 1):
+            sb = h.sub_batch([u]); sb.set_handles([h.handles[u]])
+            subs.append(sb)
+            solo.append(rg.relaygr_rank_with_cache(h.ctx, h.pool, sb).cpu().numpy())
+        torch.cuda.synchronize()
+        outs = [[], []]
+        errors = []
+
+        def worker(i):
+            try:
+                st = torch.cuda.Stream()
+                for _ in range(12):
+                    outs[i].append(rg.relaygr_rank_with_cache(h.ctx, h.pool, subs[i], stream=st))
+                st.synchronize()
+            except Exception as exc:  # noqa: BLE001
+                errors.append(exc)
+
+        ts = [threading.Thread(target=worker, args=(i,)) for i in (0, 1)]
+        for t in ts:
+            t.start()
+        for t in ts:
+            t.join()
+        torch.cuda.synchronize()
+        assert not errors, errors
+        for i in (0, 1):
+            assert len(outs[i]) == 12
+            for o in outs[i]:
+                assert np.array_equal(o.cpu().numpy(), solo[i])
+    finally:
+        h.close()
