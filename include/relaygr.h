@@ -41,8 +41,9 @@
  *     (microseconds once the stream has reached it).  Buffers passed to a call
  *     must stay valid and unmodified until that stream has passed the call's work.  A context is one model slot:
  *     its calls share its scratch buffer and staging area, so they run one after the other on the GPU: a call
- *     given another stream than the context's previous call is made to wait for that call (an event, no host
- *     wait; a stream under graph capture takes neither the wait nor the event), and host threads calling
+ *     given another stream than the context's previous call is made to wait for the work that stream holds at
+ *     that moment (an event, no host wait; if that stream has been destroyed meanwhile, the device is
+ *     synchronised instead; a stream under graph capture is left alone), and host threads calling
  *     with one context enqueue one at a time (the profiling calls of a context are not synchronised with
  *     them); several contexts may share one pool, whose calls (and the expander's and trigger's) are thread-safe.
  *   - Every function returning int returns RELAYGR_OK or a negative code; the

@@ -179,8 +179,8 @@ static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 constexpr int kMaxDevices = 64;
 static std::mutex g_static_mu;
 static char* g_static_ptr[kMaxDevices] = {};
-// Calls on the shared array are kept apart on the GPU like a context's calls on its own scratch: each ends with
-// this event (created with the address, at set-up), and a call on another stream than the last one waits for it.
+// Calls on the shared array are kept apart on the GPU like a context's calls on its own scratch: a call on another
+// stream than the last one waits for what that stream holds (order_behind; the event is created with the address).
 static hipEvent_t g_static_done[kMaxDevices] = {};
 static hipStream_t g_static_last_stream[kMaxDevices] = {};
 static bool g_static_has_call[kMaxDevices] = {};
@@ -235,7 +235,7 @@ struct relaygr_ctx {
   StagingSlot staging[kStagingSlots];   // pinned, allocated once at creation
   int next_slot = 0;
   // A context's calls share its scratch, so they must not overlap on the GPU.  On one stream they cannot; a call
-  // on another stream than the one before it is made to wait for that call (an event recorded at each call's end).
+  // on another stream than the one before it is made to wait for what that stream holds (order_behind).
   hipEvent_t call_done = nullptr;
   hipStream_t last_stream = nullptr;
   bool has_call = false;
@@ -989,6 +989,18 @@ static bool stream_is_capturing(hipStream_t st) {
   return cap != hipStreamCaptureStatusNone;
 }
 
+// Makes stream `st` wait for everything enqueued so far on `prev` (the stream of the previous call on the same
+// scratch): the event is recorded on `prev` only now, when a call arrives on another stream, so that calls that
+// stay on one stream pay nothing.  If `prev` can no longer take an event (destroyed by its owner while its work may
+// still be running) the device is synchronised instead.
+static hipError_t order_behind(hipStream_t st, hipStream_t prev, hipEvent_t ev) {
+  hipError_t e = hipEventRecord(ev, prev);
+  if (e == hipSuccess) e = hipStreamWaitEvent(st, ev, 0);
+  if (e == hipSuccess) return e;
+  (void)hipGetLastError();
+  return hipDeviceSynchronize();
+}
+
 static int run(relaygr_ctx* c, relaygr_kv_pool* pool, const relaygr_batch* b, Mode mode, float* scores, void* stream,
                const CallScratch* other = nullptr) {
   if (!c || !b) return fail(RELAYGR_EINVAL, "null context or batch");
@@ -1014,12 +1026,11 @@ static int run(relaygr_ctx* c, relaygr_kv_pool* pool, const relaygr_batch* b, Mo
   // (a stream under graph capture takes neither the wait nor the event: the captured work is ordered by its graph,
   // and against the context's other calls by whoever launches that graph)
   const bool capturing = stream_is_capturing(st);
-  if (!capturing && c->has_call && c->last_stream != st) HIP_TRY(hipStreamWaitEvent(st, c->call_done, 0));
+  if (!capturing && c->has_call && c->last_stream != st) HIP_TRY(order_behind(st, c->last_stream, c->call_done));
   if (c->cfg.dtype == RELAYGR_DTYPE_FP32) rc = run_typed<float>(c, kp, b, mode, scores, cs, st);
   else if (c->cfg.dtype == RELAYGR_DTYPE_FP16) rc = run_typed<__half>(c, kp, b, mode, scores, cs, st);
   else rc = run_typed<__hip_bfloat16>(c, kp, b, mode, scores, cs, st);
-  // whatever the call enqueued (all of it, or the part before a failure) is what the next call on another stream waits for
-  if (!capturing && hipEventRecord(c->call_done, st) == hipSuccess) { c->last_stream = st; c->has_call = true; }
+  if (!capturing) { c->last_stream = st; c->has_call = true; }
   return rc;
 }
 
@@ -1046,9 +1057,9 @@ extern "C" int relaygr_rank_with_cache_static(relaygr_ctx* ctx, relaygr_kv_pool*
     std::lock_guard<std::mutex> lk(g_static_mu);
     hipStream_t st = (hipStream_t)hip_stream;
     const bool capturing = stream_is_capturing(st);
-    if (!capturing && g_static_has_call[dev] && g_static_last_stream[dev] != st) HIP_TRY(hipStreamWaitEvent(st, g_static_done[dev], 0));
+    if (!capturing && g_static_has_call[dev] && g_static_last_stream[dev] != st) HIP_TRY(order_behind(st, g_static_last_stream[dev], g_static_done[dev]));
     rc = run(ctx, pool, batch, kRankCached, scores_dev, hip_stream, &cs);
-    if (!capturing && hipEventRecord(g_static_done[dev], st) == hipSuccess) { g_static_last_stream[dev] = st; g_static_has_call[dev] = true; }
+    if (!capturing) { g_static_last_stream[dev] = st; g_static_has_call[dev] = true; }
   }
   if (rc == RELAYGR_ENOSPC)
     return fail(rc, "rank_with_cache_static: the call does not fit the library's %zu-byte scratch (%s); use relaygr_rank_with_cache",
