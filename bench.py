@@ -21,6 +21,7 @@ import gc
 import json
 import os
 import sys
+import threading
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
@@ -507,6 +508,65 @@ def single_request_breakdown(torch, rg, synth, cfg, weights, shapes=((1024, 512)
     return out
 
 
+def single_request_concurrency(torch, rg, synth, cfg, weights, L=4096, M=512, slots=(1, 2, 4), calls=300):
+    """One user per request on several model slots at once (Section 3.2, "Concurrency inside a special instance"): k
+    contexts, each with its own stream, user and scores, rank on one shared pool; requests are issued round-robin
+    and each is timed with HIP events on its own stream.  A one-user call occupies a fraction of the chip, so
+    requests per second should grow with the slots while the per-request latency grows more slowly.  (The process
+    has four hardware queues; with the bench's current stream that bounds the slots at four.)"""
+    page = 256
+    kmax = max(slots)
+    ctxs = [rg.Context(cfg, weights, 1, L, M) for _ in range(kmax)]
+    pool = rg.KvPool(ctxs[0].cfg, cfg.dtype, kmax * rg.relaygr_kv_pool_bytes_for(ctxs[0].cfg, L, page), page)
+    streams = [torch.cuda.Stream() for _ in range(kmax)]
+    dbs, scs, solo = [], [], []
+    for i in range(kmax):
+        wl = synth.Workload("slot", cfg, seed=950 + i, n_users=1, prefix_len=L, n_cands=M, n_suffix=0)
+        b = synth.make_batch(wl, 0)
+        db = rg.Batch(b, cfg.dtype)
+        db.set_handles([rg.relaygr_kv_pool_alloc(pool, 5000 + i, L)])   # one user per slot
+        rg.relaygr_prefill_prefix(ctxs[i], pool, db)
+        sc = torch.empty(M, dtype=torch.float32, device="cuda:0")
+        rg.relaygr_rank_with_cache(ctxs[i], pool, db, sc)
+        torch.cuda.synchronize()
+        dbs.append(db); scs.append(sc); solo.append(sc.cpu().numpy().copy())
+    ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
+    out = []
+    for k in slots:
+        for i in range(k):   # warm-up on the slot's own stream
+            for _ in range(5):
+                rg.relaygr_rank_with_cache(ctxs[i], pool, dbs[i], scs[i], stream=streams[i])
+        torch.cuda.synchronize()
+        evs = [[] for _ in range(k)]
+
+        def slot_thread(i):   # one host thread per slot, as a serving process would have (the C calls release the GIL)
+            for _ in range(calls // k):
+                a, b2 = ev(), ev()
+                a.record(streams[i])
+                rg.relaygr_rank_with_cache(ctxs[i], pool, dbs[i], scs[i], stream=streams[i])
+                b2.record(streams[i])
+                evs[i].append((a, b2))
+            streams[i].synchronize()
+
+        ts = [threading.Thread(target=slot_thread, args=(i,)) for i in range(k)]
+        t0 = time.perf_counter()
+        for t in ts:
+            t.start()
+        for t in ts:
+            t.join()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        lat = [a.elapsed_time(b2) for per in evs for a, b2 in per]
+        same = all(bool(np.array_equal(scs[i].cpu().numpy(), solo[i])) for i in range(k))
+        done = (calls // k) * k
+        out.append({"slots": k, "host_threads": k, "requests_per_s": round(done / wall, 1), "candidates_per_s": round(done * M / wall, 1),
+                    "request_latency_ms": lat_summary(lat), "scores_identical_to_solo_run": same})
+    for c in ctxs:
+        c.close()
+    pool.close()
+    return {"prefix": L, "candidates": M, "calls": calls, "points": out}
+
+
 def cpu_oracle_sample(w: Loaded, cached_scores, budget_s=10.0):
     """The float64 oracle on a bounded sample: whole users of the workload (median length first), full recompute,
     until about ten seconds of CPU work are done; the GPU's scores for those users are compared in passing."""
@@ -675,6 +735,8 @@ def main() -> int:
 
     if half16 and not args.no_single:
         out["single_request_latency"] = single_request_breakdown(torch, rg, synth, cfg, weights)
+        torch.cuda.empty_cache()
+        out["single_request_concurrency"] = single_request_concurrency(torch, rg, synth, cfg, weights)
         torch.cuda.empty_cache()
     if half16 and not args.no_sweep:
         out["attention_small_m_sweep"] = small_m_sweep(torch, rg, synth)
