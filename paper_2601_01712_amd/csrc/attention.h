@@ -43,6 +43,7 @@ struct AttnParams {
   const void* knew;   // [new rows][d]
   const void* vnew;
   int n_prows;        // rows before the first new row
+  int gs;             // MFMA kernel: key splits taken by the wavefront groups of one workgroup and added in LDS (1 or 2)
 };
 
 // Key-tile schedule of one work item, shared by both kernels.
@@ -306,14 +307,20 @@ __device__ __forceinline__ void softmax_track(const f32x16_t (&s)[NQ], const int
   }
 }
 
-template <typename H, int DH, int NQ, int NW, bool SOFTMAX>
-__global__ __launch_bounds__(NW * 64, (DH >= 128) ? 1 : 512 / (NW * 64)) void attn_bf16_kernel(AttnParams p) {   // DH = 128: the 96 KiB tile ring admits one workgroup per compute unit
+// GS = 2 (SiLU form): the workgroup is two groups of NW wavefronts over the SAME rows; each group takes one of two
+// consecutive key splits with a tile ring of its own, and at the end the second group's sums go through LDS to the
+// first, which adds them (first + second, a fixed order) and writes one partial sum: two key splits cost the layer
+// tail the HBM traffic of one.  Both groups pass the same barriers; a group with fewer tiles pads with empty ones.
+template <typename H, int DH, int NQ, int NW, bool SOFTMAX, int GS = 1>
+__global__ __launch_bounds__(NW * GS * 64, (DH >= 128 || GS > 1) ? 1 : 512 / (NW * 64)) void attn_bf16_kernel(AttnParams p) {   // DH = 128: the 96 KiB tile ring admits one workgroup per compute unit
   constexpr int KS = DH / 16;              // k-steps of the first product
   constexpr int DB = DH / 32;              // 32-feature blocks of the output
   constexpr int TILE = 2 * kTile * DH;     // elements of one K tile + one V tile
   constexpr int CHUNKS = TILE / 8 / (NW * 64);   // 16-byte chunks each thread moves per tile
   static_assert(CHUNKS >= 1, "a tile is at least one 16-byte chunk per thread");
-  __shared__ __attribute__((aligned(16))) uint16_t bufs[3][TILE];
+  static_assert(GS == 1 || (GS == 2 && !SOFTMAX), "groups: one, or two in the SiLU form");
+  static_assert(GS * 3 * TILE * 2 >= (GS - 1) * NW * 64 * DB * NQ * 16 * 4, "the second group's sums fit the rings' LDS");
+  __shared__ __attribute__((aligned(16))) uint16_t bufs_all[GS][3][TILE];
 
   // Work items that stream the same K/V (row tiles of one user, same head and split) get
   // consecutive logical ids, and each of the 8 XCDs (own L2 each; workgroups are dealt to them
@@ -323,11 +330,15 @@ __global__ __launch_bounds__(NW * 64, (DH >= 128) ? 1 : 512 / (NW * 64)) void at
   const int logical = xcd_remap(blockIdx.x, total);
   if (logical >= total) return;
   const int tile_i = logical % p.n_tiles, hs = logical / p.n_tiles;
-  const int head = hs % p.n_heads, split = hs / p.n_heads;
+  const int head = hs % p.n_heads, split_ext = hs / p.n_heads;
   const AttnTile at = p.tiles[tile_i];
   const UserDesc ud = p.users[at.user];
-  const TileRange tr = tile_range(at, ud, split, p.nsplit);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int grp = GS == 1 ? 0 : __builtin_amdgcn_readfirstlane((tid >> 6) / NW);    // wavefront group (a scalar: loop counts below depend on it)
+  const int wave = (tid >> 6) - grp * NW;           // wavefront inside its group: its rows, its share of a tile
+  const int split = split_ext * GS + grp, nsplit = p.nsplit * GS;   // this group's key split of all
+  const TileRange tr = tile_range(at, ud, split, nsplit);
+  uint16_t (*bufs)[TILE] = bufs_all[grp];
   const int l32 = lane & 31, g = lane >> 5;
 
   // this lane's rows: block qb covers rows wave*32*NQ + qb*32 + l32 of the work item
@@ -369,7 +380,7 @@ __global__ __launch_bounds__(NW * 64, (DH >= 128) ? 1 : 512 / (NW * 64)) void at
 #pragma unroll
   for (int qb = 0; qb < NQ; ++qb) {
     const int lr = wave * 32 * NQ + qb * 32 + l32;
-    cand[qb] = own_key && (qb % p.nsplit) == split && lr < at.nrows && at.pos0 + lr >= ud.S;   // new rows: suffix rows, then candidates
+    cand[qb] = own_key && (qb % nsplit) == split && lr < at.nrows && at.pos0 + lr >= ud.S;   // new rows: suffix rows, then candidates
     if (cand[qb]) {
       const size_t nb = (size_t)(at.row0 + lr - p.n_prows) * p.d + head * DH;
       const uint16_t* kn = reinterpret_cast<const uint16_t*>(p.knew) + nb;
@@ -431,6 +442,11 @@ __global__ __launch_bounds__(NW * 64, (DH >= 128) ? 1 : 512 / (NW * 64)) void at
   // a wavefront whose rows all lie beyond the work item's last row only helps move tiles
   const bool wave_active = wave * 32 * NQ < at.nrows;
   const int nt = tr.t1 - tr.t0;
+  int nt_all = nt;                    // barriers every wavefront of the workgroup passes in the tile loop
+  if constexpr (GS == 2) {
+    const TileRange tro = tile_range(at, ud, split ^ 1, nsplit);
+    nt_all = max(nt, tro.t1 - tro.t0);
+  }
   if (nt == 0) start_from_own_key();
   if (nt > 0) {
     issue_tile(tr.t0, 0);
@@ -504,6 +520,31 @@ __global__ __launch_bounds__(NW * 64, (DH >= 128) ? 1 : 512 / (NW * 64)) void at
     attn_pv_half<H, DH, NQ>(vprev, pk_b, oacc);                   // the last half's second product
   }
 
+  if constexpr (GS == 2) {
+    // A group passed nt barriers above (none if it had no tiles); both groups pass nt_all, then two more around the
+    // hand-over of the second group's sums.  Nothing below returns before the last of them.
+    for (int e = nt; e < nt_all; ++e) __syncthreads();
+    __syncthreads();                                  // both groups are done with their tile rings
+    float* xch = reinterpret_cast<float*>(&bufs_all[0][0][0]);
+    const int slot = wave * 64 + lane;                // lane of the first group that holds the same rows and features
+    if (grp == 1) {
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int qb = 0; qb < NQ; ++qb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) xch[((db * NQ + qb) * 16 + e) * (NW * 64) + slot] = oacc[db][qb][e];
+    }
+    __syncthreads();
+    if (grp == 1) return;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int qb = 0; qb < NQ; ++qb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) oacc[db][qb][e] += xch[((db * NQ + qb) * 16 + e) * (NW * 64) + slot];
+  }
+
   // element e of oacc[db][qb]: feature db*32 + 8*(e/4) + 4*g + e%4, row l32 of block qb
   const float kLn2 = SOFTMAX ? 1.0f : 0.69314718055994531f;
   if constexpr (SOFTMAX) {   // a row's sum is spread over its two lanes
@@ -516,11 +557,11 @@ __global__ __launch_bounds__(NW * 64, (DH >= 128) ? 1 : 512 / (NW * 64)) void at
     if (lr >= at.nrows) continue;
     if constexpr (SOFTMAX) {
       if (g == 0) {
-        float* mlp = p.ml + split * p.ml_stride + ((size_t)(at.row0 + lr) * p.n_heads + head) * 2;
+        float* mlp = p.ml + split_ext * p.ml_stride + ((size_t)(at.row0 + lr) * p.n_heads + head) * 2;
         *reinterpret_cast<float2*>(mlp) = make_float2(mref[qb], lsum[qb]);
       }
     }
-    float* dst = p.part + split * p.split_stride + (size_t)(at.row0 + lr) * p.d + head * DH;
+    float* dst = p.part + split_ext * p.split_stride + (size_t)(at.row0 + lr) * p.d + head * DH;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll

@@ -88,6 +88,7 @@ struct Plan {
   int64_t sfx_tiles = 0, kvs_tiles = 0;   // suffix tiles / recomputed-prefix tiles held in scratch
   int n_tiles_new = 0, n_tiles_prefix = 0;
   int nsplit = 1;
+  int gs = 1;           // key splits added inside an attention workgroup (AttnParams::gs)
   // byte offsets into scratch
   size_t off_x, off_xh, off_u, off_q, off_knew, off_vnew, off_sfx, off_kvs, off_part, off_ml, off_rows, off_blob;
   size_t blob_bytes = 0;
@@ -540,7 +541,7 @@ template <> struct GemmLaunch<__half> {
 };
 
 template <typename T>
-static int launch_attention(const relaygr_model_config& cfg, const AttnParams& ap, int n_tiles, int nq, bool softmax, hipStream_t st);
+static int launch_attention(const relaygr_model_config& cfg, const AttnParams& ap, int n_tiles, int nq, bool softmax, hipStream_t st);   // ap.gs: groups per workgroup
 
 template <bool SM>
 static int launch_attention_f32(const relaygr_model_config& cfg, const AttnParams& ap, int n_tiles, hipStream_t st) {
@@ -566,7 +567,11 @@ static int launch_attention16(const relaygr_model_config& cfg, const AttnParams&
   switch (cfg.d_model / cfg.n_heads) {
     case 32: hipLaunchKernelGGL((attn_bf16_kernel<H, 32, 1, 4, SM>), grid, dim3(256), 0, st, ap); break;
     case 64:
-      if (nq == 2) hipLaunchKernelGGL((attn_bf16_kernel<H, 64, 2, 4, SM>), grid, dim3(256), 0, st, ap);
+      if (nq == 2 && ap.gs == 2) {
+        if constexpr (!SM) hipLaunchKernelGGL((attn_bf16_kernel<H, 64, 2, 4, false, 2>), grid, dim3(512), 0, st, ap);
+        else return fail(RELAYGR_EINVAL, "attention: groups per workgroup are for the SiLU form");
+      }
+      else if (nq == 2) hipLaunchKernelGGL((attn_bf16_kernel<H, 64, 2, 4, SM>), grid, dim3(256), 0, st, ap);
       else hipLaunchKernelGGL((attn_bf16_kernel<H, 64, 1, 4, SM>), grid, dim3(256), 0, st, ap);
       break;
     case 128:
@@ -721,6 +726,15 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
 
   // -- scratch
   p.nsplit = wanted_splits(n_tiles_all, H, min_key_tiles);
+  // 256-row items at d_head 64, SiLU form: two of the key splits go to the two wavefront groups of one workgroup,
+  // which add their sums in LDS -- half the partial sums for the layer tail to read -- where that still gives
+  // every compute unit a workgroup
+  p.gs = 1;
+  if (bf16 && c->attn_form == RELAYGR_ATTN_SILU && dh == 64 && nq == 2 && p.nsplit % 2 == 0 &&
+      (int64_t)n_tiles_all * H * (p.nsplit / 2) >= c->n_cus) {
+    p.gs = 2;
+    p.nsplit /= 2;
+  }
   carve(cfg, p);
   while (p.total > cs.bytes && p.nsplit > 1) { p.nsplit -= 1; carve(cfg, p); }
   if (p.total > cs.bytes)
@@ -873,7 +887,7 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
     AttnParams ap;
     ap.tiles = d_tiles; ap.users = d_users; ap.rt = rt; ap.q = qbuf; ap.sfx = sfx; ap.part = part;
     ap.split_stride = (size_t)R * d; ap.nsplit = p.nsplit; ap.d = d; ap.n_heads = H; ap.layer = l; ap.score_mul = score_mul;
-    ap.ml = ml; ap.ml_stride = (size_t)R * H * 2;
+    ap.ml = ml; ap.ml_stride = (size_t)R * H * 2; ap.gs = p.gs;
     // 16-bit SiLU form: the attention kernel adds the candidates' own keys, so the layer tail does not read q, k, v again
     const bool self_in_attn = bf16 && !softmax;
     ap.knew = self_in_attn ? (const void*)knew : nullptr; ap.vnew = vnew; ap.n_prows = p.n_prows;

@@ -117,6 +117,19 @@ def test_one_user_calls_take_the_eight_row_layer_tail(dtype, attention, d, H, bo
     run_three_routes(cfg, 810 + d, [1100], [9], [333], boost=boost)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+def test_two_key_splits_added_inside_one_workgroup(dtype):
+    """32 work items of up to 256 rows x 8 heads of 64: ranking on the cache cuts the key range in two, and the two
+    halves go to the two wavefront groups of ONE workgroup, which add their sums in LDS.  Prefix lengths give odd
+    and even tile counts (the groups then walk different numbers of tiles), two users bring suffix tiles, the second
+    work item of every user ends inside a row block."""
+    L = [130, 200, 257, 320, 385, 450, 513, 577, 640, 705, 150, 330, 460, 590, 720, 260]
+    S = [0, 0, 70, 0, 0, 0, 0, 3, 0, 0, 0, 0, 0, 0, 0, 0]
+    M = [300, 300, 230, 300, 300, 300, 300, 297, 300, 300, 300, 300, 300, 300, 300, 300]
+    assert sum((s + m + 255) // 256 for s, m in zip(S, M)) * 8 == 256      # the shape that selects that kernel
+    run_three_routes(synth.ModelConfig(2, 512, 8, dtype), 611, L, S, M)
+
+
 # ------------------------------------------------------------------------------------ fp16
 @pytest.mark.parametrize("L,S,M", [
     ([1], [0], [1]), ([65, 300], [0, 70], [3, 129]), ([513, 0, 128], [64, 2, 0], [257, 9, 1]), ([1000], [17], [400]),
