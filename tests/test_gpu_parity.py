@@ -130,6 +130,13 @@ def test_two_key_splits_added_inside_one_workgroup(dtype):
     run_three_routes(synth.ModelConfig(2, 512, 8, dtype), 611, L, S, M)
 
 
+def test_four_key_splits_on_128_row_items_pair_up_inside_workgroups():
+    """One user with 2048 candidates: 16 work items of 128 rows x 8 heads and four key splits, which the two
+    wavefront groups of a workgroup take in pairs (two partial sums reach the layer tail instead of four); 18
+    key tiles over four splits leave the last group with fewer tiles than its partner."""
+    run_three_routes(synth.ModelConfig(2, 512, 8, "bf16"), 613, [1100], [0], [2048])
+
+
 # ------------------------------------------------------------------------------------ fp16
 @pytest.mark.parametrize("L,S,M", [
     ([1], [0], [1]), ([65, 300], [0, 70], [3, 129]), ([513, 0, 128], [64, 2, 0], [257, 9, 1]), ([1000], [17], [400]),
