@@ -38,7 +38,7 @@ LATENCY_CALLS = 500          # rank calls behind every p50 / p99 (whatever --ste
 # HBM bytes per attention launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs), scaled by
 # what the same counters read for a plain 1 GiB copy (x2.0 and x1.0); profiles/bench_C3_kernels.md.  Only the
 # C3 rank launch has been counted; other workloads report null.
-MEASURED_ATTN_TRAFFIC_BYTES = {"C3": (82149 * 2 + 32768) * 1024}
+MEASURED_ATTN_TRAFFIC_BYTES = {"C3": (78080 * 2 + 16384) * 1024}
 
 WORKLOAD_TEXT = {
     "C1": "C1: fp32, 2 layers, d=64, 2 heads; 1 user, prefix 256, 16 candidates",
