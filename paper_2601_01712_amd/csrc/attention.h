@@ -38,8 +38,8 @@ struct AttnParams {
   int d, n_heads, layer;
   float score_mul;    // multiplies <q,k> before SiLU (alpha, or 1 if q is stored pre-scaled)
   // MFMA kernel, SiLU form: a candidate's own key (the diagonal of the candidate block: a per-row dot product, never an
-  // M x M tile) is added by the work item of key split 0, from the row-major k and v of the new rows; null: left to the
-  // layer-tail kernel
+  // M x M tile) is where the sums of one of the row's key splits start (row block qb: split qb mod nsplit), from the
+  // row-major k and v of the new rows; null: left to the layer-tail kernel
   const void* knew;   // [new rows][d]
   const void* vnew;
   int n_prows;        // rows before the first new row
