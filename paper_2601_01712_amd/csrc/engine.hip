@@ -788,8 +788,7 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
 
   {
   ProfScope ps(c, RELAYGR_K_SETUP, st);
-  hipLaunchKernelGGL(build_rows_kernel, dim3((p.n_rows + 255) / 256), dim3(256), 0, st, d_users, d_ps, d_ns, n, p.n_prows, p.n_rows, rt);
-  LAUNCH_CHECK("build_rows");
+  // (the row tables are built by the first layer's input LayerNorm kernel, which visits every row anyway)
   if (p.n_prows && std::is_same<T, float>::value) {   // the bf16 f1 epilogue zero-fills the ragged tail itself
     hipLaunchKernelGGL((zero_kv_tail_kernel<T>), dim3(n), dim3(256), 0, st, d_users, n, NL, H, dh);
     LAUNCH_CHECK("zero_kv_tail");
@@ -828,12 +827,13 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
       dim3 grid((R + kRowsPerBlock - 1) / kRowsPerBlock);
       bool ok = dispatch_e(d, [&](auto e) {
         constexpr int E = decltype(e)::value;
+        const RowBuild rb = {d_users, d_ps, d_ns, n, p.n_prows};
         if (l == 0)
           hipLaunchKernelGGL((ln_in_kernel<T, E, true, kPanel>), grid, dim3(256), 0, st, x, xh, (const T*)lw.ln_in_g, (const T*)lw.ln_in_b,
-                             emb_p, emb_s, emb_c, rt, 0, R, cfg.ln_eps);
+                             emb_p, emb_s, emb_c, rt, rb, 0, R, cfg.ln_eps);
         else if constexpr (!fuse_ln)
           hipLaunchKernelGGL((ln_in_kernel<T, E, false, kPanel>), grid, dim3(256), 0, st, x, xh, (const T*)lw.ln_in_g, (const T*)lw.ln_in_b,
-                             emb_p, emb_s, emb_c, rt, 0, R, cfg.ln_eps);
+                             emb_p, emb_s, emb_c, rt, rb, 0, R, cfg.ln_eps);
       });
       if (!ok) return fail(RELAYGR_EINVAL, "unsupported d_model");
       LAUNCH_CHECK("ln_in");

@@ -10,30 +10,37 @@ namespace relaygr {
 constexpr int kRowsPerBlock = 4;  // wavefronts (rows) per 256-thread workgroup
 
 // ---- row tables ------------------------------------------------------------------------------
-// pstart / nstart: n_users + 1 row boundaries of the prefix rows and of the new rows.
-__global__ void build_rows_kernel(const UserDesc* __restrict__ users, const int32_t* __restrict__ pstart,
-                                  const int32_t* __restrict__ nstart, int n_users, int n_prows, int n_rows,
-                                  RowTables rt) {
-  int r = blockIdx.x * blockDim.x + threadIdx.x;
-  if (r >= n_rows) return;
-  const int32_t* start = (r < n_prows) ? pstart : nstart;
-  int lo = 0, hi = n_users;  // find u with start[u] <= r < start[u+1]
+// pstart / nstart: n_users + 1 row boundaries of the prefix rows and of the new rows.  The entry of row r:
+// its user, kind, index inside the user's prefix / suffix / candidates, number of keys it sees in the
+// [prefix | suffix] sequence, and its row in the caller's embedding array.
+struct RowBuild {
+  const UserDesc* users;
+  const int32_t* pstart;
+  const int32_t* nstart;
+  int n_users, n_prows;
+};
+struct RowEntry { int user, kind, idx, lim, src; };
+
+__device__ __forceinline__ RowEntry row_entry(const RowBuild& rb, int r) {
+  const int32_t* start = (r < rb.n_prows) ? rb.pstart : rb.nstart;
+  int lo = 0, hi = rb.n_users;  // find u with start[u] <= r < start[u+1]
   while (hi - lo > 1) {
     int mid = (lo + hi) >> 1;
     if (start[mid] <= r) lo = mid; else hi = mid;
   }
-  const UserDesc& ud = users[lo];
-  int kind, idx, lim, src;
-  if (r < n_prows) {
-    idx = r - start[lo];
-    if (idx < ud.L) { kind = kRowPrefix; lim = idx + 1; src = ud.prefix_src0 + idx; }
-    else            { kind = kRowPad; lim = 0; src = 0; }
+  const UserDesc& ud = rb.users[lo];
+  RowEntry e;
+  e.user = lo;
+  if (r < rb.n_prows) {
+    e.idx = r - start[lo];
+    if (e.idx < ud.L) { e.kind = kRowPrefix; e.lim = e.idx + 1; e.src = ud.prefix_src0 + e.idx; }
+    else              { e.kind = kRowPad; e.lim = 0; e.src = 0; }
   } else {
     int t = r - start[lo];
-    if (t < ud.S) { kind = kRowSuffix; idx = t; lim = ud.L + t + 1; src = ud.suffix_src0 + t; }
-    else          { kind = kRowCand; idx = t - ud.S; lim = ud.L + ud.S; src = ud.cand_src0 + idx; }
+    if (t < ud.S) { e.kind = kRowSuffix; e.idx = t; e.lim = ud.L + t + 1; e.src = ud.suffix_src0 + t; }
+    else          { e.kind = kRowCand; e.idx = t - ud.S; e.lim = ud.L + ud.S; e.src = ud.cand_src0 + e.idx; }
   }
-  rt.user[r] = lo; rt.kind[r] = kind; rt.idx[r] = idx; rt.lim[r] = lim; rt.src[r] = src;
+  return e;
 }
 
 // ---- LayerNorm helpers -----------------------------------------------------------------------
@@ -69,20 +76,28 @@ __device__ __forceinline__ void store_row_run(T* __restrict__ out, int r, int la
 }
 
 // Input LayerNorm of a layer (step 1 of a layer): xh = LN(x; g, b) in the storage type.
-// With GATHER (first layer) the row is first fetched from its embedding array and also written to
-// the fp32 residual stream x.
+// With GATHER (first layer of a call) the wavefront first works out its row's table entry and writes it
+// for the kernels that follow (the call's row tables are built here, not by a launch of their own), then
+// fetches the row from its embedding array and also writes it to the fp32 residual stream x.
 template <typename T, int E, bool GATHER, bool PANEL>
 __global__ __launch_bounds__(256) void ln_in_kernel(float* __restrict__ x, T* __restrict__ xh,
                                                     const T* __restrict__ gain, const T* __restrict__ offs,
                                                     const T* __restrict__ emb_prefix, const T* __restrict__ emb_suffix,
-                                                    const T* __restrict__ emb_cand, RowTables rt,
+                                                    const T* __restrict__ emb_cand, RowTables rt, RowBuild rb,
                                                     int row_begin, int row_end, float eps) {
   const int d = 64 * E;
   int r = row_begin + blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
   if (r >= row_end) return;
   int lane = threadIdx.x & 63;
   float v[E];
-  const int kind = rt.kind[r];
+  int kind, src = 0;
+  if (GATHER) {
+    const RowEntry e = row_entry(rb, r);
+    if (lane == 0) { rt.user[r] = e.user; rt.kind[r] = e.kind; rt.idx[r] = e.idx; rt.lim[r] = e.lim; rt.src[r] = e.src; }
+    kind = e.kind; src = e.src;
+  } else {
+    kind = rt.kind[r];
+  }
   if (kind == kRowPad) {   // keep filler rows finite
 #pragma unroll
     for (int i = 0; i < E; ++i) v[i] = 0.f;
@@ -90,7 +105,7 @@ __global__ __launch_bounds__(256) void ln_in_kernel(float* __restrict__ x, T* __
     return;
   }
   if (GATHER) {
-    const T* e = (kind == kRowPrefix ? emb_prefix : kind == kRowSuffix ? emb_suffix : emb_cand) + (size_t)rt.src[r] * d + lane * E;
+    const T* e = (kind == kRowPrefix ? emb_prefix : kind == kRowSuffix ? emb_suffix : emb_cand) + (size_t)src * d + lane * E;
 #pragma unroll
     for (int i = 0; i < E; ++i) { v[i] = Elem<T>::ld(e + i); x[(size_t)r * d + lane * E + i] = v[i]; }
   } else {
