@@ -307,10 +307,10 @@ __device__ __forceinline__ void softmax_track(const f32x16_t (&s)[NQ], const int
   }
 }
 
-// GS = 2 (SiLU form): the workgroup is two groups of NW wavefronts over the SAME rows; each group takes one of two
+// GS = 2: the workgroup is two groups of NW wavefronts over the SAME rows; each group takes one of two
 // consecutive key splits with a tile ring of its own, and at the end the second group's sums go through LDS to the
-// first, which adds them (first + second, a fixed order) and writes one partial sum: two key splits cost the layer
-// tail the HBM traffic of one.  Both groups pass the same barriers; a group with fewer tiles pads with empty ones.
+// first, which adds them (first + second, a fixed order; in the softmax form after bringing both to the larger of their
+// reference scores) and writes one partial sum: two key splits cost the layer tail the HBM traffic of one.  Both groups pass the same barriers; a group with fewer tiles pads with empty ones.
 template <typename H, int DH, int NQ, int NW, bool SOFTMAX, int GS = 1>
 __global__ __launch_bounds__(NW * GS * 64, (DH >= 128 || GS > 1) ? 1 : 512 / (NW * 64)) void attn_bf16_kernel(AttnParams p) {   // DH = 128: the 96 KiB tile ring admits one workgroup per compute unit
   constexpr int KS = DH / 16;              // k-steps of the first product
@@ -318,8 +318,8 @@ __global__ __launch_bounds__(NW * GS * 64, (DH >= 128 || GS > 1) ? 1 : 512 / (NW
   constexpr int TILE = 2 * kTile * DH;     // elements of one K tile + one V tile
   constexpr int CHUNKS = TILE / 8 / (NW * 64);   // 16-byte chunks each thread moves per tile
   static_assert(CHUNKS >= 1, "a tile is at least one 16-byte chunk per thread");
-  static_assert(GS == 1 || (GS == 2 && !SOFTMAX), "groups: one, or two in the SiLU form");
-  static_assert(GS * 3 * TILE * 2 >= (GS - 1) * NW * 64 * DB * NQ * 16 * 4, "the second group's sums fit the rings' LDS");
+  static_assert(GS == 1 || GS == 2, "groups: one or two");
+  static_assert(GS * 3 * TILE * 2 >= (GS - 1) * NW * 64 * (DB * NQ * 16 + 2 * NQ) * 4, "the second group's sums fit the rings' LDS");
   __shared__ __attribute__((aligned(16))) uint16_t bufs_all[GS][3][TILE];
 
   // Work items that stream the same K/V (row tiles of one user, same head and split) get
@@ -534,15 +534,40 @@ __global__ __launch_bounds__(NW * GS * 64, (DH >= 128 || GS > 1) ? 1 : 512 / (NW
         for (int qb = 0; qb < NQ; ++qb)
 #pragma unroll
           for (int e = 0; e < 16; ++e) xch[((db * NQ + qb) * 16 + e) * (NW * 64) + slot] = oacc[db][qb][e];
+      if constexpr (SOFTMAX) {
+#pragma unroll
+        for (int qb = 0; qb < NQ; ++qb) {
+          xch[(DB * NQ * 16 + 2 * qb) * (NW * 64) + slot] = mref[qb];
+          xch[(DB * NQ * 16 + 2 * qb + 1) * (NW * 64) + slot] = lsum[qb];
+        }
+      }
     }
     __syncthreads();
     if (grp == 1) return;
+    // softmax form: both groups' sums are brought to the larger of their two reference scores first
+    float c0[NQ], c1[NQ];
+#pragma unroll
+    for (int qb = 0; qb < NQ; ++qb) {
+      c0[qb] = 1.0f; c1[qb] = 1.0f;
+      if constexpr (SOFTMAX) {
+        const float m1 = xch[(DB * NQ * 16 + 2 * qb) * (NW * 64) + slot], l1 = xch[(DB * NQ * 16 + 2 * qb + 1) * (NW * 64) + slot];
+        const float M = fmaxf(mref[qb], m1);
+        c0[qb] = (mref[qb] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mref[qb] - M);
+        c1[qb] = (m1 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m1 - M);
+        lsum[qb] = lsum[qb] * c0[qb] + l1 * c1[qb];
+        mref[qb] = M;
+      }
+    }
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
       for (int qb = 0; qb < NQ; ++qb)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) oacc[db][qb][e] += xch[((db * NQ + qb) * 16 + e) * (NW * 64) + slot];
+        for (int e = 0; e < 16; ++e) {
+          const float x = xch[((db * NQ + qb) * 16 + e) * (NW * 64) + slot];
+          if constexpr (SOFTMAX) oacc[db][qb][e] = oacc[db][qb][e] * c0[qb] + x * c1[qb];
+          else oacc[db][qb][e] += x;
+        }
   }
 
   // element e of oacc[db][qb]: feature db*32 + 8*(e/4) + 4*g + e%4, row l32 of block qb

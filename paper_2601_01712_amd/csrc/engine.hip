@@ -567,14 +567,8 @@ static int launch_attention16(const relaygr_model_config& cfg, const AttnParams&
   switch (cfg.d_model / cfg.n_heads) {
     case 32: hipLaunchKernelGGL((attn_bf16_kernel<H, 32, 1, 4, SM>), grid, dim3(256), 0, st, ap); break;
     case 64:
-      if (nq == 2 && ap.gs == 2) {
-        if constexpr (!SM) hipLaunchKernelGGL((attn_bf16_kernel<H, 64, 2, 4, false, 2>), grid, dim3(512), 0, st, ap);
-        else return fail(RELAYGR_EINVAL, "attention: groups per workgroup are for the SiLU form");
-      }
-      else if (ap.gs == 2) {
-        if constexpr (!SM) hipLaunchKernelGGL((attn_bf16_kernel<H, 64, 1, 4, false, 2>), grid, dim3(512), 0, st, ap);
-        else return fail(RELAYGR_EINVAL, "attention: groups per workgroup are for the SiLU form");
-      }
+      if (nq == 2 && ap.gs == 2) hipLaunchKernelGGL((attn_bf16_kernel<H, 64, 2, 4, SM, 2>), grid, dim3(512), 0, st, ap);
+      else if (ap.gs == 2) hipLaunchKernelGGL((attn_bf16_kernel<H, 64, 1, 4, SM, 2>), grid, dim3(512), 0, st, ap);
       else if (nq == 2) hipLaunchKernelGGL((attn_bf16_kernel<H, 64, 2, 4, SM>), grid, dim3(256), 0, st, ap);
       else hipLaunchKernelGGL((attn_bf16_kernel<H, 64, 1, 4, SM>), grid, dim3(256), 0, st, ap);
       break;
@@ -730,11 +724,11 @@ static int run_typed(relaygr_ctx* c, KvPool* pool, const relaygr_batch* b, Mode 
 
   // -- scratch
   p.nsplit = wanted_splits(n_tiles_all, H, min_key_tiles);
-  // d_head 64, SiLU form: two of the key splits go to the two wavefront groups of one workgroup, which add their
+  // d_head 64: two of the key splits go to the two wavefront groups of one workgroup, which add their
   // sums in LDS -- half the partial sums for the layer tail to read -- where that still gives every compute unit a
   // workgroup (with fewer, e.g. one user with 512 candidates, the attention launch itself gets 25 % slower)
   p.gs = 1;
-  if (bf16 && c->attn_form == RELAYGR_ATTN_SILU && dh == 64 && p.nsplit % 2 == 0 &&
+  if (bf16 && dh == 64 && p.nsplit % 2 == 0 &&
       (int64_t)n_tiles_all * H * (p.nsplit / 2) >= c->n_cus) {
     p.gs = 2;
     p.nsplit /= 2;

@@ -117,24 +117,27 @@ def test_one_user_calls_take_the_eight_row_layer_tail(dtype, attention, d, H, bo
     run_three_routes(cfg, 810 + d, [1100], [9], [333], boost=boost)
 
 
+@pytest.mark.parametrize("attention", ["silu", "softmax"])
 @pytest.mark.parametrize("dtype", ["bf16", "fp16"])
-def test_two_key_splits_added_inside_one_workgroup(dtype):
+def test_two_key_splits_added_inside_one_workgroup(dtype, attention):
     """32 work items of up to 256 rows x 8 heads of 64: ranking on the cache cuts the key range in two, and the two
-    halves go to the two wavefront groups of ONE workgroup, which add their sums in LDS.  Prefix lengths give odd
+    halves go to the two wavefront groups of ONE workgroup, which add their sums in LDS (in the softmax form after
+    bringing them to a common reference score).  Prefix lengths give odd
     and even tile counts (the groups then walk different numbers of tiles), two users bring suffix tiles, the second
     work item of every user ends inside a row block."""
     L = [130, 200, 257, 320, 385, 450, 513, 577, 640, 705, 150, 330, 460, 590, 720, 260]
     S = [0, 0, 70, 0, 0, 0, 0, 3, 0, 0, 0, 0, 0, 0, 0, 0]
     M = [300, 300, 230, 300, 300, 300, 300, 297, 300, 300, 300, 300, 300, 300, 300, 300]
     assert sum((s + m + 255) // 256 for s, m in zip(S, M)) * 8 == 256      # the shape that selects that kernel
-    run_three_routes(synth.ModelConfig(2, 512, 8, dtype), 611, L, S, M)
+    run_three_routes(synth.ModelConfig(2, 512, 8, dtype, attention=attention), 611, L, S, M)
 
 
-def test_four_key_splits_on_128_row_items_pair_up_inside_workgroups():
+@pytest.mark.parametrize("attention", ["silu", "softmax"])
+def test_four_key_splits_on_128_row_items_pair_up_inside_workgroups(attention):
     """One user with 2048 candidates: 16 work items of 128 rows x 8 heads and four key splits, which the two
     wavefront groups of a workgroup take in pairs (two partial sums reach the layer tail instead of four); 18
     key tiles over four splits leave the last group with fewer tiles than its partner."""
-    run_three_routes(synth.ModelConfig(2, 512, 8, "bf16"), 613, [1100], [0], [2048])
+    run_three_routes(synth.ModelConfig(2, 512, 8, "bf16", attention=attention), 613, [1100], [0], [2048])
 
 
 # ------------------------------------------------------------------------------------ fp16
