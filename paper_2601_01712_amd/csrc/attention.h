@@ -310,7 +310,8 @@ __device__ __forceinline__ void softmax_track(const f32x16_t (&s)[NQ], const int
 // GS = 2: the workgroup is two groups of NW wavefronts over the SAME rows; each group takes one of two
 // consecutive key splits with a tile ring of its own, and at the end the second group's sums go through LDS to the
 // first, which adds them (first + second, a fixed order; in the softmax form after bringing both to the larger of their
-// reference scores) and writes one partial sum: two key splits cost the layer tail the HBM traffic of one.  Both groups pass the same barriers; a group with fewer tiles pads with empty ones.
+// reference scores) and writes one partial sum: two key splits cost the layer tail the HBM traffic of one.  Both
+// groups pass the same barriers; a group with fewer tiles pads with empty ones.
 template <typename H, int DH, int NQ, int NW, bool SOFTMAX, int GS = 1>
 __global__ __launch_bounds__(NW * GS * 64, (DH >= 128 || GS > 1) ? 1 : 512 / (NW * 64)) void attn_bf16_kernel(AttnParams p) {   // DH = 128: the 96 KiB tile ring admits one workgroup per compute unit
   constexpr int KS = DH / 16;              // k-steps of the first product
